@@ -1,0 +1,114 @@
+#!/usr/bin/env python3
+"""Benchmark of the template-planning hot path on one MI355X.
+
+A step = one whole oob_plan_templates call (set-up, level 1, every level S' >= 2, template
+extraction, coverage) on the GPT-175B-shaped workload (98 profile entries, templates for
+8..64 nodes x 8 GPUs, 128 microbatches) with the profile already resident in HBM.
+Prints ONE JSON line.  Metric: dynamic-program states per second (structural count of valid
+states, 3 724 666 per step for the headline workload) and wall-ms per full template set.
+"""
+import argparse
+import dataclasses
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# Arithmetic per candidate split (s, k, m) in the int64 formulation of Eq. 1-3: 4 adds, one
+# 64-bit compare with 3 selects, one 64x32 multiply, one (cost, index) compare-and-select;
+# about 9 int64-class operations = 30 32-bit lane operations.  The kernels need fewer (see
+# the design doc); the roofline figure is quoted on this algorithmic count.
+OPS_PER_CANDIDATE = 30
+PEAK_LANE_OPS = 256 * 64 * 2.4e9  # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T 32-bit lane-ops/s
+
+
+def cpu_baseline(inp):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    from oracle import capi
+
+    sample = dataclasses.replace(inp, n_max=min(inp.n_max, 16))
+    t0 = time.time()
+    o = capi.Oracle(sample)
+    dt = time.time() - t0
+    res = {"value": o.states / dt, "unit": "states/s", "cores": capi.lib().oob_oracle_threads(),
+           "kind": "oracle", "seconds": round(dt, 2), "candidates_per_s": o.candidates / dt,
+           "sample": f"same profile, templates for {sample.n_min}..{sample.n_max} nodes only: "
+                     f"{o.states} states, {o.candidates} candidates"}
+    o.close()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=4, help="workload 1-4 (default: headline 4)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build plans on ONE GPU (no collectives); run with --gpus 1. "
+              "The '8 GPUs' of the workload are the cluster being planned for.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import inputs
+    import paper_2309_08125_amd as P
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    inp = inputs.config(args.config)
+    planner = P.Planner(inp.L, inp.n_max, inp.gpus_per_node)
+    prof = P.DeviceProfile(inp)
+    out = planner.new_outputs(inp)
+    planner.level_timing(True)
+
+    for _ in range(args.warmup):
+        planner.enqueue(prof, out)
+    torch.cuda.synchronize()
+    level_ms = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        planner.enqueue(prof, out)
+        level_ms.append(planner.last_level_ms())  # HIP events around the level launches
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    res = out.to_host()
+    assert int(res["status"][0]) == 0, "device status"
+    states, cands = res["states"], res["candidates"]
+    Smax = P.oob_plan_max_stages(inp.L, inp.n_max, inp.gpus_per_node, inp.microbatches)
+    launches = max(1, Smax - 1)
+    lvl_ms = sum(level_ms) / len(level_ms)
+    achieved = cands * OPS_PER_CANDIDATE / (lvl_ms * 1e-3)
+    line = {
+        "metric": "DP states/sec (wall-ms per full template set in ms_per_step)",
+        "value": states * args.steps / elapsed,
+        "unit": "states/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64 (exact integers < 2^52; int64 in and out)",
+        "data": "synthetic",
+        "config": {"workload": f"config {args.config}: {inp.name}, L={inp.L} profile entries, "
+                               f"templates n={inp.n_min}..{inp.n_max} x {inp.gpus_per_node} GPUs, "
+                               f"N_b={inp.microbatches}, f={inp.f}",
+                   "states": states, "candidates": cands, "levels": Smax},
+        "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12,
+                     "unit": "T lane-op/s", "frac": achieved / PEAK_LANE_OPS, "traffic": None,
+                     "kernel": "level kernels S'>=2 (divide/combine, Eq. 1-3)",
+                     "ops_per_candidate": OPS_PER_CANDIDATE, "launches": launches,
+                     "avg_launch_ms": lvl_ms / launches, "levels_ms_per_step": lvl_ms,
+                     "candidates_per_s": cands / (lvl_ms * 1e-3)},
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(inp)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,6 @@
+"""MI355X-native pipeline-template planner (Oobleck, Section 4.1) -- Python binding."""
+from .binding import (  # noqa: F401
+    OOB_ECAPACITY, OOB_EHIP, OOB_EINVAL, OOB_EOVERFLOW, OOB_FORBIDDEN, OOB_OK, SYMBOLS,
+    DeviceProfile, DeviceTemplates, Planner, load, oob_plan_create, oob_plan_destroy,
+    oob_plan_max_stages, oob_plan_templates, oob_plan_workspace_size, template_stages,
+)

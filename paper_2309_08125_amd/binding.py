@@ -1,0 +1,242 @@
+"""Thin Python binding of the C ABI in include/oob_plan.h.
+
+Argument marshalling only: every step of the planning path runs in the HIP
+kernels of liboob_plan.so.  PyTorch supplies device memory and the stream.
+There is no CPU fallback: if the library is missing, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "lib", "liboob_plan.so")
+
+OOB_OK, OOB_EINVAL, OOB_ECAPACITY, OOB_EOVERFLOW, OOB_EHIP = 0, -1, -2, -3, -4
+OOB_FORBIDDEN = 1 << 62
+_ERR = {OOB_EINVAL: "OOB_EINVAL", OOB_ECAPACITY: "OOB_ECAPACITY", OOB_EOVERFLOW: "OOB_EOVERFLOW",
+        OOB_EHIP: "OOB_EHIP"}
+
+SYMBOLS = ["oob_plan_max_stages", "oob_plan_workspace_size", "oob_plan_create",
+           "oob_plan_templates", "oob_plan_templates_batch", "oob_plan_destroy", "oob_plan_block",
+           "oob_plan_level_timing", "oob_plan_last_level_ms"]
+
+
+class oob_profile(C.Structure):
+    _fields_ = [("fwd_ns", C.c_void_p), ("bwd_ns", C.c_void_p), ("mem_bytes", C.c_void_p),
+                ("boundary_ns", C.c_void_p)]
+
+
+class oob_templates(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("feasible", "S", "kstar", "T", "T1", "T2", "T3", "tmax", "stage_off", "stage_begin",
+                 "stage_gpus", "cover_hdr", "cover_maxpipes", "status")] + \
+               [("states", C.c_int64), ("candidates", C.c_int64)]
+
+
+class oob_block_desc(C.Structure):
+    _fields_ = [("n", C.c_int32), ("elem_off", C.c_int64), ("T_bytes", C.c_int64),
+                ("T1_bytes", C.c_int64), ("tmax_bytes", C.c_int64), ("T3_bytes", C.c_int64),
+                ("kstar_bytes", C.c_int64), ("choice_bytes", C.c_int64)]
+
+
+_lib = None
+
+
+def load():
+    """Loads liboob_plan.so (built by paper_2309_08125_amd/build.py).  Fails loudly."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2309_08125_amd.build` "
+                               "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        L.oob_plan_max_stages.argtypes = [C.c_int] * 4
+        L.oob_plan_max_stages.restype = C.c_int
+        L.oob_plan_workspace_size.argtypes = [C.c_int] * 3
+        L.oob_plan_workspace_size.restype = C.c_size_t
+        L.oob_plan_create.argtypes = [C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                      C.c_size_t]
+        L.oob_plan_create.restype = C.c_int
+        L.oob_plan_templates.argtypes = [C.c_void_p, C.POINTER(oob_profile), C.c_int, C.c_int,
+                                         C.c_int, C.c_int, C.c_int, C.c_int64, C.c_int,
+                                         C.POINTER(oob_templates), C.c_void_p]
+        L.oob_plan_templates.restype = C.c_int
+        L.oob_plan_templates_batch.argtypes = [C.c_void_p, C.c_int, C.POINTER(oob_profile),
+                                               C.POINTER(C.c_int), C.POINTER(C.c_int),
+                                               C.POINTER(C.c_int), C.POINTER(C.c_int),
+                                               C.POINTER(C.c_int), C.POINTER(C.c_int64),
+                                               C.POINTER(C.c_int), C.POINTER(oob_templates),
+                                               C.c_void_p]
+        L.oob_plan_templates_batch.restype = C.c_int
+        L.oob_plan_destroy.argtypes = [C.c_void_p]
+        L.oob_plan_destroy.restype = C.c_int
+        L.oob_plan_level_timing.argtypes = [C.c_void_p, C.c_int]
+        L.oob_plan_level_timing.restype = C.c_int
+        L.oob_plan_last_level_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
+        L.oob_plan_last_level_ms.restype = C.c_int
+        L.oob_plan_block.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(oob_block_desc)]
+        L.oob_plan_block.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def check(rc: int, what: str):
+    if rc != OOB_OK:
+        raise RuntimeError(f"{what}: {_ERR.get(rc, rc)}")
+
+
+# ---- the C entry points under their own names (thin wrappers) ----------------------------
+def oob_plan_max_stages(L, n_max, gpus_per_node, microbatches) -> int:
+    return load().oob_plan_max_stages(L, n_max, gpus_per_node, microbatches)
+
+
+def oob_plan_workspace_size(max_L, max_nodes, max_gpus_per_node) -> int:
+    return load().oob_plan_workspace_size(max_L, max_nodes, max_gpus_per_node)
+
+
+def oob_plan_create(max_L, max_nodes, max_gpus_per_node, dev_workspace_ptr, workspace_bytes):
+    h = C.c_void_p()
+    rc = load().oob_plan_create(C.byref(h), max_L, max_nodes, max_gpus_per_node,
+                                C.c_void_p(dev_workspace_ptr), workspace_bytes)
+    return rc, h
+
+
+def oob_plan_templates(h, profile: oob_profile, L, n_min, n_max, gpus_per_node, microbatches,
+                       mem_cap, f, out: oob_templates, stream_ptr) -> int:
+    return load().oob_plan_templates(h, C.byref(profile), L, n_min, n_max, gpus_per_node,
+                                     microbatches, mem_cap, f, C.byref(out),
+                                     C.c_void_p(stream_ptr))
+
+
+def oob_plan_destroy(h) -> int:
+    return load().oob_plan_destroy(h)
+
+
+# ---- convenience layer over torch device memory ------------------------------------------
+class DeviceProfile:
+    """A PlanInput's arrays resident in HBM."""
+
+    def __init__(self, inp, device="cuda:0"):
+        import torch
+
+        self.inp = inp
+        self.t = {
+            "fwd_ns": torch.from_numpy(inp.fwd_ns.reshape(-1).copy()).to(device),
+            "bwd_ns": torch.from_numpy(inp.bwd_ns.reshape(-1).copy()).to(device),
+            "mem_bytes": torch.from_numpy(inp.mem_bytes.copy()).to(device),
+            "boundary_ns": torch.from_numpy(inp.boundary_ns.copy()).to(device),
+        }
+        self.c = oob_profile(*(self.t[k].data_ptr() for k in
+                               ("fwd_ns", "bwd_ns", "mem_bytes", "boundary_ns")))
+
+
+class DeviceTemplates:
+    """Result buffers in HBM for `count` templates of at most Smax stages."""
+
+    I32 = ("feasible", "S", "kstar", "stage_off", "stage_begin", "stage_gpus", "cover_hdr",
+           "cover_maxpipes", "status")
+    I64 = ("T", "T1", "T2", "T3", "tmax")
+
+    def __init__(self, count: int, Smax: int, f: int, device="cuda:0"):
+        import torch
+
+        sizes = {"feasible": count, "S": count, "kstar": count, "stage_off": count + 1,
+                 "stage_begin": count * (Smax + 1), "stage_gpus": count * Smax, "cover_hdr": 8,
+                 "cover_maxpipes": max(count, f + 1), "status": 1}
+        self.t = {k: torch.zeros(max(1, sizes[k]), dtype=torch.int32, device=device)
+                  for k in self.I32}
+        self.t.update({k: torch.zeros(count, dtype=torch.int64, device=device) for k in self.I64})
+        self.c = oob_templates()
+        for k in self.I32 + self.I64:
+            setattr(self.c, k, self.t[k].data_ptr())
+
+    def to_host(self) -> Dict[str, "object"]:
+        r = {k: v.cpu().numpy() for k, v in self.t.items()}
+        r["states"], r["candidates"] = int(self.c.states), int(self.c.candidates)
+        return r
+
+
+class Planner:
+    """Owns a workspace tensor and a handle sized for the given maxima."""
+
+    def __init__(self, max_L: int, max_nodes: int, max_gpus_per_node: int, device="cuda:0"):
+        import torch
+
+        self.device = torch.device(device)
+        nbytes = oob_plan_workspace_size(max_L, max_nodes, max_gpus_per_node)
+        if nbytes == 0:
+            raise ValueError("oob_plan_workspace_size: dimensions out of range")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        rc, self.h = oob_plan_create(max_L, max_nodes, max_gpus_per_node,
+                                     self.workspace.data_ptr(), nbytes)
+        check(rc, "oob_plan_create")
+
+    def close(self):
+        if getattr(self, "h", None):
+            oob_plan_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def level_timing(self, enable: bool = True):
+        check(load().oob_plan_level_timing(self.h, int(enable)), "oob_plan_level_timing")
+
+    def last_level_ms(self) -> float:
+        ms = C.c_float()
+        check(load().oob_plan_last_level_ms(self.h, C.byref(ms)), "oob_plan_last_level_ms")
+        return float(ms.value)
+
+    def new_outputs(self, inp) -> DeviceTemplates:
+        Smax = oob_plan_max_stages(inp.L, inp.n_max, inp.gpus_per_node, inp.microbatches)
+        return DeviceTemplates(inp.n_max - inp.n_min + 1, Smax, inp.f, self.device)
+
+    def enqueue(self, prof: DeviceProfile, out: DeviceTemplates, stream=None) -> None:
+        """oob_plan_templates on `stream` (default: torch's current stream); no sync."""
+        import torch
+
+        inp = prof.inp
+        s = stream if stream is not None else torch.cuda.current_stream(self.device)
+        rc = oob_plan_templates(self.h, prof.c, inp.L, inp.n_min, inp.n_max, inp.gpus_per_node,
+                                inp.microbatches, inp.mem_cap, inp.f, out.c, s.cuda_stream)
+        check(rc, "oob_plan_templates")
+
+    def plan(self, inp) -> Dict[str, "object"]:
+        import torch
+
+        prof = DeviceProfile(inp, self.device)
+        out = self.new_outputs(inp)
+        self.enqueue(prof, out)
+        torch.cuda.synchronize(self.device)
+        return out.to_host()
+
+    def block(self, S: int, delta: int) -> Optional[Dict[str, "object"]]:
+        """Records of (S', delta) left by the last call, arrays [n, n] indexed [u, v - S']."""
+        import numpy as np
+        import torch
+
+        d = oob_block_desc()
+        if load().oob_plan_block(self.h, S, delta, C.byref(d)) != OOB_OK:
+            return None
+        n = d.n
+        out = {}
+        for name, off, dt in (("T", d.T_bytes, torch.float64), ("T1", d.T1_bytes, torch.float64),
+                              ("tmax", d.tmax_bytes, torch.float64), ("T3", d.T3_bytes, torch.float64),
+                              ("kstar", d.kstar_bytes, torch.int32),
+                              ("choice", d.choice_bytes, torch.int32)):
+            esz = 8 if dt == torch.float64 else 4
+            lo = off + d.elem_off * esz
+            out[name] = self.workspace[lo: lo + n * n * esz].view(dt).reshape(n, n).cpu().numpy()
+        return out
+
+
+def template_stages(r: dict, i: int):
+    S = int(r["S"][i])
+    off = int(r["stage_off"][i])
+    return (list(map(int, r["stage_begin"][off + i: off + i + S + 1])),
+            list(map(int, r["stage_gpus"][off: off + S])))

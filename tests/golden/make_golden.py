@@ -1,0 +1,66 @@
+"""Writes the stored expected values for the full-size configurations.
+
+Calls only the CPU oracle (oracle/) and the input generators (inputs/).  Output:
+tests/golden/<name>_expected.json with the templates, the coverage and one SHA-256 per
+stage-count level over the canonical form of every state record of that level
+(tests/parity_util.canonical_oracle_block).  Takes minutes for configuration 4.
+
+    python tests/golden/make_golden.py cfg4
+    python tests/golden/make_golden.py cfg5 <instance> [<instance> ...]
+"""
+import hashlib
+import json
+import os
+import sys
+import time
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, os.path.dirname(os.path.dirname(HERE)))
+sys.path.insert(0, os.path.dirname(HERE))
+
+import inputs  # noqa: E402
+from oracle import capi  # noqa: E402
+import parity_util as PU  # noqa: E402
+
+
+def expected(inp) -> dict:
+    t0 = time.time()
+    o = capi.Oracle(inp)
+    t = o.templates(inp.n_min, inp.n_max)
+    c = capi.coverage(t["feasible"], inp.n_min, inp.f)
+    out = {k: [int(x) for x in v] for k, v in t.items()}
+    out["cover_hdr"] = [int(x) for x in c["hdr"]]
+    out["cover_maxpipes"] = [int(x) for x in c["maxpipes"]]
+    out["states"], out["candidates"] = int(o.states), int(o.candidates)
+    digests = {}
+    for S in range(1, o.Smax + 1):
+        h = hashlib.sha256()
+        for delta in range(o.D):
+            if o.valid(S, delta):
+                h.update(PU.canonical_oracle_block(o.block(S, delta), S, inp.L))
+        digests[str(S)] = h.hexdigest()
+    out["level_sha256"] = digests
+    out["_meta"] = {"name": inp.name, "L": inp.L, "n_min": inp.n_min, "n_max": inp.n_max,
+                    "M": inp.gpus_per_node, "microbatches": inp.microbatches, "f": inp.f,
+                    "oracle_seconds": round(time.time() - t0, 1),
+                    "written_by": "tests/golden/make_golden.py (CPU oracle only)"}
+    o.close()
+    return out
+
+
+def main():
+    which = sys.argv[1]
+    if which == "cfg4":
+        inp = inputs.config(4)
+        json.dump(expected(inp), open(os.path.join(HERE, "cfg4_expected.json"), "w"))
+    elif which == "cfg5":
+        insts = inputs.config(5)
+        for idx in map(int, sys.argv[2:]):
+            json.dump(expected(insts[idx]),
+                      open(os.path.join(HERE, f"cfg5_{idx}_expected.json"), "w"))
+    else:
+        raise SystemExit(__doc__)
+
+
+if __name__ == "__main__":
+    main()

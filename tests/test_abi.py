@@ -1,0 +1,71 @@
+"""Host logic of the C ABI that needs no GPU: the library loads, exports every declared
+symbol, validates arguments before touching the device, and sizes its workspace."""
+import ctypes as C
+import os
+import re
+
+import paper_2309_08125_amd as P
+from paper_2309_08125_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "oob_plan.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(oob_plan_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = P.load()
+    names = declared_symbols()
+    assert len(names) >= 7
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(B.SYMBOLS) == names
+
+
+def test_max_stages_and_workspace_size():
+    assert P.oob_plan_max_stages(98, 64, 8, 128) == 98
+    assert P.oob_plan_max_stages(12, 4, 1, 8) == 4
+    assert P.oob_plan_max_stages(128, 32, 8, 64) == 64
+    assert P.oob_plan_max_stages(0, 1, 1, 1) == P.OOB_EINVAL
+    small, big = P.oob_plan_workspace_size(12, 4, 1), P.oob_plan_workspace_size(98, 64, 8)
+    assert 0 < small < big
+    # four double and two int32 arrays per table record, 2 * 3724666-ish padded records
+    assert 250e6 < big < 400e6
+    assert P.oob_plan_workspace_size(2000, 4, 1) == 0  # beyond OOB_MAX_L
+
+
+def test_create_and_call_reject_bad_arguments_without_touching_the_gpu():
+    rc, h = P.oob_plan_create(12, 4, 1, 0, 1 << 20)
+    assert rc == P.OOB_EINVAL  # null workspace
+    rc, h = P.oob_plan_create(12, 4, 1, 0x1001, 1 << 30)
+    assert rc == P.OOB_EINVAL  # not 256-byte aligned
+    rc, h = P.oob_plan_create(12, 4, 1, 0x10000, 16)
+    assert rc == P.OOB_ECAPACITY  # workspace too small
+    need = P.oob_plan_workspace_size(12, 4, 1)
+    rc, h = P.oob_plan_create(12, 4, 1, 0x10000, need)  # a fake address: never dereferenced here
+    assert rc == P.OOB_OK
+    prof = B.oob_profile(1, 1, 1, 1)
+    out = B.oob_templates()
+    for name, _ in B.oob_templates._fields_[:14]:
+        setattr(out, name, 1)
+    call = lambda **kw: P.oob_plan_templates(h, prof, kw.get("L", 12), kw.get("n_min", 1),
+                                             kw.get("n_max", 4), kw.get("M", 1), kw.get("nb", 8),
+                                             kw.get("cap", 1 << 30), kw.get("f", 1), out, 0)
+    assert call(L=0) == P.OOB_EINVAL
+    assert call(n_min=0) == P.OOB_EINVAL
+    assert call(n_min=3, n_max=2) == P.OOB_EINVAL
+    assert call(M=0) == P.OOB_EINVAL
+    assert call(nb=-1) == P.OOB_EINVAL
+    assert call(f=-1) == P.OOB_EINVAL
+    assert call(cap=0) == P.OOB_EINVAL
+    assert call(L=13) == P.OOB_ECAPACITY
+    assert call(n_max=5) == P.OOB_ECAPACITY
+    assert call(M=2) == P.OOB_ECAPACITY
+    out.status = None
+    assert call() == P.OOB_EINVAL  # null output pointer
+    d = B.oob_block_desc()
+    assert P.load().oob_plan_block(h, 1, 0, C.byref(d)) == P.OOB_EINVAL  # no call yet
+    assert P.oob_plan_destroy(h) == P.OOB_OK

@@ -1,0 +1,177 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI, on a real MI355X.
+
+Integer work: everything must match bit for bit -- every field of every state record of
+every level, the templates, the stage lists, the coverage and the work counters.
+"""
+import hashlib
+import json
+import os
+import sys
+
+import numpy as np
+import pytest
+
+import inputs
+from oracle import capi
+import parity_util as PU
+
+pytestmark = pytest.mark.gpu
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    import paper_2309_08125_amd as pkg
+
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    pkg.load()
+    return pkg
+
+
+def oracle_expected(inp):
+    o = capi.Oracle(inp)
+    want = o.templates(inp.n_min, inp.n_max)
+    c = capi.coverage(want["feasible"], inp.n_min, inp.f)
+    want["cover_hdr"], want["cover_maxpipes"] = c["hdr"], c["maxpipes"]
+    want["states"], want["candidates"] = o.states, o.candidates
+    return o, want
+
+
+def full_check(P, planner, inp):
+    """Templates and every block of every level against the oracle."""
+    say(f"case {inp.name} L={inp.L} M={inp.gpus_per_node} n={inp.n_min}-{inp.n_max} "
+        f"nb={inp.microbatches} f={inp.f} cap={inp.mem_cap}")
+    got = planner.plan(inp)
+    o, want = oracle_expected(inp)
+    try:
+        PU.compare_templates(got, want, inp.n_max - inp.n_min + 1)
+        nstates = 0
+        for S in range(1, o.Smax + 1):
+            for delta in range(o.D):
+                gb = planner.block(S, delta)
+                assert (gb is not None) == o.valid(S, delta), (S, delta)
+                if gb is not None:
+                    nstates += PU.compare_block(gb, o.block(S, delta), S, inp.L)
+        return got, nstates
+    finally:
+        o.close()
+
+
+SHAPES = [(5, 1, 1, 3, 6), (6, 2, 1, 3, 8), (7, 2, 1, 2, 5), (6, 4, 1, 2, 12), (8, 4, 2, 3, 12),
+          (6, 3, 1, 2, 0), (7, 1, 1, 4, 0), (9, 3, 1, 4, 4), (12, 2, 2, 5, 0), (10, 8, 1, 2, 16),
+          (1, 1, 1, 1, 4), (1, 4, 1, 2, 4), (3, 2, 1, 5, 2), (37, 3, 1, 5, 9), (70, 2, 1, 6, 11)]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_small_random_every_state(P, shape):
+    """Small and ragged shapes (L not a multiple of any tile, L = 1, more nodes than layers,
+    N_b below the stage limit, the paper's N_b = 4 S' mode), three variants of the memory cap /
+    forbidden GPU counts, every state compared."""
+    L, M, n_min, n_max, nb = shape
+    planner = P.Planner(L, n_max, M)
+    for seed in range(3):
+        for var in ("plain", "tight", "forbid"):
+            inp = inputs.random_small(seed, L, M, n_min, n_max, nb, f=seed,
+                                      tight_mem=(var == "tight"), forbid_some_d=(var == "forbid"))
+            full_check(P, planner, inp)
+    planner.close()
+
+
+def test_handle_reuse_across_shapes(P):
+    """One handle sized for the maxima serves smaller jobs back to back."""
+    planner = P.Planner(40, 6, 4)
+    for i, (L, M, n_max, nb) in enumerate([(40, 4, 6, 16), (9, 2, 3, 5), (25, 3, 6, 0), (40, 1, 6, 40)]):
+        full_check(P, planner, inputs.random_small(50 + i, L, M, 1, n_max, nb, f=1, tight_mem=(i % 2 == 0)))
+    planner.close()
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3])
+def test_configs_1_to_3_every_state(P, cfg):
+    inp = inputs.config(cfg)
+    planner = P.Planner(inp.L, inp.n_max, inp.gpus_per_node)
+    got, nstates = full_check(P, planner, inp)
+    assert got["feasible"].all()
+    say(f"config {cfg}: {got['states']} states ({nstates} exist), {got['candidates']} candidates: bit-exact")
+    planner.close()
+
+
+def check_against_golden(P, inp, path):
+    g = json.load(open(path))
+    planner = P.Planner(inp.L, inp.n_max, inp.gpus_per_node)
+    got = planner.plan(inp)
+    want = {k: np.array(v) for k, v in g.items() if isinstance(v, list)}
+    want["states"], want["candidates"] = g["states"], g["candidates"]
+    PU.compare_templates(got, want, inp.n_max - inp.n_min + 1)
+    Smax = P.oob_plan_max_stages(inp.L, inp.n_max, inp.gpus_per_node, inp.microbatches)
+    D = inp.gpus_per_node - 1 + inp.n_max
+    bad = []
+    for S in range(1, Smax + 1):
+        h = hashlib.sha256()
+        for delta in range(D):
+            gb = planner.block(S, delta)
+            if gb is not None:
+                h.update(PU.canonical_gpu_block(gb, S, inp.L))
+        if h.hexdigest() != g["level_sha256"][str(S)]:
+            bad.append(S)
+    planner.close()
+    assert not bad, f"levels whose state records differ from the oracle's: {bad[:10]}"
+    return got
+
+
+@pytest.mark.timeout(900)
+def test_config4_full_size_against_stored_oracle_results(P):
+    """The headline workload in the configuration bench.py times.  The oracle needs minutes
+    for it, so its templates and a SHA-256 per level over all state records are stored by
+    tests/golden/make_golden.py (which calls only the oracle)."""
+    inp = inputs.config(4)
+    say("config 4 (L=98, n=8..64 x 8 GPUs)")
+    got = check_against_golden(P, inp, os.path.join(GOLD, "cfg4_expected.json"))
+    assert (got["states"], got["candidates"]) == (3724666, 16232508904)
+
+
+def test_device_status_reports_bad_profile_values(P):
+    import torch
+
+    inp = inputs.random_small(3, 8, 2, 1, 2, 6)
+    planner = P.Planner(8, 2, 2)
+    bad = inputs.PlanInput("neg", inp.fwd_ns.copy(), inp.bwd_ns, inp.mem_bytes, inp.boundary_ns, 1, 2, 2, 6,
+                           inp.mem_cap, 1)
+    bad.fwd_ns[3, 0] = -5
+    assert int(planner.plan(bad)["status"][0]) == P.OOB_EINVAL
+    big = inputs.PlanInput("big", inp.fwd_ns * (1 << 45), inp.bwd_ns, inp.mem_bytes, inp.boundary_ns, 1, 2, 2,
+                           6, inp.mem_cap, 1)
+    assert int(planner.plan(big)["status"][0]) == P.OOB_EOVERFLOW
+    assert int(planner.plan(inp)["status"][0]) == P.OOB_OK
+    planner.close()
+
+
+def test_large_times_stay_exact(P):
+    """Times near the top of the exactly representable range (sums around 2^44)."""
+    inp = inputs.random_small(11, 9, 2, 1, 3, 7, t_lo=(1 << 36), t_hi=(1 << 37))
+    planner = P.Planner(9, 3, 2)
+    full_check(P, planner, inp)
+    planner.close()
+
+
+def test_two_calls_same_answer(P):
+    """Determinism: the same job twice on one handle gives identical tables."""
+    inp = inputs.config(2)
+    planner = P.Planner(inp.L, inp.n_max, inp.gpus_per_node)
+    a = planner.plan(inp)
+    blocks_a = {(S, d): planner.block(S, d) for S in (2, 5, 9) for d in range(3, 12)}
+    b = planner.plan(inp)
+    for k in a:
+        assert np.array_equal(np.asarray(a[k]), np.asarray(b[k])), k
+    for (S, d), ba in blocks_a.items():
+        bb = planner.block(S, d)
+        assert (ba is None) == (bb is None)
+        if ba is not None:
+            for k in ba:
+                assert np.array_equal(ba[k], bb[k])
+    planner.close()
