@@ -131,24 +131,15 @@ int oob_plan_destroy(oob_plan *h);
 int oob_plan_level_timing(oob_plan *h, int enable);
 int oob_plan_last_level_ms(oob_plan *h, float *ms /* HOST */);
 
-/* Introspection of the tables left in the workspace by the last oob_plan_templates call, so
- * that a test can compare every state with a reference.  The block of (S', delta) holds
- * n*n records, record (u, v) at index u*n + (v - S') (v - u >= S'; other indices are
- * padding).  Device set index: delta = g-1 for g GPUs inside a node (g < M),
- * delta = M-2+a for a whole nodes.  Offsets are in elements from the start of each array,
- * arrays are given as byte offsets into the workspace.  Returns OOB_EINVAL when (S', delta)
- * has no states. */
-typedef struct {
-    int32_t n;              /* L - S' + 1                                                   */
-    int64_t elem_off;       /* first element of the block                                   */
-    int64_t T_bytes;        /* double[]  total of the record under its own S' (+inf: none)  */
-    int64_t T1_bytes;       /* double[]                                                     */
-    int64_t tmax_bytes;     /* double[]                                                     */
-    int64_t T3_bytes;       /* double[]                                                     */
-    int64_t kstar_bytes;    /* int32[]                                                      */
-    int64_t choice_bytes;   /* int32[]   s | k << 10 | m << 21                              */
-} oob_block_desc;
-int oob_plan_block(const oob_plan *h, int S, int delta, oob_block_desc *desc);
+/* Introspection for tests: copies the records of (S', delta) left in the workspace by the last
+ * oob_plan_templates call into dense DEVICE arrays of n*n entries, n = L - S' + 1, record
+ * (u, v) at index u*n + (v - S') (v - u >= S'; other entries read as "no such state").
+ * T is the record's total under its own S' (+inf: the state does not exist); choice packs the
+ * winning split as s | k << 10 | m << 21.  Device set index: delta = g-1 for g GPUs inside a
+ * node (g < M), delta = M-2+a for a whole nodes.  Returns OOB_EINVAL when (S', delta) has no
+ * states.  Enqueued on `stream`. */
+int oob_plan_export_block(oob_plan *h, int S, int delta, double *T, double *T1, double *tmax,
+                          double *T3, int32_t *kstar, int32_t *choice, void *stream);
 
 #ifdef __cplusplus
 }

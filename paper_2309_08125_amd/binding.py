@@ -19,7 +19,7 @@ _ERR = {OOB_EINVAL: "OOB_EINVAL", OOB_ECAPACITY: "OOB_ECAPACITY", OOB_EOVERFLOW:
         OOB_EHIP: "OOB_EHIP"}
 
 SYMBOLS = ["oob_plan_max_stages", "oob_plan_workspace_size", "oob_plan_create",
-           "oob_plan_templates", "oob_plan_templates_batch", "oob_plan_destroy", "oob_plan_block",
+           "oob_plan_templates", "oob_plan_templates_batch", "oob_plan_destroy", "oob_plan_export_block",
            "oob_plan_level_timing", "oob_plan_last_level_ms"]
 
 
@@ -33,12 +33,6 @@ class oob_templates(C.Structure):
                 ("feasible", "S", "kstar", "T", "T1", "T2", "T3", "tmax", "stage_off", "stage_begin",
                  "stage_gpus", "cover_hdr", "cover_maxpipes", "status")] + \
                [("states", C.c_int64), ("candidates", C.c_int64)]
-
-
-class oob_block_desc(C.Structure):
-    _fields_ = [("n", C.c_int32), ("elem_off", C.c_int64), ("T_bytes", C.c_int64),
-                ("T1_bytes", C.c_int64), ("tmax_bytes", C.c_int64), ("T3_bytes", C.c_int64),
-                ("kstar_bytes", C.c_int64), ("choice_bytes", C.c_int64)]
 
 
 _lib = None
@@ -76,8 +70,8 @@ def load():
         L.oob_plan_level_timing.restype = C.c_int
         L.oob_plan_last_level_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         L.oob_plan_last_level_ms.restype = C.c_int
-        L.oob_plan_block.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(oob_block_desc)]
-        L.oob_plan_block.restype = C.c_int
+        L.oob_plan_export_block.argtypes = [C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 7
+        L.oob_plan_export_block.restype = C.c_int
         _lib = L
     return _lib
 
@@ -205,6 +199,7 @@ class Planner:
         rc = oob_plan_templates(self.h, prof.c, inp.L, inp.n_min, inp.n_max, inp.gpus_per_node,
                                 inp.microbatches, inp.mem_cap, inp.f, out.c, s.cuda_stream)
         check(rc, "oob_plan_templates")
+        self.last_L = inp.L
 
     def plan(self, inp) -> Dict[str, "object"]:
         import torch
@@ -217,22 +212,22 @@ class Planner:
 
     def block(self, S: int, delta: int) -> Optional[Dict[str, "object"]]:
         """Records of (S', delta) left by the last call, arrays [n, n] indexed [u, v - S']."""
-        import numpy as np
         import torch
 
-        d = oob_block_desc()
-        if load().oob_plan_block(self.h, S, delta, C.byref(d)) != OOB_OK:
+        n = self.last_L - S + 1
+        if n < 1:
             return None
-        n = d.n
-        out = {}
-        for name, off, dt in (("T", d.T_bytes, torch.float64), ("T1", d.T1_bytes, torch.float64),
-                              ("tmax", d.tmax_bytes, torch.float64), ("T3", d.T3_bytes, torch.float64),
-                              ("kstar", d.kstar_bytes, torch.int32),
-                              ("choice", d.choice_bytes, torch.int32)):
-            esz = 8 if dt == torch.float64 else 4
-            lo = off + d.elem_off * esz
-            out[name] = self.workspace[lo: lo + n * n * esz].view(dt).reshape(n, n).cpu().numpy()
-        return out
+        bufs = {k: torch.empty(n * n, dtype=torch.float64, device=self.device)
+                for k in ("T", "T1", "tmax", "T3")}
+        bufs.update({k: torch.empty(n * n, dtype=torch.int32, device=self.device)
+                     for k in ("kstar", "choice")})
+        s = torch.cuda.current_stream(self.device)
+        rc = load().oob_plan_export_block(self.h, S, delta, *(bufs[k].data_ptr() for k in
+                                          ("T", "T1", "tmax", "T3", "kstar", "choice")),
+                                          C.c_void_p(s.cuda_stream))
+        if rc != OOB_OK:
+            return None
+        return {k: v.cpu().numpy().reshape(n, n) for k, v in bufs.items()}
 
 
 def template_stages(r: dict, i: int):

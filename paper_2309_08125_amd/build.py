@@ -21,7 +21,7 @@ def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wno-unused-command-line-argument",
+           "-fno-honor-nans", "-Wno-unused-command-line-argument",
            "-I", os.path.join(ROOT, "include"), "-I", SRC_DIR, "-o", LIB] + sources()
     if verbose:
         print(" ".join(cmd))

@@ -4,12 +4,17 @@
 // S' stages on device set delta.  Device sets: G(g) = g GPUs inside one node (delta = g-1,
 // 1 <= g <= M-1) and A(a) = a whole nodes (delta = M-2+a).  Both kinds form an additive
 // family: a set of `units` is split into m and units-m, with delta = fam_base + units where
-// fam_base = -1 inside a node (units = GPUs, A(1) counts as M GPUs) and M-2 across nodes
-// (units = nodes).
+// fam_base = -1 inside a node (units = GPUs; A(1) counts as M GPUs when it is the target)
+// and fam_base = M-2 across nodes (units = nodes).
 //
-// Level S' stores, for every delta in [dlo(S'), dhi(S')], a dense n x n block, n = L-S'+1,
-// record (u, v) at row i = u, column j = v - S'; only j >= i are states, the rest is padding
-// that holds the "no such state" value so that the inner loops need no masks.
+// Storage.  Every valid (S', delta) owns one table: the (u, v) plane in ABSOLUTE layer
+// coordinates, 0 <= u <= v <= L, cut into 8 x 8 blocks (block row u/8, block column v/8, only
+// block columns >= block rows are kept), 64 records per block, row-major inside the block.
+// Absolute coordinates make the three operands of a split at k line up on the same block
+// grid: left child at (u, k), right child at (k, v), target at (u, v) -- the layout of a
+// blocked matrix product.  Entries that are not states (v - u < S', u >= L, v > L) inside a
+// block that holds at least one state carry the "no such state" value, so inner loops need
+// no masks; blocks without any state are never written and never read.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -24,13 +29,12 @@ struct Shape {
 
 __host__ __device__ inline int imin(int a, int b) { return a < b ? a : b; }
 __host__ __device__ inline int imax(int a, int b) { return a > b ? a : b; }
+__host__ __device__ inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
 // (S', delta) exists ("Choosing the number of stages": a stage never spans nodes and every
 // GPU is used): G(g): S' <= g;  A(a): a <= S' <= a*M.  The valid deltas of a level are the
 // contiguous range [dlo, dhi].
-__host__ __device__ inline int dlo_of(int S, int M) {
-    return S <= M ? S - 1 : M - 2 + (S + M - 1) / M;
-}
+__host__ __device__ inline int dlo_of(int S, int M) { return S <= M ? S - 1 : M - 2 + cdiv(S, M); }
 __host__ __device__ inline int dhi_of(int S, int M, int n_max) { return M - 2 + imin(S, n_max); }
 
 __host__ __device__ inline int smax_of(int L, int n_max, int M, int Nb) {
@@ -42,27 +46,68 @@ __host__ __device__ inline int smax_of(int L, int n_max, int M, int Nb) {
 
 // Family of a target device set.
 struct Family {
+    int fam;      // 0: inside one node (units = GPUs), 1: across nodes (units = nodes)
     int fam_base; // delta of a member with `e` units is fam_base + e
     int units;    // units of the target
 };
 __host__ __device__ inline Family family_of(int delta, int M) {
     Family f;
-    if (delta >= M) { f.fam_base = M - 2; f.units = delta - (M - 2); }        // A(a), a >= 2
-    else            { f.fam_base = -1;    f.units = delta < M - 1 ? delta + 1 : M; } // one node
+    if (delta >= M) { f.fam = 1; f.fam_base = M - 2; f.units = delta - (M - 2); }               // A(a), a >= 2
+    else            { f.fam = 0; f.fam_base = -1;    f.units = delta < M - 1 ? delta + 1 : M; } // one node
     return f;
 }
 
-// Left-half unit counts m for which both children (s, m) and (S'-s, units-m) exist:
-// the closed range [lo, hi] (empty when lo > hi).
-__host__ __device__ inline void m_range(int fam_base, int units, int s, int r, int M, int *lo,
-                                        int *hi) {
-    if (fam_base < 0) { // GPUs of one node: child (s, G(m)) needs s <= m
-        *lo = imax(1, s);
-        *hi = imin(units - 1, units - r);
-    } else {            // whole nodes: child (s, A(m)) needs m <= s <= m*M
-        *lo = imax(imax(1, (s + M - 1) / M), units - r);
-        *hi = imin(imin(units - 1, s), units - (r + M - 1) / M);
+// Unit counts e for which the CHILD state (S, member e of the family) exists: [lo, hi].
+// Across nodes: ceil(S/M) <= e <= min(S, n_max).  Inside a node a child is always some
+// G(e): S <= e <= M-1.
+__host__ __device__ inline void child_units(int fam, int S, int M, int n_max, int *lo, int *hi) {
+    if (fam == 0) { *lo = S; *hi = M - 1; }
+    else              { *lo = cdiv(S, M); *hi = imin(S, n_max); }
+}
+
+// Left-half unit counts m for which both children (s, m) and (r, units-m) exist: [lo, hi]
+// (empty when lo > hi).
+__host__ __device__ inline void m_range(int fam, int units, int s, int r, int M, int n_max,
+                                        int *lo, int *hi) {
+    int alo, ahi, blo, bhi;
+    child_units(fam, s, M, n_max, &alo, &ahi);
+    child_units(fam, r, M, n_max, &blo, &bhi);
+    *lo = imax(alo, units - bhi);
+    *hi = imin(ahi, units - blo);
+}
+
+// Target unit counts of a family at level S': inside a node S' <= g <= M (g = M is A(1));
+// across nodes max(2, ceil(S'/M)) <= a <= min(S', n_max).
+__host__ __device__ inline void target_units(int fam, int S, int M, int n_max, int *lo, int *hi) {
+    if (fam == 0) { *lo = S; *hi = M; }
+    else          { *lo = imax(2, cdiv(S, M)); *hi = imin(S, n_max); }
+}
+
+// ---- blocked (u, v) plane ----------------------------------------------------------------
+__host__ __device__ inline int nblocks_of(int L) { return L / 8 + 1; } // v runs 0..L
+__host__ __device__ inline int tri_blocks(int NB) { return NB * (NB + 1) / 2; }
+__host__ __device__ inline int tri_index(int ub, int vb, int NB) {
+    return ub * NB - ub * (ub - 1) / 2 + (vb - ub);
+}
+
+// Blocks of level S' that hold at least one state: (ub, vb = ub + d) with 8d + 7 >= S' and
+// 8 ub + S' <= L.  They are enumerated by decreasing d (the blocks far from the diagonal have
+// the longest split ranges, so the heaviest workgroups start first).
+__host__ __device__ inline int tile_dmin(int S) { return S / 8; } // = ceil((S' - 7) / 8)
+__host__ __device__ inline int tile_count(int L, int S) {
+    const int NB = nblocks_of(L), ubmax = (L - S) / 8;
+    int c = 0;
+    for (int d = NB - 1; d >= tile_dmin(S); --d) c += imin(ubmax, NB - 1 - d) + 1;
+    return c;
+}
+__host__ __device__ inline void tile_decode(int L, int S, int t, int *ub, int *vb) {
+    const int NB = nblocks_of(L), ubmax = (L - S) / 8;
+    for (int d = NB - 1; d >= tile_dmin(S); --d) {
+        const int c = imin(ubmax, NB - 1 - d) + 1;
+        if (t < c) { *ub = t; *vb = t + d; return; }
+        t -= c;
     }
+    *ub = 0; *vb = 0;
 }
 
 } // namespace oob

@@ -5,17 +5,29 @@
 // Arithmetic.  Inputs and outputs are int64.  Inside the tables every time is held as an
 // IEEE double: gfx950 issues 64-bit floating add / min / compare at full rate (one VALU
 // instruction each) while a 64-bit integer add or compare takes two or more, and doubles are
-// exact for integers below 2^53.  The set-up kernel proves the bound (every cost the
+// exact for integers below 2^53.  The set-up kernel proves the bound (every quantity the
 // recursion can form stays below 2^52 ns, about 52 days) or reports OOB_EOVERFLOW, so the
-// results are bit-identical to int64 arithmetic.
+// results are bit-identical to int64 arithmetic in any evaluation order.
 //
 // What a state stores.  With r = S' - s and children A = (s, u, k, left set),
 // B = (r, k, v, right set), Eq. 1-3 give the candidate's total
-//     slowest stage in A (A.tmax >= B.tmax):  T = A.T + cl * A.tmax + 2 * B.T1
-//     slowest stage in B:                     T = A.T1 + B.T + cr * B.tmax
+//     slowest stage in A (A.tmax >= B.tmax):  T = (A.T + cl * A.tmax) + 2 * B.T1
+//     slowest stage in B:                     T = A.T1 + (B.T + cr * B.tmax)
 // where X.T is the child's own total under its own stage count, and (cl, cr) = (-r, 0) when
 // N_b is the caller's microbatch count or (3r, 4s) when N_b = 4 S' per state.  So the hot
-// loop needs only (T, T1, tmax) per child; T3 and k* are carried per state for the output.
+// loop needs only (T, T1, tmax) per child: 2 adds, 1 compare, 2 selects, 1 min per candidate.
+// T3 and k* are carried per state for the output only.
+//
+// One level S' = two kernels.
+//   k_split  grid (block of the (u,v) plane) x (split s) x (group of target device sets).
+//            A workgroup stages, per chunk of k, the left-child records of every m it needs
+//            and the right-child records of every m' in LDS, pre-combined with cl / cr; each
+//            wave owns 8 target device sets x an 8 x 8 block of (u, v) (one state per lane and
+//            set) and walks k ascending, all m per k, keeping only the running minimum and,
+//            per state, the first k that reached it.  Result: per (s, state) the minimum over
+//            (k, m) and that k.
+//   k_select per state: first s with the smallest partial minimum, then the first m at that
+//            (s, k) whose candidate equals it -- the smallest (T, s, k, m) -- and the record.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <new>
@@ -30,29 +42,37 @@ namespace oob {
 
 constexpr double kNone = __builtin_huge_val(); // total of a state that does not exist
 constexpr long long kExactBound = 1LL << 52;
+constexpr int kInternalError = -5;             // status: a state's minimum was not re-found
+
+struct Rec { double T, T1, tmax, T3; };        // 32 bytes, one per (table, u, v)
 
 // Device view of the workspace.
 struct Tables {
     Shape sh;
-    long long *lvl_base; // [Smax+2] first element of level S'
-    long long *PT;       // [(M+1)*(L+1)] prefix sums of F+B for d GPUs (row d)
-    int *PF;             // [(M+1)*(L+1)] prefix counts of forbidden entries
-    long long *PM;       // [L+1] prefix sums of bytes
-    double *T, *T1, *tmax, *T3;
-    int *kstar, *choice;
-    int *stack;          // [count*(Smax+1)*4] backtracking stacks
+    int NB;               // blocks per side of the (u, v) plane
+    int tab_recs;         // records per table = tri_blocks(NB) * 64
+    long long *lvl_tab;   // [Smax+2] index of the first table of level S'
+    long long *PT;        // [(M+1)*(L+1)] prefix sums of F+B for d GPUs (row d)
+    int *PF;              // [(M+1)*(L+1)] prefix counts of forbidden entries
+    long long *PM;        // [L+1] prefix sums of bytes
+    Rec *rec;             // [tables * tab_recs]
+    int *kstar, *choice;  // [tables * tab_recs]
+    double *partT;        // [(S'-1) * deltas * tiles * 64] per-split minima of the current level
+    int *partK;           // same shape: first k reaching the minimum
+    int *stack;           // backtracking stacks / coverage ring
+    int *status;
 };
 
-__device__ __forceinline__ long long elem(const Tables &t, int S, int delta, int i, int j) {
-    const int n = t.sh.L - S + 1;
-    return t.lvl_base[S] + ((long long)(delta - dlo_of(S, t.sh.M)) * n + i) * n + j;
+__device__ __forceinline__ long long rec_index(const Tables &t, int S, int delta, int u, int v) {
+    const long long tab = t.lvl_tab[S] + (delta - dlo_of(S, t.sh.M));
+    return tab * t.tab_recs + (long long)tri_index(u >> 3, v >> 3, t.NB) * 64 + ((u & 7) << 3) + (v & 7);
 }
 
 // ---------------------------------------------------------------------------------------
 // Set-up: prefix sums (Eq. 4's sums become differences), input validation, level offsets.
 // One block; thread d-1 scans the profile row of d GPUs.
 // ---------------------------------------------------------------------------------------
-__global__ void k_setup(Tables t, oob_profile prof, int *status) {
+__global__ void k_setup(Tables t, oob_profile prof) {
     const int L = t.sh.L, M = t.sh.M, W = L + 1;
     __shared__ long long s_worst[OOB_MAX_GPUS + 1];
     __shared__ int s_bad;
@@ -60,21 +80,23 @@ __global__ void k_setup(Tables t, oob_profile prof, int *status) {
     __syncthreads();
     const int d = threadIdx.x + 1;
     if (d <= M) {
-        long long acc = 0, worst = 0;
+        long long acc = 0;
         int forb = 0, bad = 0;
         t.PT[d * W] = 0;
         t.PF[d * W] = 0;
         for (int l = 0; l < L; ++l) {
             const long long F = prof.fwd_ns[(size_t)l * M + d - 1], B = prof.bwd_ns[(size_t)l * M + d - 1];
-            if (F < 0 || B < 0) bad = 1;
+            if (F < 0 || B < 0) bad = imax(bad, 1);
             const int fb = (F >= OOB_FORBIDDEN || B >= OOB_FORBIDDEN);
-            if (!fb) { acc += F + B; if (acc >= kExactBound) { bad = 2; acc = 0; } }
+            if (!fb && F >= 0 && B >= 0) {
+                if (F >= kExactBound || B >= kExactBound || acc + F + B >= kExactBound) { bad = imax(bad, 2); acc = 0; }
+                else acc += F + B;
+            }
             forb += fb;
             t.PT[d * W + l + 1] = acc;
             t.PF[d * W + l + 1] = forb;
         }
-        worst = acc;
-        s_worst[d] = worst;
+        s_worst[d] = acc;
         if (bad) atomicMax(&s_bad, bad);
     }
     if (threadIdx.x == blockDim.x - 1) { // bytes, boundary terms, level offsets
@@ -83,18 +105,19 @@ __global__ void k_setup(Tables t, oob_profile prof, int *status) {
         t.PM[0] = 0;
         for (int l = 0; l < L; ++l) {
             const long long mb = prof.mem_bytes[l], x = prof.boundary_ns[l];
-            if (mb < 0 || x < 0 || mb >= OOB_FORBIDDEN || acc + mb >= OOB_FORBIDDEN) bad = 1;
-            if (x >= kExactBound || xs + x >= kExactBound) bad = imax(bad, 2); else xs += x;
-            acc += mb;
+            if (mb < 0 || x < 0 || mb >= OOB_FORBIDDEN || acc + mb >= OOB_FORBIDDEN) bad = imax(bad, 1);
+            else acc += mb;
+            if (x >= kExactBound || xs + x >= kExactBound) bad = imax(bad, 2);
+            else if (x > 0) xs += x;
             t.PM[l + 1] = acc;
         }
         s_worst[0] = xs;
         if (bad) atomicMax(&s_bad, bad);
-        long long base = 0;
+        long long tab = 0;
         for (int S = 1; S <= t.sh.Smax + 1; ++S) {
-            t.lvl_base[S] = base;
-            const int n = L - S + 1, nd = dhi_of(S, M, t.sh.n_max) - dlo_of(S, M) + 1;
-            if (S <= t.sh.Smax && nd > 0) base += (long long)nd * n * n;
+            t.lvl_tab[S] = tab;
+            const int nd = dhi_of(S, M, t.sh.n_max) - dlo_of(S, M) + 1;
+            if (S <= t.sh.Smax && nd > 0) tab += nd;
         }
     }
     __syncthreads();
@@ -115,7 +138,7 @@ __global__ void k_setup(Tables t, oob_profile prof, int *status) {
             const long long mult = nb + 4LL * t.sh.Smax + 4;
             if (worst >= kExactBound / mult) st = OOB_EOVERFLOW;
         }
-        *status = st;
+        *t.status = st;
     }
 }
 
@@ -132,78 +155,208 @@ __device__ __forceinline__ bool stage_time(const Tables &t, const long long *X, 
 }
 
 // ---------------------------------------------------------------------------------------
-// Level 1 ("Conquer", Eq. 4): one thread per (delta, i, j) of the level-1 blocks.
+// Level 1 ("Conquer", Eq. 4): grid (block of the plane, delta), one lane per (u, v).
 // ---------------------------------------------------------------------------------------
-__global__ void k_level1(Tables t, const long long *X) {
-    const int L = t.sh.L, M = t.sh.M, n = L;
-    const long long total = (long long)M * n * n;
-    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= total) return;
-    const int j = (int)(idx % n), i = (int)((idx / n) % n), delta = (int)(idx / ((long long)n * n));
-    const long long o = t.lvl_base[1] + idx;
-    double T = kNone, T1 = kNone, tm = 0.0, T3 = 0.0;
-    if (j >= i) {
+__global__ void __launch_bounds__(64) k_level1(Tables t, const long long *X) {
+    const int L = t.sh.L, M = t.sh.M;
+    int ub, vb;
+    tile_decode(L, 1, blockIdx.x, &ub, &vb);
+    const int delta = blockIdx.y, u = ub * 8 + (threadIdx.x >> 3), v = vb * 8 + (threadIdx.x & 7);
+    Rec r = {kNone, kNone, 0.0, 0.0};
+    if (u < L && v <= L && v - u >= 1) {
         const int d = delta < M - 1 ? delta + 1 : M;
         long long st;
-        if (stage_time(t, X, i, j + 1, d, &st)) {
+        if (stage_time(t, X, u, v, d, &st)) {
             const double nb = t.sh.Nb > 0 ? (double)t.sh.Nb : 4.0;
-            T1 = tm = T3 = (double)st;
-            T = T1 + (nb - 2.0) * tm + T3; // Eq. 2 with S' = 1, k* = 0
+            r.T1 = r.tmax = r.T3 = (double)st;
+            r.T = r.T1 + (nb - 2.0) * r.tmax + r.T3; // Eq. 2 with S' = 1, k* = 0
         }
     }
-    t.T[o] = T; t.T1[o] = T1; t.tmax[o] = tm; t.T3[o] = T3;
-    t.kstar[o] = 0; t.choice[o] = 0;
+    const long long o = rec_index(t, 1, delta, ub * 8, vb * 8) + threadIdx.x;
+    t.rec[o] = r;
+    t.kstar[o] = 0;
+    t.choice[o] = 0;
 }
 
 // ---------------------------------------------------------------------------------------
-// Levels S' >= 2 ("Divide", Eq. 1-3), plain version: one thread per state, candidates in
-// the order s, k, m with a strict-minimum update (so the smallest (T, s, k, m) wins).
+// Levels S' >= 2 ("Divide", Eq. 1-3), first kernel: per (s, state) the minimum over (k, m).
+//   grid.x  block (ub, vb) of the plane      grid.y  s - 1      grid.z  group of 8*waves sets
+//   fam     0: targets inside one node (units = GPUs), 1: whole-node targets (units = nodes)
+// PC = k values staged per pass.
 // ---------------------------------------------------------------------------------------
-__global__ void k_combine_simple(Tables t, int Sp) {
-    const int L = t.sh.L, M = t.sh.M, n = L - Sp + 1;
-    const int dlo = dlo_of(Sp, M), nd = dhi_of(Sp, M, t.sh.n_max) - dlo + 1;
-    const long long total = (long long)nd * n * n;
-    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= total) return;
-    const int j = (int)(idx % n), i = (int)((idx / n) % n), delta = dlo + (int)(idx / ((long long)n * n));
-    const long long o = t.lvl_base[Sp] + idx;
-    double best = kNone;
-    int bs = 0, bp = 0, bm = 0;
-    if (j >= i) {
-        const Family fam = family_of(delta, M);
-        for (int s = 1; s < Sp; ++s) {
-            const int r = Sp - s;
-            int mlo, mhi;
-            m_range(fam.fam_base, fam.units, s, r, M, &mlo, &mhi);
-            if (mlo > mhi) continue;
-            const double cl = t.sh.Nb > 0 ? -(double)r : 3.0 * r, cr = t.sh.Nb > 0 ? 0.0 : 4.0 * s;
-            for (int p = i; p <= j; ++p) {          // k = p + s
-                for (int m = mlo; m <= mhi; ++m) {
-                    const long long oa = elem(t, s, fam.fam_base + m, i, p);
-                    const long long ob = elem(t, r, fam.fam_base + fam.units - m, p + s, j + s);
-                    const double aT = t.T[oa], aT1 = t.T1[oa], am = t.tmax[oa];
-                    const double bT = t.T[ob], bT1 = t.T1[ob], bmx = t.tmax[ob];
-                    const double left = aT + cl * am + 2.0 * bT1;
-                    const double right = aT1 + (bT + cr * bmx);
-                    const double T = am >= bmx ? left : right;
-                    if (T < best) { best = T; bs = s; bp = p; bm = m; }
+template <int PC>
+__global__ void __launch_bounds__(512) k_split(Tables t, int Sp, int fam, int NT, int NAall) {
+    HIP_DYNAMIC_SHARED(double2, s_pair) // [ntab][PC][8] (x, y) pairs, then double tmax[ntab][PC][8]
+    const int L = t.sh.L, M = t.sh.M, n_max = t.sh.n_max;
+    const int s = blockIdx.y + 1, r = Sp - s;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int ul = lane >> 3, vl = lane & 7;
+    int ub, vb;
+    tile_decode(L, Sp, blockIdx.x, &ub, &vb);
+    const int fam_base = fam ? M - 2 : -1;
+    int t_lo, t_hi;
+    target_units(fam, Sp, M, n_max, &t_lo, &t_hi);
+    const int a_wg0 = t_lo + blockIdx.z * nw * 8, a_wg1 = imin(t_hi, a_wg0 + nw * 8 - 1);
+    int A_lo, A_hi, B_lo, B_hi;
+    child_units(fam, s, M, n_max, &A_lo, &A_hi);
+    child_units(fam, r, M, n_max, &B_lo, &B_hi);
+    // left / right unit counts some target of this workgroup pairs up
+    const int mA0 = imax(A_lo, a_wg0 - B_hi), mA1 = imin(A_hi, a_wg1 - B_lo);
+    const int mB0 = imax(B_lo, a_wg0 - A_hi), mB1 = imin(B_hi, a_wg1 - A_lo);
+    const int kmin = ub * 8 + s, kmax = imin(vb * 8 + 7, L) - r;
+    const bool work = mA0 <= mA1 && mB0 <= mB1 && kmin <= kmax;
+    const int nA = work ? mA1 - mA0 + 1 : 0, nB = work ? mB1 - mB0 + 1 : 0, dummy = nA + nB;
+    constexpr int TS = PC * 8;
+    double *s_tm = (double *)(s_pair + (size_t)(dummy + 1) * TS);
+
+    // this wave's targets a0..a0+7 and the left unit counts they use
+    const int a0 = a_wg0 + wave * 8, a1 = imin(a_wg1, a0 + 7);
+    const int mw0 = imax(mA0, a0 - B_hi), mw1 = imin(mA1, a1 - B_lo);
+    const bool wave_work = work && a0 <= a_wg1 && mw0 <= mw1;
+
+    double best[8];
+    int bestk[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { best[q] = kNone; bestk[q] = 0; }
+
+    if (work) {
+        for (int e = threadIdx.x; e < TS; e += blockDim.x) { // the "no such table" slot
+            s_pair[dummy * TS + e] = make_double2(kNone, kNone);
+            s_tm[dummy * TS + e] = 0.0;
+        }
+        const double cl = t.sh.Nb > 0 ? -(double)r : 3.0 * r, cr = t.sh.Nb > 0 ? 0.0 : 4.0 * s;
+        const long long tabA = t.lvl_tab[s] - dlo_of(s, M) + fam_base, tabB = t.lvl_tab[r] - dlo_of(r, M) + fam_base;
+        const int fillA = nA * TS, fill = (nA + nB) * TS;
+        for (int kc = (kmin / PC) * PC; kc <= kmax; kc += PC) {
+            __syncthreads(); // previous pass fully consumed
+            for (int e = threadIdx.x; e < fill; e += blockDim.x) {
+                if (e < fillA) {       // left child (s, u, k, m): row u of block (ub, k/8)
+                    const int tab = e / TS, rem = e - tab * TS, u_l = rem / PC, k_l = rem - u_l * PC;
+                    const int k = kc + k_l;
+                    const Rec a = t.rec[(tabA + mA0 + tab) * t.tab_recs + (long long)tri_index(ub, k >> 3, t.NB) * 64 +
+                                        (u_l << 3) + (k & 7)];
+                    const int o = (tab * PC + k_l) * 8 + u_l;
+                    s_pair[o] = make_double2(a.T + cl * a.tmax, a.T1);
+                    s_tm[o] = a.tmax;
+                } else {               // right child (r, k, v, m'): row k of block (k/8, vb)
+                    const int e2 = e - fillA, tab = e2 / TS, rem = e2 - tab * TS, k_l = rem >> 3, v_l = rem & 7;
+                    const int k = kc + k_l;
+                    const Rec b = t.rec[(tabB + mB0 + tab) * t.tab_recs + (long long)tri_index(k >> 3, vb, t.NB) * 64 +
+                                        ((k & 7) << 3) + v_l];
+                    const int o = ((nA + tab) * PC + k_l) * 8 + v_l;
+                    s_pair[o] = make_double2(2.0 * b.T1, b.T + cr * b.tmax);
+                    s_tm[o] = b.tmax;
+                }
+            }
+            __syncthreads();
+            if (!wave_work) continue;
+#pragma unroll 1
+            for (int kl = 0; kl < PC; ++kl) {
+                const int k = kc + kl;
+                if (k < kmin || k > kmax) continue;
+                double cur[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) cur[q] = kNone;
+#pragma unroll 1
+                for (int mm = mw0; mm <= mw1; mm += 8) {
+                    double apa[8], at1[8], atm[8], bb2[15], bbt[15], btm[15];
+#pragma unroll
+                    for (int qm = 0; qm < 8; ++qm) {
+                        const int m = mm + qm;
+                        const int tab = m <= mA1 ? m - mA0 : dummy;
+                        const int o = (tab * PC + kl) * 8 + ul;
+                        const double2 p = s_pair[o];
+                        apa[qm] = p.x; at1[qm] = p.y; atm[qm] = s_tm[o];
+                    }
+#pragma unroll
+                    for (int d = 0; d < 15; ++d) {
+                        const int mp = a0 - mm - 7 + d; // m' = (a0 + qa) - (mm + qm), d = qa - qm + 7
+                        const int tab = (mp >= mB0 && mp <= mB1) ? nA + mp - mB0 : dummy;
+                        const int o = (tab * PC + kl) * 8 + vl;
+                        const double2 p = s_pair[o];
+                        bb2[d] = p.x; bbt[d] = p.y; btm[d] = s_tm[o];
+                    }
+#pragma unroll
+                    for (int qm = 0; qm < 8; ++qm)
+#pragma unroll
+                        for (int qa = 0; qa < 8; ++qa) {
+                            const int d = qa - qm + 7;
+                            const double T = atm[qm] >= btm[d] ? apa[qm] + bb2[d] : at1[qm] + bbt[d];
+                            cur[qa] = fmin(cur[qa], T);
+                        }
+                }
+#pragma unroll
+                for (int q = 0; q < 8; ++q) { // first k that reaches the minimum
+                    const bool lt = cur[q] < best[q];
+                    best[q] = lt ? cur[q] : best[q];
+                    bestk[q] = lt ? k : bestk[q];
                 }
             }
         }
     }
-    double T1 = kNone, tm = 0.0, T3 = 0.0;
+    if (a0 <= a_wg1) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            if (a0 + q > a_wg1) break;
+            const int aidx = fam_base + a0 + q - dlo_of(Sp, M);
+            const long long slot = ((long long)(s - 1) * NAall + aidx) * NT + blockIdx.x;
+            t.partT[slot * 64 + lane] = best[q];
+            t.partK[slot * 64 + lane] = bestk[q];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Levels S' >= 2, second kernel: grid (block of the plane, delta), one lane per state.
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(64) k_select(Tables t, int Sp, int NT, int NAall) {
+    const int L = t.sh.L, M = t.sh.M, lane = threadIdx.x;
+    int ub, vb;
+    tile_decode(L, Sp, blockIdx.x, &ub, &vb);
+    const int aidx = blockIdx.y, delta = dlo_of(Sp, M) + aidx;
+    const int u = ub * 8 + (lane >> 3), v = vb * 8 + (lane & 7);
+    double best = kNone;
+    int bs = 0, bk = 0;
+    for (int s = 1; s < Sp; ++s) { // first s with the smallest minimum
+        const long long o = (((long long)(s - 1) * NAall + aidx) * NT + blockIdx.x) * 64 + lane;
+        const double T = t.partT[o];
+        if (T < best) { best = T; bs = s; bk = t.partK[o]; }
+    }
+    Rec out = {kNone, kNone, 0.0, 0.0};
     int ks = 0, ch = 0;
     if (best < kNone) {
         const Family fam = family_of(delta, M);
-        const long long oa = elem(t, bs, fam.fam_base + bm, i, bp);
-        const long long ob = elem(t, Sp - bs, fam.fam_base + fam.units - bm, bp + bs, j + bs);
-        T1 = t.T1[oa] + t.T1[ob];
-        if (t.tmax[oa] >= t.tmax[ob]) { tm = t.tmax[oa]; ks = t.kstar[oa]; T3 = t.T3[oa] + t.T1[ob]; }
-        else                          { tm = t.tmax[ob]; ks = bs + t.kstar[ob]; T3 = t.T3[ob]; }
-        ch = bs | ((bp + bs) << 10) | (bm << 21);
+        const int r = Sp - bs;
+        int mlo, mhi;
+        m_range(fam.fam, fam.units, bs, r, M, t.sh.n_max, &mlo, &mhi);
+        const double cl = t.sh.Nb > 0 ? -(double)r : 3.0 * r, cr = t.sh.Nb > 0 ? 0.0 : 4.0 * bs;
+        int bm = 0;
+        Rec a = out, b = out;
+        for (int m = mlo; m <= mhi; ++m) { // first m whose candidate equals the minimum
+            a = t.rec[rec_index(t, bs, fam.fam_base + m, u, bk)];
+            b = t.rec[rec_index(t, r, fam.fam_base + fam.units - m, bk, v)];
+            const double T = a.tmax >= b.tmax ? (a.T + cl * a.tmax) + 2.0 * b.T1 : a.T1 + (b.T + cr * b.tmax);
+            if (T == best) { bm = m; break; }
+        }
+        if (bm == 0) {
+#ifdef OOB_EMU_DEBUG
+            fprintf(stderr, "select fail Sp=%d delta=%d u=%d v=%d best=%g bs=%d bk=%d mlo=%d mhi=%d\n", Sp, delta, u, v, best, bs, bk, mlo, mhi);
+#endif
+            *t.status = kInternalError;
+        } else {
+            const long long oa = rec_index(t, bs, fam.fam_base + bm, u, bk);
+            const long long ob = rec_index(t, r, fam.fam_base + fam.units - bm, bk, v);
+            out.T = best;
+            out.T1 = a.T1 + b.T1;                                                                // Eq. 1
+            if (a.tmax >= b.tmax) { out.tmax = a.tmax; ks = t.kstar[oa]; out.T3 = a.T3 + b.T1; } // Eq. 3
+            else                  { out.tmax = b.tmax; ks = bs + t.kstar[ob]; out.T3 = b.T3; }
+            ch = bs | (bk << 10) | (bm << 21);
+        }
     }
-    t.T[o] = best; t.T1[o] = T1; t.tmax[o] = tm; t.T3[o] = T3;
-    t.kstar[o] = ks; t.choice[o] = ch;
+    const long long o = rec_index(t, Sp, delta, ub * 8, vb * 8) + lane;
+    t.rec[o] = out;
+    t.kstar[o] = ks;
+    t.choice[o] = ch;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -218,7 +371,7 @@ __global__ void k_pick(Tables t, oob_templates out) {
     if (n <= t.sh.n_max)
         for (int S = n; S <= t.sh.Smax; ++S) {
             if (delta < dlo_of(S, M) || delta > dhi_of(S, M, t.sh.n_max)) continue;
-            const double T = t.T[elem(t, S, delta, 0, L - S)];
+            const double T = t.rec[rec_index(t, S, delta, 0, L)].T;
             if (T < best) { best = T; bestS = S; }
         }
     out.feasible[i] = bestS > 0;
@@ -226,9 +379,10 @@ __global__ void k_pick(Tables t, oob_templates out) {
     long long T = 0, T1 = 0, T2 = 0, T3 = 0, tm = 0;
     int ks = 0;
     if (bestS > 0) {
-        const long long o = elem(t, bestS, delta, 0, L - bestS);
-        T = (long long)best; T1 = (long long)t.T1[o]; T3 = (long long)t.T3[o];
-        tm = (long long)t.tmax[o]; ks = t.kstar[o];
+        const long long o = rec_index(t, bestS, delta, 0, L);
+        const Rec r = t.rec[o];
+        T = (long long)best; T1 = (long long)r.T1; T3 = (long long)r.T3; tm = (long long)r.tmax;
+        ks = t.kstar[o];
         const long long nb = t.sh.Nb > 0 ? t.sh.Nb : 4LL * bestS;
         T2 = (nb - bestS + ks - 1) * tm; // Eq. 2
     }
@@ -241,8 +395,8 @@ __global__ void k_backtrack(Tables t, oob_templates out) {
     if (i > t.sh.count) return;
     int off = 0;
     for (int q = 0; q < i && q < t.sh.count; ++q) off += out.S[q];
-    if (i == t.sh.count) { out.stage_off[i] = off; return; }
     out.stage_off[i] = off;
+    if (i == t.sh.count) return;
     const int S = out.S[i];
     if (S == 0) return;
     const int L = t.sh.L, M = t.sh.M;
@@ -259,10 +413,10 @@ __global__ void k_backtrack(Tables t, oob_templates out) {
             ++pos;
             continue;
         }
-        const int ch = t.choice[elem(t, Sq, delta, u, v - Sq)];
+        const int ch = t.choice[rec_index(t, Sq, delta, u, v)];
         const int s = ch & 1023, k = (ch >> 10) & 2047, m = (ch >> 21) & 1023;
         const Family fam = family_of(delta, M);
-        if (sp + 2 > t.sh.Smax + 1) break; // cannot happen: pending stages never exceed S
+        if (sp + 2 > t.sh.Smax + 1 || s < 1 || s >= Sq) { *t.status = kInternalError; break; }
         // right half first so that the left half is expanded first
         stk[sp * 4] = Sq - s; stk[sp * 4 + 1] = fam.fam_base + fam.units - m; stk[sp * 4 + 2] = k; stk[sp * 4 + 3] = v; ++sp;
         stk[sp * 4] = s; stk[sp * 4 + 1] = fam.fam_base + m; stk[sp * 4 + 2] = u; stk[sp * 4 + 3] = k; ++sp;
@@ -273,7 +427,7 @@ __global__ void k_backtrack(Tables t, oob_templates out) {
 // ---------------------------------------------------------------------------------------
 // Node specification and coverage (Section 4.1.1, Appendix A): one thread; the sizes are a
 // run of consecutive integers, so "largest pipeline count summing to x" is a coin-change
-// recursion over at most N <= n_max (f + 1) entries held in the backtracking scratch.
+// recursion; x only looks back n_hi entries, so a ring in the backtracking scratch holds it.
 // ---------------------------------------------------------------------------------------
 __global__ void k_coverage(Tables t, oob_templates out, int len) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
@@ -289,7 +443,6 @@ __global__ void k_coverage(Tables t, oob_templates out, int len) {
     const int N = n_hi + f * n0;
     const int lo_thm = (f + 1) * n0, lo_tail = N - f < 1 ? 1 : N - f;
     const int lo = lo_thm < lo_tail ? lo_thm : lo_tail;
-    // best[x mod (n_hi+1)]: a ring is enough because x only looks back n_hi entries
     int *best = t.stack; // free again: k_backtrack has finished
     const int ring = n_hi + 1;
     int thm = 1, tail = 1;
@@ -312,50 +465,78 @@ __global__ void k_coverage(Tables t, oob_templates out, int len) {
     out.cover_hdr[4] = p > n0 - 1; out.cover_hdr[5] = lo; out.cover_hdr[6] = thm; out.cover_hdr[7] = tail;
 }
 
+// Copies one table into dense n x n arrays, n = L-S'+1, entry [u][v - S'] (tests only).
+__global__ void k_export(Tables t, int S, int delta, double *T, double *T1, double *tmax, double *T3,
+                         int *kstar, int *choice) {
+    const int n = t.sh.L - S + 1;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n * n) return;
+    const int u = idx / n, j = idx % n, v = j + S;
+    Rec r = {kNone, kNone, 0.0, 0.0};
+    int ks = 0, ch = 0;
+    if (j >= u) {
+        const long long o = rec_index(t, S, delta, u, v);
+        r = t.rec[o]; ks = t.kstar[o]; ch = t.choice[o];
+    }
+    T[idx] = r.T; T1[idx] = r.T1; tmax[idx] = r.tmax; T3[idx] = r.T3; kstar[idx] = ks; choice[idx] = ch;
+}
+
 // ---------------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------------
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// Elements of all level blocks for a shape.
-long long table_elems(int L, int M, int n_max, int Nb) {
+long long table_count(int L, int M, int n_max, int Nb) {
     const int Smax = smax_of(L, n_max, M, Nb);
     long long e = 0;
     for (int S = 1; S <= Smax; ++S) {
-        const int n = L - S + 1, nd = dhi_of(S, M, n_max) - dlo_of(S, M) + 1;
-        if (nd > 0) e += (long long)nd * n * n;
+        const int nd = dhi_of(S, M, n_max) - dlo_of(S, M) + 1;
+        if (nd > 0) e += nd;
     }
     return e;
 }
 
+// Largest (S'-1) * deltas * tiles over the levels: slots of the per-split minima.
+long long part_slots(int L, int M, int n_max, int Nb) {
+    const int Smax = smax_of(L, n_max, M, Nb);
+    long long best = 1;
+    for (int S = 2; S <= Smax; ++S) {
+        const long long nd = dhi_of(S, M, n_max) - dlo_of(S, M) + 1;
+        if (nd <= 0) continue;
+        const long long sl = (long long)(S - 1) * nd * tile_count(L, S);
+        if (sl > best) best = sl;
+    }
+    return best;
+}
+
 struct Carve {
-    size_t lvl_base, PT, PF, PM, T, T1, tmax, T3, kstar, choice, stack, total;
+    size_t lvl_tab, PT, PF, PM, rec, kstar, choice, partT, partK, stack, total;
+    long long recs, slots;
 };
-// Byte offsets of the workspace arrays; sized for the handle's maxima so that a call with a
-// smaller shape uses a prefix of each array.
+// Byte offsets of the workspace arrays, sized for the handle's maxima.
 Carve carve(int L, int nodes, int M) {
     Carve c;
-    const long long E = table_elems(L, M, nodes, 0);
+    c.recs = table_count(L, M, nodes, 0) * tri_blocks(nblocks_of(L)) * 64;
+    c.slots = part_slots(L, M, nodes, 0);
+    const size_t E = (size_t)c.recs;
     const int Smax = smax_of(L, nodes, M, 0);
     size_t o = 0;
-    c.lvl_base = o; o = align_up(o + sizeof(long long) * (OOB_MAX_L + 3));
-    c.PT = o;       o = align_up(o + sizeof(long long) * (size_t)(M + 1) * (L + 1));
-    c.PF = o;       o = align_up(o + sizeof(int) * (size_t)(M + 1) * (L + 1));
-    c.PM = o;       o = align_up(o + sizeof(long long) * (size_t)(L + 1));
-    c.T = o;        o = align_up(o + sizeof(double) * (size_t)E);
-    c.T1 = o;       o = align_up(o + sizeof(double) * (size_t)E);
-    c.tmax = o;     o = align_up(o + sizeof(double) * (size_t)E);
-    c.T3 = o;       o = align_up(o + sizeof(double) * (size_t)E);
-    c.kstar = o;    o = align_up(o + sizeof(int) * (size_t)E);
-    c.choice = o;   o = align_up(o + sizeof(int) * (size_t)E);
-    c.stack = o;    o = align_up(o + sizeof(int) * (size_t)nodes * (Smax + 1) * 4 + sizeof(int) * (size_t)(nodes + 2));
+    c.lvl_tab = o; o = align_up(o + sizeof(long long) * (OOB_MAX_L + 3));
+    c.PT = o;      o = align_up(o + sizeof(long long) * (size_t)(M + 1) * (L + 1));
+    c.PF = o;      o = align_up(o + sizeof(int) * (size_t)(M + 1) * (L + 1));
+    c.PM = o;      o = align_up(o + sizeof(long long) * (size_t)(L + 1));
+    c.rec = o;     o = align_up(o + sizeof(Rec) * E);
+    c.kstar = o;   o = align_up(o + sizeof(int) * E);
+    c.choice = o;  o = align_up(o + sizeof(int) * E);
+    c.partT = o;   o = align_up(o + sizeof(double) * (size_t)c.slots * 64);
+    c.partK = o;   o = align_up(o + sizeof(int) * (size_t)c.slots * 64);
+    c.stack = o;   o = align_up(o + sizeof(int) * ((size_t)nodes * (Smax + 1) * 4 + nodes + 2));
     c.total = o;
     return c;
 }
 
-// Structural work counts: states = records with v - u >= S'; candidates = (s, k, m) with both
-// children valid.  A block with n = L-S'+1 has n(n+1)/2 states and n(n+1)(n+2)/6 (u, k, v)
-// triples per (s, m).
+// Structural work counts: states = (u, v) with v - u >= S' per table; candidates = (s, k, m)
+// with both children valid: per (s, m) pair one per (u, k, v), u + s <= k <= v - r.
 void work_counts(const Shape &sh, long long *states, long long *cands) {
     long long st = 0, ca = 0;
     for (int S = 1; S <= sh.Smax; ++S) {
@@ -368,13 +549,44 @@ void work_counts(const Shape &sh, long long *states, long long *cands) {
             long long pairs = 0;
             for (int s = 1; s < S; ++s) {
                 int lo, hi;
-                m_range(fam.fam_base, fam.units, s, S - s, sh.M, &lo, &hi);
+                m_range(fam.fam, fam.units, s, S - s, sh.M, sh.n_max, &lo, &hi);
                 if (hi >= lo) pairs += hi - lo + 1;
             }
             ca += pairs * (n * (n + 1) * (n + 2) / 6);
         }
     }
     *states = st; *cands = ca;
+}
+
+constexpr size_t kLdsLimit = 160 * 1024; // gfx950: 160 KB of LDS per workgroup
+constexpr size_t kLdsPrefer = 64 * 1024; // at least two workgroups per compute unit
+
+// Launch shape of k_split for one family of one level.
+struct SplitPlan { int waves, groups, pc; size_t lds; };
+bool plan_split(const Shape &sh, int Sp, int fam, SplitPlan *p) {
+    int t_lo, t_hi;
+    target_units(fam, Sp, sh.M, sh.n_max, &t_lo, &t_hi);
+    if (fam == 0 && Sp > sh.M) return false;
+    if (t_hi < t_lo) return false;
+    const int cnt = t_hi - t_lo + 1;
+    p->waves = imin(8, cdiv(cnt, 8));
+    p->groups = cdiv(cnt, 8 * p->waves);
+    int ntab = 1;
+    for (int s = 1; s < Sp; ++s) {
+        int A_lo, A_hi, B_lo, B_hi;
+        child_units(fam, s, sh.M, sh.n_max, &A_lo, &A_hi);
+        child_units(fam, Sp - s, sh.M, sh.n_max, &B_lo, &B_hi);
+        for (int g = 0; g < p->groups; ++g) {
+            const int a0 = t_lo + g * p->waves * 8, a1 = imin(t_hi, a0 + p->waves * 8 - 1);
+            const int mA0 = imax(A_lo, a0 - B_hi), mA1 = imin(A_hi, a1 - B_lo);
+            const int mB0 = imax(B_lo, a0 - A_hi), mB1 = imin(B_hi, a1 - A_lo);
+            if (mA0 <= mA1 && mB0 <= mB1) ntab = imax(ntab, mA1 - mA0 + 1 + mB1 - mB0 + 1 + 1);
+        }
+    }
+    const size_t per_k = (size_t)ntab * 8 * 24;
+    p->pc = per_k * 4 <= kLdsPrefer ? 4 : per_k * 2 <= kLdsPrefer ? 2 : 1;
+    p->lds = per_k * p->pc;
+    return true;
 }
 
 } // namespace oob
@@ -386,8 +598,7 @@ struct oob_plan {
     char *ws;
     size_t ws_bytes;
     Carve cv;
-    long long max_elems; // capacity of each table array, in records
-    Shape last;       // shape of the last call (for oob_plan_block)
+    Shape last;       // shape of the last call (for oob_plan_export_block)
     bool have_last;
     hipEvent_t ev_begin, ev_end; // optional: recorded around the level launches
     bool timed;
@@ -429,32 +640,33 @@ extern "C" int oob_plan_create(oob_plan **h, int max_L, int max_nodes, int max_g
     p->max_L = max_L; p->max_nodes = max_nodes; p->max_M = max_gpus_per_node;
     p->ws = (char *)dev_workspace; p->ws_bytes = workspace_bytes; p->cv = cv; p->have_last = false;
     p->ev_begin = nullptr; p->ev_end = nullptr; p->timed = false;
-    p->max_elems = table_elems(max_L, max_gpus_per_node, max_nodes, 0);
     *h = p;
     return OOB_OK;
 }
 
 extern "C" int oob_plan_destroy(oob_plan *h) {
     if (!h) return OOB_EINVAL;
-    if (h->ev_begin) { hipEventDestroy(h->ev_begin); hipEventDestroy(h->ev_end); }
+    if (h->ev_begin) { (void)hipEventDestroy(h->ev_begin); (void)hipEventDestroy(h->ev_end); }
     delete h;
     return OOB_OK;
 }
 
-static Tables make_tables(const oob_plan *h, const Shape &sh) {
+static Tables make_tables(const oob_plan *h, const Shape &sh, int *status) {
     Tables t;
     t.sh = sh;
-    t.lvl_base = (long long *)(h->ws + h->cv.lvl_base);
+    t.NB = nblocks_of(sh.L);
+    t.tab_recs = tri_blocks(t.NB) * 64;
+    t.lvl_tab = (long long *)(h->ws + h->cv.lvl_tab);
     t.PT = (long long *)(h->ws + h->cv.PT);
     t.PF = (int *)(h->ws + h->cv.PF);
     t.PM = (long long *)(h->ws + h->cv.PM);
-    t.T = (double *)(h->ws + h->cv.T);
-    t.T1 = (double *)(h->ws + h->cv.T1);
-    t.tmax = (double *)(h->ws + h->cv.tmax);
-    t.T3 = (double *)(h->ws + h->cv.T3);
+    t.rec = (Rec *)(h->ws + h->cv.rec);
     t.kstar = (int *)(h->ws + h->cv.kstar);
     t.choice = (int *)(h->ws + h->cv.choice);
+    t.partT = (double *)(h->ws + h->cv.partT);
+    t.partK = (int *)(h->ws + h->cv.partK);
     t.stack = (int *)(h->ws + h->cv.stack);
+    t.status = status;
     return t;
 }
 
@@ -462,6 +674,16 @@ static bool out_ok(const oob_templates *o) {
     return o && o->feasible && o->S && o->kstar && o->T && o->T1 && o->T2 && o->T3 && o->tmax &&
            o->stage_off && o->stage_begin && o->stage_gpus && o->cover_hdr && o->cover_maxpipes &&
            o->status;
+}
+
+template <int PC>
+static void launch_split(const Tables &t, int S, int fam, const SplitPlan &sp, int NT, int NAall,
+                         hipStream_t st) {
+    if (sp.lds > kLdsPrefer) // beyond the default dynamic-LDS limit of a launch
+        (void)hipFuncSetAttribute((const void *)k_split<PC>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)kLdsLimit);
+    hipLaunchKernelGGL(k_split<PC>, dim3(NT, S - 1, sp.groups), dim3(sp.waves * 64), sp.lds, st, t, S, fam,
+                       NT, NAall);
 }
 
 extern "C" int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L, int n_min, int n_max,
@@ -473,28 +695,40 @@ extern "C" int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L
         return OOB_EINVAL;
     if (L > h->max_L || n_max > h->max_nodes || gpus_per_node > h->max_M) return OOB_ECAPACITY;
     if ((long long)n_max * ((long long)f + 1) > (1 << 24)) return OOB_ECAPACITY;
+    const int M = gpus_per_node;
+    if (table_count(L, M, n_max, microbatches) * tri_blocks(nblocks_of(L)) * 64 > h->cv.recs ||
+        part_slots(L, M, n_max, microbatches) > h->cv.slots)
+        return OOB_ECAPACITY;
     Shape sh;
-    sh.L = L; sh.M = gpus_per_node; sh.n_min = n_min; sh.n_max = n_max; sh.Nb = microbatches; sh.f = f;
+    sh.L = L; sh.M = M; sh.n_min = n_min; sh.n_max = n_max; sh.Nb = microbatches; sh.f = f;
     sh.cap = mem_cap; sh.count = n_max - n_min + 1;
-    sh.Smax = smax_of(L, n_max, gpus_per_node, microbatches);
-    if (table_elems(L, gpus_per_node, n_max, microbatches) > h->max_elems) return OOB_ECAPACITY;
-    const Tables t = make_tables(h, sh);
+    sh.Smax = smax_of(L, n_max, M, microbatches);
+    // launch shapes first, so that nothing is enqueued when a level cannot be staged in LDS
+    for (int S = 2; S <= sh.Smax; ++S)
+        for (int fam = 0; fam < 2; ++fam) {
+            SplitPlan sp;
+            if (plan_split(sh, S, fam, &sp) && sp.lds > kLdsLimit) return OOB_ECAPACITY;
+        }
+    const Tables t = make_tables(h, sh, (int *)out->status);
     hipStream_t st = (hipStream_t)stream;
     work_counts(sh, (long long *)&out->states, (long long *)&out->candidates);
 
-    hipLaunchKernelGGL(k_setup, dim3(1), dim3(OOB_MAX_GPUS + 1), 0, st, t, *profile, out->status);
-    {
-        const long long total = (long long)sh.M * L * L;
-        hipLaunchKernelGGL(k_level1, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, t,
-                           (const long long *)profile->boundary_ns);
-    }
+    hipLaunchKernelGGL(k_setup, dim3(1), dim3(OOB_MAX_GPUS + 1), 0, st, t, *profile);
+    hipLaunchKernelGGL(k_level1, dim3(tile_count(L, 1), M), dim3(64), 0, st, t,
+                       (const long long *)profile->boundary_ns);
     if (h->ev_begin) OOB_HIP_CHECK(hipEventRecord(h->ev_begin, st));
     for (int S = 2; S <= sh.Smax; ++S) {
-        const long long n = L - S + 1;
-        const int nd = dhi_of(S, sh.M, sh.n_max) - dlo_of(S, sh.M) + 1;
-        if (nd <= 0) continue;
-        const long long total = nd * n * n;
-        hipLaunchKernelGGL(k_combine_simple, dim3((unsigned)((total + 63) / 64)), dim3(64), 0, st, t, S);
+        const int NAall = dhi_of(S, M, n_max) - dlo_of(S, M) + 1;
+        if (NAall <= 0) continue;
+        const int NT = tile_count(L, S);
+        for (int fam = 0; fam < 2; ++fam) {
+            SplitPlan sp;
+            if (!plan_split(sh, S, fam, &sp)) continue;
+            if (sp.pc == 4) launch_split<4>(t, S, fam, sp, NT, NAall, st);
+            else if (sp.pc == 2) launch_split<2>(t, S, fam, sp, NT, NAall, st);
+            else launch_split<1>(t, S, fam, sp, NT, NAall, st);
+        }
+        hipLaunchKernelGGL(k_select, dim3(NT, NAall), dim3(64), 0, st, t, S, NT, NAall);
     }
     if (h->ev_end) { OOB_HIP_CHECK(hipEventRecord(h->ev_end, st)); h->timed = true; }
     hipLaunchKernelGGL(k_pick, dim3((sh.count + 63) / 64), dim3(64), 0, st, t, *out);
@@ -528,7 +762,7 @@ extern "C" int oob_plan_level_timing(oob_plan *h, int enable) {
         OOB_HIP_CHECK(hipEventCreate(&h->ev_begin));
         OOB_HIP_CHECK(hipEventCreate(&h->ev_end));
     } else if (!enable && h->ev_begin) {
-        hipEventDestroy(h->ev_begin); hipEventDestroy(h->ev_end);
+        (void)hipEventDestroy(h->ev_begin); (void)hipEventDestroy(h->ev_end);
         h->ev_begin = h->ev_end = nullptr;
     }
     h->timed = false;
@@ -542,23 +776,16 @@ extern "C" int oob_plan_last_level_ms(oob_plan *h, float *ms) {
     return OOB_OK;
 }
 
-extern "C" int oob_plan_block(const oob_plan *h, int S, int delta, oob_block_desc *desc) {
-    if (!h || !desc || !h->have_last) return OOB_EINVAL;
+extern "C" int oob_plan_export_block(oob_plan *h, int S, int delta, double *T, double *T1, double *tmax,
+                                     double *T3, int32_t *kstar, int32_t *choice, void *stream) {
+    if (!h || !h->have_last || !T || !T1 || !tmax || !T3 || !kstar || !choice) return OOB_EINVAL;
     const Shape &sh = h->last;
     if (S < 1 || S > sh.Smax) return OOB_EINVAL;
-    const int dlo = dlo_of(S, sh.M), dhi = dhi_of(S, sh.M, sh.n_max);
-    if (delta < dlo || delta > dhi) return OOB_EINVAL;
-    long long base = 0;
-    for (int q = 1; q < S; ++q) {
-        const long long n = sh.L - q + 1;
-        const int nd = dhi_of(q, sh.M, sh.n_max) - dlo_of(q, sh.M) + 1;
-        if (nd > 0) base += nd * n * n;
-    }
-    const long long n = sh.L - S + 1;
-    desc->n = (int32_t)n;
-    desc->elem_off = base + (long long)(delta - dlo) * n * n;
-    desc->T_bytes = (int64_t)h->cv.T; desc->T1_bytes = (int64_t)h->cv.T1;
-    desc->tmax_bytes = (int64_t)h->cv.tmax; desc->T3_bytes = (int64_t)h->cv.T3;
-    desc->kstar_bytes = (int64_t)h->cv.kstar; desc->choice_bytes = (int64_t)h->cv.choice;
+    if (delta < dlo_of(S, sh.M) || delta > dhi_of(S, sh.M, sh.n_max)) return OOB_EINVAL;
+    const Tables t = make_tables(h, sh, nullptr);
+    const int n = sh.L - S + 1;
+    hipLaunchKernelGGL(k_export, dim3((n * n + 255) / 256), dim3(256), 0, (hipStream_t)stream, t, S, delta, T,
+                       T1, tmax, T3, (int *)kstar, (int *)choice);
+    OOB_HIP_CHECK(hipGetLastError());
     return OOB_OK;
 }

@@ -32,8 +32,8 @@ def test_max_stages_and_workspace_size():
     assert P.oob_plan_max_stages(0, 1, 1, 1) == P.OOB_EINVAL
     small, big = P.oob_plan_workspace_size(12, 4, 1), P.oob_plan_workspace_size(98, 64, 8)
     assert 0 < small < big
-    # four double and two int32 arrays per table record, 2 * 3724666-ish padded records
-    assert 250e6 < big < 400e6
+    # 40 bytes per record slot of the blocked (u, v) planes plus the per-split minima
+    assert 0.5e9 < big < 2e9
     assert P.oob_plan_workspace_size(2000, 4, 1) == 0  # beyond OOB_MAX_L
 
 
@@ -66,6 +66,5 @@ def test_create_and_call_reject_bad_arguments_without_touching_the_gpu():
     assert call(M=2) == P.OOB_ECAPACITY
     out.status = None
     assert call() == P.OOB_EINVAL  # null output pointer
-    d = B.oob_block_desc()
-    assert P.load().oob_plan_block(h, 1, 0, C.byref(d)) == P.OOB_EINVAL  # no call yet
+    assert P.load().oob_plan_export_block(h, 1, 0, 1, 1, 1, 1, 1, 1, None) == P.OOB_EINVAL  # no call yet
     assert P.oob_plan_destroy(h) == P.OOB_OK
