@@ -141,6 +141,12 @@ int oob_plan_last_level_ms(oob_plan *h, float *ms /* HOST */);
 int oob_plan_export_block(oob_plan *h, int S, int delta, double *T, double *T1, double *tmax,
                           double *T3, int32_t *kstar, int32_t *choice, void *stream);
 
+/* Introspection for tests: copies four int32 flags of the last call to a DEVICE array.
+ * flags[0] = 1 when every (total, split point) pair fitted one double key, so that the keyed
+ * split kernel did the levels S' >= 2; 0 when the plain split kernel did (totals near the top
+ * of the exact range).  Both give identical results.  flags[1..3] are reserved. */
+int oob_plan_export_flags(oob_plan *h, int32_t *flags, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,7 @@ _ERR = {OOB_EINVAL: "OOB_EINVAL", OOB_ECAPACITY: "OOB_ECAPACITY", OOB_EOVERFLOW:
 
 SYMBOLS = ["oob_plan_max_stages", "oob_plan_workspace_size", "oob_plan_create",
            "oob_plan_templates", "oob_plan_templates_batch", "oob_plan_destroy", "oob_plan_export_block",
-           "oob_plan_level_timing", "oob_plan_last_level_ms"]
+           "oob_plan_level_timing", "oob_plan_last_level_ms", "oob_plan_export_flags"]
 
 
 class oob_profile(C.Structure):
@@ -70,6 +70,8 @@ def load():
         L.oob_plan_level_timing.restype = C.c_int
         L.oob_plan_last_level_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         L.oob_plan_last_level_ms.restype = C.c_int
+        L.oob_plan_export_flags.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oob_plan_export_flags.restype = C.c_int
         L.oob_plan_export_block.argtypes = [C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 7
         L.oob_plan_export_block.restype = C.c_int
         _lib = L
@@ -209,6 +211,16 @@ class Planner:
         self.enqueue(prof, out)
         torch.cuda.synchronize(self.device)
         return out.to_host()
+
+    def flags(self):
+        """[keyed split kernel used, reserved x3] of the last call."""
+        import torch
+
+        buf = torch.zeros(4, dtype=torch.int32, device=self.device)
+        s = torch.cuda.current_stream(self.device)
+        check(load().oob_plan_export_flags(self.h, buf.data_ptr(), C.c_void_p(s.cuda_stream)),
+              "oob_plan_export_flags")
+        return buf.cpu().numpy().tolist()
 
     def block(self, S: int, delta: int) -> Optional[Dict[str, "object"]]:
         """Records of (S', delta) left by the last call, arrays [n, n] indexed [u, v - S']."""

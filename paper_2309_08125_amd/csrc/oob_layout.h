@@ -83,6 +83,13 @@ __host__ __device__ inline void target_units(int fam, int S, int M, int n_max, i
     else          { *lo = imax(2, cdiv(S, M)); *hi = imin(S, n_max); }
 }
 
+// Bits that hold a split point k <= L.
+__host__ __device__ inline int key_bits(int L) {
+    int b = 1;
+    while ((1 << b) <= L) ++b;
+    return b;
+}
+
 // ---- blocked (u, v) plane ----------------------------------------------------------------
 __host__ __device__ inline int nblocks_of(int L) { return L / 8 + 1; } // v runs 0..L
 __host__ __device__ inline int tri_blocks(int NB) { return NB * (NB + 1) / 2; }
@@ -108,6 +115,33 @@ __host__ __device__ inline void tile_decode(int L, int S, int t, int *ub, int *v
         t -= c;
     }
     *ub = 0; *vb = 0;
+}
+
+// Split points k of a block of the plane at level S': kmin = 8 ub + s .. kmax = vmax - (S' - s),
+// vmax = min(8 vb + 7, L): their number does not depend on s.  The keyed split kernel cuts
+// this range into segments of kSegK consecutive k, one workgroup each.
+constexpr int kSegK = 8;
+__host__ __device__ inline int tile_krange(int L, int S, int ub, int vb) {
+    return imin(vb * 8 + 7, L) - ub * 8 - S + 1;
+}
+__host__ __device__ inline int seg_count(int L, int S) { // over all blocks of the level
+    const int NB = nblocks_of(L), ubmax = (L - S) / 8;
+    int c = 0;
+    for (int d = NB - 1; d >= tile_dmin(S); --d)
+        for (int ub = 0; ub <= imin(ubmax, NB - 1 - d); ++ub) c += cdiv(tile_krange(L, S, ub, ub + d), kSegK);
+    return c;
+}
+// g-th segment of the level -> block (ub, vb), its index t in tile order, segment j of it.
+__host__ __device__ inline void seg_decode(int L, int S, int g, int *t, int *ub, int *vb, int *j) {
+    const int NB = nblocks_of(L), ubmax = (L - S) / 8;
+    int tt = 0;
+    for (int d = NB - 1; d >= tile_dmin(S); --d)
+        for (int u = 0; u <= imin(ubmax, NB - 1 - d); ++u, ++tt) {
+            const int c = cdiv(tile_krange(L, S, u, u + d), kSegK);
+            if (g < c) { *t = tt; *ub = u; *vb = u + d; *j = g; return; }
+            g -= c;
+        }
+    *t = 0; *ub = 0; *vb = 0; *j = 0;
 }
 
 } // namespace oob

@@ -58,8 +58,10 @@ struct Tables {
     Rec *rec;             // [tables * tab_recs]
     int *kstar, *choice;  // [tables * tab_recs]
     double *partT;        // [(S'-1) * deltas * tiles * 64] per-split minima of the current level
+    unsigned long long *partKey; // the same memory: keys total * 2^kbits + k (keyed kernel)
     int *partK;           // same shape: first k reaching the minimum
     int *stack;           // backtracking stacks / coverage ring
+    int *flags;           // [0] 1: (total, k) keys fit a double (k_split_key runs), 0: k_split runs
     int *status;
 };
 
@@ -137,7 +139,10 @@ __global__ void k_setup(Tables t, oob_profile prof) {
             const long long nb = t.sh.Nb > 0 ? t.sh.Nb : 4LL * t.sh.Smax;
             const long long mult = nb + 4LL * t.sh.Smax + 4;
             if (worst >= kExactBound / mult) st = OOB_EOVERFLOW;
+            // a total and a split point k <= L fit one double as total * 2^kbits + k
+            t.flags[0] = worst < (kExactBound >> key_bits(L)) / mult;
         }
+        if (st != OOB_OK) t.flags[0] = 0;
         *t.status = st;
     }
 }
@@ -187,6 +192,7 @@ __global__ void __launch_bounds__(64) k_level1(Tables t, const long long *X) {
 template <int PC>
 __global__ void __launch_bounds__(512) k_split(Tables t, int Sp, int fam, int NT, int NAall) {
     HIP_DYNAMIC_SHARED(double2, s_pair) // [ntab][PC][8] (x, y) pairs, then double tmax[ntab][PC][8]
+    if (t.flags[0] != 0) return;        // the keyed kernel handles this job
     const int L = t.sh.L, M = t.sh.M, n_max = t.sh.n_max;
     const int s = blockIdx.y + 1, r = Sp - s;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
@@ -307,6 +313,169 @@ __global__ void __launch_bounds__(512) k_split(Tables t, int Sp, int fam, int NT
 }
 
 // ---------------------------------------------------------------------------------------
+// Levels S' >= 2, first kernel, keyed variant (runs when flags[0] = 1).
+//
+// Same result as k_split, different mapping.  A workgroup owns (block of the plane, s) and a
+// group of up to kKeyTargets target sets; per chunk of k it stages the left records of every
+// m and the right records of every m' (padded to whole 8-blocks of m') in LDS.  Work items
+// are (k, 8-block of m'); the waves take them round robin.  An item keeps its 8 right records
+// in registers and streams m: step m forms the 8 candidates (m, m'0..m'0+7), which belong to
+// the 8 consecutive targets a = m + m'0 + i.  The 8 running minima rotate: after step m the
+// minimum of target m + m'0 is complete for this item and is merged into the workgroup's LDS
+// table acc[a][lane] with an integer atomic min on the bits of key = total * 2^kbits + k
+// (non-negative doubles order like their bit patterns).  The key makes the merge order-free
+// and yields, per (s, state), the smallest total and the first k reaching it at once.
+// ---------------------------------------------------------------------------------------
+constexpr int kKeyTargets = 64;
+constexpr int kFillBatch = 4; // records a thread has in flight while staging
+
+__global__ void __launch_bounds__(512) k_split_key(Tables t, int Sp, int fam, int NT, int NAall, int pcs) {
+    HIP_DYNAMIC_SHARED(double2, s_pair) // [nA + 8 nmb][PC][8] pairs | double tmax[same] | u64 acc[na][64]
+    if (t.flags[0] == 0) return;        // keys do not fit: k_split handles this job
+    const int L = t.sh.L, M = t.sh.M, n_max = t.sh.n_max;
+    const int s = blockIdx.y + 1, r = Sp - s;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int ul = lane >> 3, vl = lane & 7;
+    const int PC = 1 << pcs, TS = PC * 8;  // k values staged per pass, records per table and pass
+    int tile, ub, vb, seg;
+    seg_decode(L, Sp, blockIdx.x, &tile, &ub, &vb, &seg);
+    const int fam_base = fam ? M - 2 : -1;
+    int t_lo, t_hi;
+    target_units(fam, Sp, M, n_max, &t_lo, &t_hi);
+    const int a_g0 = t_lo + blockIdx.z * kKeyTargets, a_g1 = imin(t_hi, a_g0 + kKeyTargets - 1);
+    const int na = a_g1 - a_g0 + 1;
+    int A_lo, A_hi, B_lo, B_hi;
+    child_units(fam, s, M, n_max, &A_lo, &A_hi);
+    child_units(fam, r, M, n_max, &B_lo, &B_hi);
+    const int mA0 = imax(A_lo, a_g0 - B_hi), mA1 = imin(A_hi, a_g1 - B_lo);
+    const int mB0 = imax(B_lo, a_g0 - A_hi), mB1 = imin(B_hi, a_g1 - A_lo);
+    // this workgroup's segment of the split points of the block
+    const int kmin = ub * 8 + s + seg * kSegK, kmax = imin(imin(vb * 8 + 7, L) - r, kmin + kSegK - 1);
+    const bool work = mA0 <= mA1 && mB0 <= mB1 && kmin <= kmax;
+    if (!work) return;                  // nothing to merge: the keys stay "no such state"
+    const int nA = mA1 - mA0 + 1, nB = mB1 - mB0 + 1, nmb = cdiv(nB, 8);
+    const int ntab = nA + 8 * nmb;
+    double *s_tm = (double *)(s_pair + (size_t)ntab * TS);
+    unsigned long long *s_acc = (unsigned long long *)(s_tm + (size_t)ntab * TS);
+    const unsigned long long kNoneBits = 0x7FF0000000000000ull;
+    const int kbits = key_bits(L);
+    const double KS = (double)(1 << kbits);
+
+    for (int e = threadIdx.x; e < na * 64; e += blockDim.x) s_acc[e] = kNoneBits;
+    {
+        const double cl = t.sh.Nb > 0 ? -(double)r : 3.0 * r, cr = t.sh.Nb > 0 ? 0.0 : 4.0 * s;
+        const long long tabA = t.lvl_tab[s] - dlo_of(s, M) + fam_base, tabB = t.lvl_tab[r] - dlo_of(r, M) + fam_base;
+        const int fillA = nA * TS, fill = ntab * TS;
+        const int kb_lo = kmin >> 3, kb_hi = kmax >> 3; // 8-blocks of k that hold states of both children
+        for (int kc = (kmin >> pcs) << pcs; kc <= kmax; kc += PC) {
+            __syncthreads(); // previous pass fully consumed (first pass: acc initialised)
+            for (int e0 = threadIdx.x; e0 < fill; e0 += blockDim.x * kFillBatch) {
+                Rec rec[kFillBatch];
+#pragma unroll
+                for (int q = 0; q < kFillBatch; ++q) { // all loads of the batch first
+                    const int e = e0 + q * blockDim.x;
+                    rec[q] = Rec{kNone, kNone, 0.0, 0.0};
+                    if (e < fillA) {       // left child (s, u, k, m): row u of block (ub, k/8)
+                        const int tab = e / TS, rem = e - tab * TS, u_l = rem >> pcs, k = kc + (rem & (PC - 1));
+                        if ((k >> 3) >= kb_lo && (k >> 3) <= kb_hi)
+                            rec[q] = t.rec[(tabA + mA0 + tab) * t.tab_recs +
+                                           (long long)tri_index(ub, k >> 3, t.NB) * 64 + (u_l << 3) + (k & 7)];
+                    } else if (e < fill) { // right child (r, k, v, m'): row k of block (k/8, vb)
+                        const int e2 = e - fillA, tab = e2 / TS, rem = e2 - tab * TS, k = kc + (rem >> 3);
+                        if (tab < nB && (k >> 3) >= kb_lo && (k >> 3) <= kb_hi)
+                            rec[q] = t.rec[(tabB + mB0 + tab) * t.tab_recs +
+                                           (long long)tri_index(k >> 3, vb, t.NB) * 64 + ((k & 7) << 3) + (rem & 7)];
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < kFillBatch; ++q) {
+                    const int e = e0 + q * blockDim.x;
+                    if (e < fillA) {
+                        const int tab = e / TS, rem = e - tab * TS, u_l = rem >> pcs, k_l = rem & (PC - 1);
+                        const int o = (tab * PC + k_l) * 8 + u_l;
+                        s_pair[o] = make_double2(rec[q].T + cl * rec[q].tmax, rec[q].T1);
+                        s_tm[o] = rec[q].tmax;
+                    } else if (e < fill) { // same order in LDS as in the fill index: [table][k][v]
+                        s_pair[e] = make_double2(2.0 * rec[q].T1, rec[q].T + cr * rec[q].tmax);
+                        s_tm[e] = rec[q].tmax;
+                    }
+                }
+            }
+            __syncthreads();
+            const int kl0 = imax(0, kmin - kc), nk = imin(PC - 1, kmax - kc) - kl0 + 1;
+            for (int item = wave; item < nk * nmb; item += nw) {
+                const int kq = item / nmb, mb = item - kq * nmb, kl = kl0 + kq, k = kc + kl;
+                const int mp0 = mB0 + 8 * mb;                       // first m' of the block
+                const int mlo = imax(mA0, a_g0 - (mp0 + 7)), mhi = imin(mA1, a_g1 - mp0);
+                if (mlo > mhi) continue;
+                double bb2[8], bbt[8], btm[8], acc[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int o = ((nA + 8 * mb + i) * PC + kl) * 8 + vl;
+                    const double2 p = s_pair[o];
+                    bb2[i] = p.x; bbt[i] = p.y; btm[i] = s_tm[o];
+                    acc[i] = kNone;
+                }
+                const double kd = (double)k;
+                const int len = mhi - mlo + 1, j0 = (8 - (len & 7)) & 7;
+                int mbase = mlo - j0; // step j of a group handles m = mbase + j; the first group may start at j0
+                const int aoff = mp0 - a_g0;
+                // one step: candidates (m, m'0 + i), i = 0..7, into the rotating minima; then the minimum
+                // of target m + m'0 is complete for this item
+#define OOB_STEP(j)                                                                                   \
+    {                                                                                                 \
+        const int m = mbase + (j);                                                                    \
+        const int o = ((m - mA0) * PC + kl) * 8 + ul;                                                 \
+        const double2 p = s_pair[o];                                                                  \
+        const double atm = s_tm[o];                                                                   \
+        _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                               \
+            const double T = atm >= btm[i] ? p.x + bb2[i] : p.y + bbt[i];                             \
+            acc[((j) + i) & 7] = fmin(acc[((j) + i) & 7], T);                                         \
+        }                                                                                             \
+        const int ai = m + aoff;                                                                      \
+        if (ai >= 0 && ai < na)                                                                       \
+            atomicMin(&s_acc[ai * 64 + lane], (unsigned long long)__double_as_longlong(fma(acc[(j)], KS, kd))); \
+        acc[(j)] = kNone;                                                                             \
+    }
+                if (j0) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (j >= j0) OOB_STEP(j)
+                    mbase += 8;
+                }
+                for (; mbase <= mhi; mbase += 8) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) OOB_STEP(j)
+                }
+#undef OOB_STEP
+                // the last step was j = 7 with m = mhi: minima 0..6 belong to targets mhi + m'0 + 1 + i
+#pragma unroll
+                for (int i = 0; i < 7; ++i) {
+                    const int ai = mhi + 1 + i + aoff;
+                    if (ai >= 0 && ai < na)
+                        atomicMin(&s_acc[ai * 64 + lane], (unsigned long long)__double_as_longlong(fma(acc[i], KS, kd)));
+                }
+            }
+        }
+    }
+    __syncthreads();
+    // merge into the level's keys: other segments of the same block do the same
+    for (int e = threadIdx.x; e < na * 64; e += blockDim.x) {
+        const unsigned long long key = s_acc[e];
+        if (key == kNoneBits) continue;
+        const int aidx = fam_base + a_g0 + (e >> 6) - dlo_of(Sp, M);
+        const long long slot = ((long long)(s - 1) * NAall + aidx) * NT + tile;
+        atomicMin(&t.partKey[slot * 64 + (e & 63)], key);
+    }
+}
+
+// Sets n keys to "no such state".
+__global__ void k_fill_keys(unsigned long long *keys, long long n) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) keys[i] = 0x7FF0000000000000ull;
+}
+
+// ---------------------------------------------------------------------------------------
 // Levels S' >= 2, second kernel: grid (block of the plane, delta), one lane per state.
 // ---------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(64) k_select(Tables t, int Sp, int NT, int NAall) {
@@ -317,10 +486,23 @@ __global__ void __launch_bounds__(64) k_select(Tables t, int Sp, int NT, int NAa
     const int u = ub * 8 + (lane >> 3), v = vb * 8 + (lane & 7);
     double best = kNone;
     int bs = 0, bk = 0;
-    for (int s = 1; s < Sp; ++s) { // first s with the smallest minimum
-        const long long o = (((long long)(s - 1) * NAall + aidx) * NT + blockIdx.x) * 64 + lane;
-        const double T = t.partT[o];
-        if (T < best) { best = T; bs = s; bk = t.partK[o]; }
+    if (t.flags[0]) { // keys total * 2^kbits + k; consumed keys go back to "no such state"
+        const double KS = (double)(1 << key_bits(L)), inv = 1.0 / KS;
+        for (int s = 1; s < Sp; ++s) {
+            const long long o = (((long long)(s - 1) * NAall + aidx) * NT + blockIdx.x) * 64 + lane;
+            const double key = t.partT[o];
+            if (key < kNone) {
+                t.partT[o] = kNone;
+                const double T = floor(key * inv);
+                if (T < best) { best = T; bs = s; bk = (int)(key - T * KS); }
+            }
+        }
+    } else {
+        for (int s = 1; s < Sp; ++s) { // first s with the smallest minimum
+            const long long o = (((long long)(s - 1) * NAall + aidx) * NT + blockIdx.x) * 64 + lane;
+            const double T = t.partT[o];
+            if (T < best) { best = T; bs = s; bk = t.partK[o]; }
+        }
     }
     Rec out = {kNone, kNone, 0.0, 0.0};
     int ks = 0, ch = 0;
@@ -425,44 +607,45 @@ __global__ void k_backtrack(Tables t, oob_templates out) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Node specification and coverage (Section 4.1.1, Appendix A): one thread; the sizes are a
-// run of consecutive integers, so "largest pipeline count summing to x" is a coin-change
-// recursion; x only looks back n_hi entries, so a ring in the backtracking scratch holds it.
+// Node specification and coverage (Section 4.1.1, Appendix A), one wave.  The template sizes
+// are the consecutive integers n0..n_hi, so c pipelines can use exactly the node counts
+// c n0 .. c n_hi; the largest pipeline count whose sizes sum to x is therefore
+// c = floor(x / n0) when x <= c n_hi, and x is no sum of sizes at all otherwise (fewer
+// pipelines reach even less).  That is the value the coin-change recursion of Section 4.2.1
+// gives, without the table.
 // ---------------------------------------------------------------------------------------
-__global__ void k_coverage(Tables t, oob_templates out, int len) {
-    if (blockIdx.x != 0 || threadIdx.x != 0) return;
-    for (int q = 0; q < 8; ++q) out.cover_hdr[q] = 0;
-    for (int q = 0; q < len; ++q) out.cover_maxpipes[q] = 0;
-    const int cnt = t.sh.count, f = t.sh.f;
-    int i0 = -1;
-    for (int q = 0; q < cnt; ++q) if (out.feasible[q]) { i0 = q; break; }
-    if (i0 < 0) return;
-    int i1 = i0;
-    while (i1 + 1 < cnt && out.feasible[i1 + 1]) ++i1;
-    const int n0 = t.sh.n_min + i0, n_hi = t.sh.n_min + i1, p = n_hi - n0 + 1;
+__global__ void __launch_bounds__(64) k_coverage(Tables t, oob_templates out, int len) {
+    __shared__ int s_i0, s_i1, s_thm, s_tail;
+    const int cnt = t.sh.count, f = t.sh.f, lane = threadIdx.x;
+    if (lane == 0) {
+        int i0 = -1;
+        for (int q = 0; q < cnt; ++q) if (out.feasible[q]) { i0 = q; break; }
+        int i1 = i0;
+        while (i0 >= 0 && i1 + 1 < cnt && out.feasible[i1 + 1]) ++i1;
+        s_i0 = i0; s_i1 = i1; s_thm = 1; s_tail = 1;
+    }
+    for (int q = lane; q < len; q += 64) out.cover_maxpipes[q] = 0;
+    __syncthreads();
+    if (s_i0 < 0) {
+        if (lane < 8) out.cover_hdr[lane] = 0;
+        return;
+    }
+    const int n0 = t.sh.n_min + s_i0, n_hi = t.sh.n_min + s_i1, p = n_hi - n0 + 1;
     const int N = n_hi + f * n0;
     const int lo_thm = (f + 1) * n0, lo_tail = N - f < 1 ? 1 : N - f;
     const int lo = lo_thm < lo_tail ? lo_thm : lo_tail;
-    int *best = t.stack; // free again: k_backtrack has finished
-    const int ring = n_hi + 1;
-    int thm = 1, tail = 1;
-    best[0] = 0;
-    for (int x = 1; x <= N; ++x) {
-        int b = -1;
-        for (int c = n0; c <= n_hi && c <= x; ++c) {
-            const int prev = best[(x - c) % ring];
-            if (prev >= 0 && prev + 1 > b) b = prev + 1;
-        }
-        best[x % ring] = b;
-        const int c = b < 0 ? 0 : b;
-        if (x >= lo) {
-            if (x - lo < len) out.cover_maxpipes[x - lo] = c;
-            if (x >= lo_thm && c < f + 1) thm = 0;
-            if (x >= lo_tail && c < 1) tail = 0;
-        }
+    for (int x = lo + lane; x <= N; x += 64) {
+        int c = x / n0;
+        if ((long long)c * n_hi < x) c = 0;
+        if (x - lo < len) out.cover_maxpipes[x - lo] = c;
+        if (x >= lo_thm && c < f + 1) atomicMin(&s_thm, 0);
+        if (x >= lo_tail && c < 1) atomicMin(&s_tail, 0);
     }
-    out.cover_hdr[0] = n0; out.cover_hdr[1] = n_hi; out.cover_hdr[2] = p; out.cover_hdr[3] = N;
-    out.cover_hdr[4] = p > n0 - 1; out.cover_hdr[5] = lo; out.cover_hdr[6] = thm; out.cover_hdr[7] = tail;
+    __syncthreads();
+    if (lane == 0) {
+        out.cover_hdr[0] = n0; out.cover_hdr[1] = n_hi; out.cover_hdr[2] = p; out.cover_hdr[3] = N;
+        out.cover_hdr[4] = p > n0 - 1; out.cover_hdr[5] = lo; out.cover_hdr[6] = s_thm; out.cover_hdr[7] = s_tail;
+    }
 }
 
 // Copies one table into dense n x n arrays, n = L-S'+1, entry [u][v - S'] (tests only).
@@ -510,7 +693,7 @@ long long part_slots(int L, int M, int n_max, int Nb) {
 }
 
 struct Carve {
-    size_t lvl_tab, PT, PF, PM, rec, kstar, choice, partT, partK, stack, total;
+    size_t lvl_tab, PT, PF, PM, rec, kstar, choice, partT, partK, stack, flags, total;
     long long recs, slots;
 };
 // Byte offsets of the workspace arrays, sized for the handle's maxima.
@@ -531,6 +714,7 @@ Carve carve(int L, int nodes, int M) {
     c.partT = o;   o = align_up(o + sizeof(double) * (size_t)c.slots * 64);
     c.partK = o;   o = align_up(o + sizeof(int) * (size_t)c.slots * 64);
     c.stack = o;   o = align_up(o + sizeof(int) * ((size_t)nodes * (Smax + 1) * 4 + nodes + 2));
+    c.flags = o;   o = align_up(o + sizeof(int) * 64);
     c.total = o;
     return c;
 }
@@ -586,6 +770,38 @@ bool plan_split(const Shape &sh, int Sp, int fam, SplitPlan *p) {
     const size_t per_k = (size_t)ntab * 8 * 24;
     p->pc = per_k * 4 <= kLdsPrefer ? 4 : per_k * 2 <= kLdsPrefer ? 2 : 1;
     p->lds = per_k * p->pc;
+    return true;
+}
+
+// Launch shape of k_split_key for one family of one level: pc = log2 of the k values per pass.
+constexpr size_t kKeyLdsPrefer = 52 * 1024; // three workgroups per compute unit
+constexpr int kKeyWaves = 4;
+bool plan_split_key(const Shape &sh, int Sp, int fam, SplitPlan *p) {
+    int t_lo, t_hi;
+    target_units(fam, Sp, sh.M, sh.n_max, &t_lo, &t_hi);
+    if (fam == 0 && Sp > sh.M) return false;
+    if (t_hi < t_lo) return false;
+    const int cnt = t_hi - t_lo + 1;
+    p->groups = cdiv(cnt, kKeyTargets);
+    int ntab = 1;
+    for (int s = 1; s < Sp; ++s) {
+        int A_lo, A_hi, B_lo, B_hi;
+        child_units(fam, s, sh.M, sh.n_max, &A_lo, &A_hi);
+        child_units(fam, Sp - s, sh.M, sh.n_max, &B_lo, &B_hi);
+        for (int g = 0; g < p->groups; ++g) {
+            const int a0 = t_lo + g * kKeyTargets, a1 = imin(t_hi, a0 + kKeyTargets - 1);
+            const int mA0 = imax(A_lo, a0 - B_hi), mA1 = imin(A_hi, a1 - B_lo);
+            const int mB0 = imax(B_lo, a0 - A_hi), mB1 = imin(B_hi, a1 - A_lo);
+            if (mA0 <= mA1 && mB0 <= mB1) ntab = imax(ntab, mA1 - mA0 + 1 + 8 * cdiv(mB1 - mB0 + 1, 8));
+        }
+    }
+    const size_t acc = (size_t)imin(cnt, kKeyTargets) * 64 * 8, per_k = (size_t)ntab * 8 * 24;
+    const int krange = imin(kSegK, sh.L - Sp + 2); // split points a workgroup handles
+    int pcs = 0;
+    while (pcs < 7 && (1 << pcs) < krange && acc + (per_k << (pcs + 1)) <= kKeyLdsPrefer) ++pcs;
+    p->pc = pcs;
+    p->lds = acc + (per_k << pcs);
+    p->waves = kKeyWaves;
     return true;
 }
 
@@ -664,8 +880,10 @@ static Tables make_tables(const oob_plan *h, const Shape &sh, int *status) {
     t.kstar = (int *)(h->ws + h->cv.kstar);
     t.choice = (int *)(h->ws + h->cv.choice);
     t.partT = (double *)(h->ws + h->cv.partT);
+    t.partKey = (unsigned long long *)(h->ws + h->cv.partT);
     t.partK = (int *)(h->ws + h->cv.partK);
     t.stack = (int *)(h->ws + h->cv.stack);
+    t.flags = (int *)(h->ws + h->cv.flags);
     t.status = status;
     return t;
 }
@@ -674,6 +892,15 @@ static bool out_ok(const oob_templates *o) {
     return o && o->feasible && o->S && o->kstar && o->T && o->T1 && o->T2 && o->T3 && o->tmax &&
            o->stage_off && o->stage_begin && o->stage_gpus && o->cover_hdr && o->cover_maxpipes &&
            o->status;
+}
+
+static void launch_split_key(const Tables &t, int S, int fam, const SplitPlan &sp, int NT, int NAall,
+                             hipStream_t st) {
+    if (sp.lds > kLdsPrefer)
+        (void)hipFuncSetAttribute((const void *)k_split_key, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)kLdsLimit);
+    hipLaunchKernelGGL(k_split_key, dim3(seg_count(t.sh.L, S), S - 1, sp.groups), dim3(sp.waves * 64), sp.lds, st,
+                       t, S, fam, NT, NAall, sp.pc);
 }
 
 template <int PC>
@@ -708,6 +935,7 @@ extern "C" int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L
         for (int fam = 0; fam < 2; ++fam) {
             SplitPlan sp;
             if (plan_split(sh, S, fam, &sp) && sp.lds > kLdsLimit) return OOB_ECAPACITY;
+            if (plan_split_key(sh, S, fam, &sp) && sp.lds > kLdsLimit) return OOB_ECAPACITY;
         }
     const Tables t = make_tables(h, sh, (int *)out->status);
     hipStream_t st = (hipStream_t)stream;
@@ -716,14 +944,20 @@ extern "C" int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L
     hipLaunchKernelGGL(k_setup, dim3(1), dim3(OOB_MAX_GPUS + 1), 0, st, t, *profile);
     hipLaunchKernelGGL(k_level1, dim3(tile_count(L, 1), M), dim3(64), 0, st, t,
                        (const long long *)profile->boundary_ns);
+    {
+        const long long nkeys = part_slots(L, M, n_max, microbatches) * 64;
+        hipLaunchKernelGGL(k_fill_keys, dim3((unsigned)((nkeys + 255) / 256)), dim3(256), 0, st, t.partKey, nkeys);
+    }
     if (h->ev_begin) OOB_HIP_CHECK(hipEventRecord(h->ev_begin, st));
     for (int S = 2; S <= sh.Smax; ++S) {
         const int NAall = dhi_of(S, M, n_max) - dlo_of(S, M) + 1;
         if (NAall <= 0) continue;
         const int NT = tile_count(L, S);
         for (int fam = 0; fam < 2; ++fam) {
-            SplitPlan sp;
-            if (!plan_split(sh, S, fam, &sp)) continue;
+            SplitPlan sp, kp;
+            if (!plan_split(sh, S, fam, &sp) || !plan_split_key(sh, S, fam, &kp)) continue;
+            // exactly one of the two does the work: the set-up kernel decides (flags[0])
+            launch_split_key(t, S, fam, kp, NT, NAall, st);
             if (sp.pc == 4) launch_split<4>(t, S, fam, sp, NT, NAall, st);
             else if (sp.pc == 2) launch_split<2>(t, S, fam, sp, NT, NAall, st);
             else launch_split<1>(t, S, fam, sp, NT, NAall, st);
@@ -773,6 +1007,19 @@ extern "C" int oob_plan_last_level_ms(oob_plan *h, float *ms) {
     if (!h || !ms || !h->ev_begin || !h->timed) return OOB_EINVAL;
     OOB_HIP_CHECK(hipEventSynchronize(h->ev_end));
     OOB_HIP_CHECK(hipEventElapsedTime(ms, h->ev_begin, h->ev_end));
+    return OOB_OK;
+}
+
+// Copies flags[0..3] of the last call to a device array (tests: which split kernel ran).
+__global__ void k_export_flags(const int *flags, int *dst) {
+    if (threadIdx.x < 4) dst[threadIdx.x] = flags[threadIdx.x];
+}
+
+extern "C" int oob_plan_export_flags(oob_plan *h, int32_t *flags, void *stream) {
+    if (!h || !h->have_last || !flags) return OOB_EINVAL;
+    hipLaunchKernelGGL(k_export_flags, dim3(1), dim3(64), 0, (hipStream_t)stream, (const int *)(h->ws + h->cv.flags),
+                       (int *)flags);
+    OOB_HIP_CHECK(hipGetLastError());
     return OOB_OK;
 }
 

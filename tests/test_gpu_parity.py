@@ -153,11 +153,21 @@ def test_device_status_reports_bad_profile_values(P):
     planner.close()
 
 
-def test_large_times_stay_exact(P):
-    """Times near the top of the exactly representable range (sums around 2^44)."""
-    inp = inputs.random_small(11, 9, 2, 1, 3, 7, t_lo=(1 << 36), t_hi=(1 << 37))
-    planner = P.Planner(9, 3, 2)
-    full_check(P, planner, inp)
+def test_large_times_stay_exact_both_split_kernels(P):
+    """Times near the top of the exactly representable range.  Up to a bound the set-up
+    kernel checks, (total, split point) pairs fit one double and the keyed split kernel runs;
+    above it the plain split kernel runs.  Both must match the oracle bit for bit."""
+    planner = P.Planner(12, 4, 3)
+    seen = set()
+    for seed in range(4):
+        for inp in (inputs.random_small(20 + seed, 9, 2, 1, 3, 7, t_lo=(1 << 38), t_hi=(1 << 39)),
+                    inputs.random_small(30 + seed, 12, 3, 1, 4, 0, t_lo=(1 << 36), t_hi=(1 << 37),
+                                        tight_mem=True),
+                    inputs.random_small(40 + seed, 9, 2, 1, 3, 7, t_lo=(1 << 30), t_hi=(1 << 31)),
+                    inputs.random_small(50 + seed, 12, 3, 1, 4, 9)):
+            full_check(P, planner, inp)
+            seen.add(planner.flags()[0])
+    assert seen == {0, 1}, "both split kernels must have been exercised"
     planner.close()
 
 
