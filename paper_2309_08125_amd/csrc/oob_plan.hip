@@ -33,6 +33,7 @@
 #include <new>
 #include <stdint.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include "oob_layout.h"
@@ -329,14 +330,15 @@ __global__ void __launch_bounds__(512) k_split(Tables t, int Sp, int fam, int NT
 constexpr int kKeyTargets = 64;
 constexpr int kFillBatch = 4; // records a thread has in flight while staging
 
-__global__ void __launch_bounds__(512) k_split_key(Tables t, int Sp, int fam, int NT, int NAall, int pcs) {
+template <int PCS>
+__global__ void __launch_bounds__(512) k_split_key(Tables t, int Sp, int fam, int NT, int NAall) {
     HIP_DYNAMIC_SHARED(double2, s_pair) // [nA + 8 nmb][PC][8] pairs | double tmax[same] | u64 acc[na][64]
     if (t.flags[0] == 0) return;        // keys do not fit: k_split handles this job
     const int L = t.sh.L, M = t.sh.M, n_max = t.sh.n_max;
     const int s = blockIdx.y + 1, r = Sp - s;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const int ul = lane >> 3, vl = lane & 7;
-    const int PC = 1 << pcs, TS = PC * 8;  // k values staged per pass, records per table and pass
+    constexpr int pcs = PCS, PC = 1 << PCS, TS = PC * 8; // k values staged per pass, records per table and pass
     int tile, ub, vb, seg;
     seg_decode(L, Sp, blockIdx.x, &tile, &ub, &vb, &seg);
     const int fam_base = fam ? M - 2 : -1;
@@ -361,45 +363,49 @@ __global__ void __launch_bounds__(512) k_split_key(Tables t, int Sp, int fam, in
     const int kbits = key_bits(L);
     const double KS = (double)(1 << kbits);
 
-    for (int e = threadIdx.x; e < na * 64; e += blockDim.x) s_acc[e] = kNoneBits;
+    // rows 1..na are the targets; rows 0 and na+1 swallow the minima of targets outside the group
+    for (int e = threadIdx.x; e < (na + 2) * 64; e += blockDim.x) s_acc[e] = kNoneBits;
     {
         const double cl = t.sh.Nb > 0 ? -(double)r : 3.0 * r, cr = t.sh.Nb > 0 ? 0.0 : 4.0 * s;
         const long long tabA = t.lvl_tab[s] - dlo_of(s, M) + fam_base, tabB = t.lvl_tab[r] - dlo_of(r, M) + fam_base;
         const int fillA = nA * TS, fill = ntab * TS;
         const int kb_lo = kmin >> 3, kb_hi = kmax >> 3; // 8-blocks of k that hold states of both children
+        // record e of the staging order for the pass starting at kc: [left tables][u][k] then
+        // [right tables][k][v]; k outside the 8-blocks that hold states reads as "no such state"
+        auto load = [&](int kc, int e) -> Rec {
+            Rec rc = {kNone, kNone, 0.0, 0.0};
+            if (e < fillA) {       // left child (s, u, k, m): row u of block (ub, k/8)
+                const int tab = e / TS, rem = e - tab * TS, u_l = rem >> pcs, k = kc + (rem & (PC - 1));
+                if ((k >> 3) >= kb_lo && (k >> 3) <= kb_hi)
+                    rc = t.rec[(tabA + mA0 + tab) * t.tab_recs + (long long)tri_index(ub, k >> 3, t.NB) * 64 +
+                               (u_l << 3) + (k & 7)];
+            } else if (e < fill) { // right child (r, k, v, m'): row k of block (k/8, vb)
+                const int e2 = e - fillA, tab = e2 / TS, rem = e2 - tab * TS, k = kc + (rem >> 3);
+                if (tab < nB && (k >> 3) >= kb_lo && (k >> 3) <= kb_hi)
+                    rc = t.rec[(tabB + mB0 + tab) * t.tab_recs + (long long)tri_index(k >> 3, vb, t.NB) * 64 +
+                               ((k & 7) << 3) + (rem & 7)];
+            }
+            return rc;
+        };
+        auto store = [&](int e, const Rec &rc) {
+            if (e < fillA) {
+                const int tab = e / TS, rem = e - tab * TS, u_l = rem >> pcs, k_l = rem & (PC - 1);
+                const int o = (tab * PC + k_l) * 8 + u_l;
+                s_pair[o] = make_double2(rc.T + cl * rc.tmax, rc.T1);
+                s_tm[o] = rc.tmax;
+            } else if (e < fill) { // same order in LDS as in the staging order: [table][k][v]
+                s_pair[e] = make_double2(2.0 * rc.T1, rc.T + cr * rc.tmax);
+                s_tm[e] = rc.tmax;
+            }
+        };
         for (int kc = (kmin >> pcs) << pcs; kc <= kmax; kc += PC) {
             __syncthreads(); // previous pass fully consumed (first pass: acc initialised)
             for (int e0 = threadIdx.x; e0 < fill; e0 += blockDim.x * kFillBatch) {
-                Rec rec[kFillBatch];
+                Rec rc[kFillBatch];
 #pragma unroll
-                for (int q = 0; q < kFillBatch; ++q) { // all loads of the batch first
-                    const int e = e0 + q * blockDim.x;
-                    rec[q] = Rec{kNone, kNone, 0.0, 0.0};
-                    if (e < fillA) {       // left child (s, u, k, m): row u of block (ub, k/8)
-                        const int tab = e / TS, rem = e - tab * TS, u_l = rem >> pcs, k = kc + (rem & (PC - 1));
-                        if ((k >> 3) >= kb_lo && (k >> 3) <= kb_hi)
-                            rec[q] = t.rec[(tabA + mA0 + tab) * t.tab_recs +
-                                           (long long)tri_index(ub, k >> 3, t.NB) * 64 + (u_l << 3) + (k & 7)];
-                    } else if (e < fill) { // right child (r, k, v, m'): row k of block (k/8, vb)
-                        const int e2 = e - fillA, tab = e2 / TS, rem = e2 - tab * TS, k = kc + (rem >> 3);
-                        if (tab < nB && (k >> 3) >= kb_lo && (k >> 3) <= kb_hi)
-                            rec[q] = t.rec[(tabB + mB0 + tab) * t.tab_recs +
-                                           (long long)tri_index(k >> 3, vb, t.NB) * 64 + ((k & 7) << 3) + (rem & 7)];
-                    }
-                }
+                for (int q = 0; q < kFillBatch; ++q) rc[q] = load(kc, e0 + q * blockDim.x); // loads first
 #pragma unroll
-                for (int q = 0; q < kFillBatch; ++q) {
-                    const int e = e0 + q * blockDim.x;
-                    if (e < fillA) {
-                        const int tab = e / TS, rem = e - tab * TS, u_l = rem >> pcs, k_l = rem & (PC - 1);
-                        const int o = (tab * PC + k_l) * 8 + u_l;
-                        s_pair[o] = make_double2(rec[q].T + cl * rec[q].tmax, rec[q].T1);
-                        s_tm[o] = rec[q].tmax;
-                    } else if (e < fill) { // same order in LDS as in the fill index: [table][k][v]
-                        s_pair[e] = make_double2(2.0 * rec[q].T1, rec[q].T + cr * rec[q].tmax);
-                        s_tm[e] = rec[q].tmax;
-                    }
-                }
+                for (int q = 0; q < kFillBatch; ++q) store(e0 + q * blockDim.x, rc[q]);
             }
             __syncthreads();
             const int kl0 = imax(0, kmin - kc), nk = imin(PC - 1, kmax - kc) - kl0 + 1;
@@ -432,9 +438,8 @@ __global__ void __launch_bounds__(512) k_split_key(Tables t, int Sp, int fam, in
             const double T = atm >= btm[i] ? p.x + bb2[i] : p.y + bbt[i];                             \
             acc[((j) + i) & 7] = fmin(acc[((j) + i) & 7], T);                                         \
         }                                                                                             \
-        const int ai = m + aoff;                                                                      \
-        if (ai >= 0 && ai < na)                                                                       \
-            atomicMin(&s_acc[ai * 64 + lane], (unsigned long long)__double_as_longlong(fma(acc[(j)], KS, kd))); \
+        const int row = imin(imax(m + aoff, -1), na) + 1;                                             \
+        atomicMin(&s_acc[row * 64 + lane], (unsigned long long)__double_as_longlong(fma(acc[(j)], KS, kd))); \
         acc[(j)] = kNone;                                                                             \
     }
                 if (j0) {
@@ -451,9 +456,8 @@ __global__ void __launch_bounds__(512) k_split_key(Tables t, int Sp, int fam, in
                 // the last step was j = 7 with m = mhi: minima 0..6 belong to targets mhi + m'0 + 1 + i
 #pragma unroll
                 for (int i = 0; i < 7; ++i) {
-                    const int ai = mhi + 1 + i + aoff;
-                    if (ai >= 0 && ai < na)
-                        atomicMin(&s_acc[ai * 64 + lane], (unsigned long long)__double_as_longlong(fma(acc[i], KS, kd)));
+                    const int row = imin(imax(mhi + 1 + i + aoff, -1), na) + 1;
+                    atomicMin(&s_acc[row * 64 + lane], (unsigned long long)__double_as_longlong(fma(acc[i], KS, kd)));
                 }
             }
         }
@@ -461,7 +465,7 @@ __global__ void __launch_bounds__(512) k_split_key(Tables t, int Sp, int fam, in
     __syncthreads();
     // merge into the level's keys: other segments of the same block do the same
     for (int e = threadIdx.x; e < na * 64; e += blockDim.x) {
-        const unsigned long long key = s_acc[e];
+        const unsigned long long key = s_acc[64 + e];
         if (key == kNoneBits) continue;
         const int aidx = fam_base + a_g0 + (e >> 6) - dlo_of(Sp, M);
         const long long slot = ((long long)(s - 1) * NAall + aidx) * NT + tile;
@@ -488,15 +492,20 @@ __global__ void __launch_bounds__(64) k_select(Tables t, int Sp, int NT, int NAa
     int bs = 0, bk = 0;
     if (t.flags[0]) { // keys total * 2^kbits + k; consumed keys go back to "no such state"
         const double KS = (double)(1 << key_bits(L)), inv = 1.0 / KS;
-        for (int s = 1; s < Sp; ++s) {
-            const long long o = (((long long)(s - 1) * NAall + aidx) * NT + blockIdx.x) * 64 + lane;
-            const double key = t.partT[o];
-            if (key < kNone) {
-                t.partT[o] = kNone;
-                const double T = floor(key * inv);
-                if (T < best) { best = T; bs = s; bk = (int)(key - T * KS); }
+        const long long o0 = ((long long)aidx * NT + blockIdx.x) * 64 + lane, os = (long long)NAall * NT * 64;
+        double bkey = kNone;
+        for (int s0 = 1; s0 < Sp; s0 += 8) { // eight independent loads in flight
+            double key[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) key[q] = s0 + q < Sp ? t.partT[o0 + (s0 + q - 1) * os] : kNone;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const double T = floor(key[q] * inv); // +inf stays +inf
+                if (T < best) { best = T; bs = s0 + q; bkey = key[q]; }
             }
         }
+        if (best < kNone) bk = (int)(bkey - best * KS);
+        for (int s = 1; s < Sp; ++s) t.partT[o0 + (s - 1) * os] = kNone;
     } else {
         for (int s = 1; s < Sp; ++s) { // first s with the smallest minimum
             const long long o = (((long long)(s - 1) * NAall + aidx) * NT + blockIdx.x) * 64 + lane;
@@ -774,8 +783,13 @@ bool plan_split(const Shape &sh, int Sp, int fam, SplitPlan *p) {
 }
 
 // Launch shape of k_split_key for one family of one level: pc = log2 of the k values per pass.
-constexpr size_t kKeyLdsPrefer = 52 * 1024; // three workgroups per compute unit
-constexpr int kKeyWaves = 4;
+static int env_or(const char *name, int dflt) {
+    const char *v = getenv(name);
+    return v && *v ? atoi(v) : dflt;
+}
+static const size_t kKeyLdsPrefer = (size_t)env_or("OOB_TUNE_KEY_LDS_KB", 78) * 1024;
+static const int kKeyWaves = env_or("OOB_TUNE_KEY_WAVES", 6);
+static const int kKeyMaxPcs = env_or("OOB_TUNE_KEY_MAXPCS", 3);
 bool plan_split_key(const Shape &sh, int Sp, int fam, SplitPlan *p) {
     int t_lo, t_hi;
     target_units(fam, Sp, sh.M, sh.n_max, &t_lo, &t_hi);
@@ -795,10 +809,10 @@ bool plan_split_key(const Shape &sh, int Sp, int fam, SplitPlan *p) {
             if (mA0 <= mA1 && mB0 <= mB1) ntab = imax(ntab, mA1 - mA0 + 1 + 8 * cdiv(mB1 - mB0 + 1, 8));
         }
     }
-    const size_t acc = (size_t)imin(cnt, kKeyTargets) * 64 * 8, per_k = (size_t)ntab * 8 * 24;
+    const size_t acc = (size_t)(imin(cnt, kKeyTargets) + 2) * 64 * 8, per_k = (size_t)ntab * 8 * 24;
     const int krange = imin(kSegK, sh.L - Sp + 2); // split points a workgroup handles
     int pcs = 0;
-    while (pcs < 7 && (1 << pcs) < krange && acc + (per_k << (pcs + 1)) <= kKeyLdsPrefer) ++pcs;
+    while (pcs < kKeyMaxPcs && (1 << pcs) < krange && acc + (per_k << (pcs + 1)) <= kKeyLdsPrefer) ++pcs;
     p->pc = pcs;
     p->lds = acc + (per_k << pcs);
     p->waves = kKeyWaves;
@@ -894,13 +908,23 @@ static bool out_ok(const oob_templates *o) {
            o->status;
 }
 
+template <int PCS>
+static void launch_split_key_pc(const Tables &t, int S, int fam, const SplitPlan &sp, int NT, int NAall,
+                                hipStream_t st) {
+    if (sp.lds > kLdsPrefer)
+        (void)hipFuncSetAttribute((const void *)k_split_key<PCS>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)kLdsLimit);
+    hipLaunchKernelGGL(k_split_key<PCS>, dim3(seg_count(t.sh.L, S), S - 1, sp.groups), dim3(sp.waves * 64), sp.lds,
+                       st, t, S, fam, NT, NAall);
+}
 static void launch_split_key(const Tables &t, int S, int fam, const SplitPlan &sp, int NT, int NAall,
                              hipStream_t st) {
-    if (sp.lds > kLdsPrefer)
-        (void)hipFuncSetAttribute((const void *)k_split_key, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)kLdsLimit);
-    hipLaunchKernelGGL(k_split_key, dim3(seg_count(t.sh.L, S), S - 1, sp.groups), dim3(sp.waves * 64), sp.lds, st,
-                       t, S, fam, NT, NAall, sp.pc);
+    switch (sp.pc) {
+    case 0: launch_split_key_pc<0>(t, S, fam, sp, NT, NAall, st); break;
+    case 1: launch_split_key_pc<1>(t, S, fam, sp, NT, NAall, st); break;
+    case 2: launch_split_key_pc<2>(t, S, fam, sp, NT, NAall, st); break;
+    default: launch_split_key_pc<3>(t, S, fam, sp, NT, NAall, st); break;
+    }
 }
 
 template <int PC>
