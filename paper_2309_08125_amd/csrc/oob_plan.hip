@@ -62,6 +62,8 @@ struct Tables {
     unsigned long long *partKey; // the same memory: keys total * 2^kbits + k (keyed kernel)
     int *partK;           // same shape: first k reaching the minimum
     int *stack;           // backtracking stacks / coverage ring
+    int2 *seg_tab;        // per level: (tile index, ub | vb << 8 | segment << 16) of every split task
+    long long *seg_off;   // [Smax+2] first entry of level S' in seg_tab
     int *flags;           // [0] 1: (total, k) keys fit a double (k_split_key runs), 0: k_split runs
     int *status;
 };
@@ -75,7 +77,7 @@ __device__ __forceinline__ long long rec_index(const Tables &t, int S, int delta
 // Set-up: prefix sums (Eq. 4's sums become differences), input validation, level offsets.
 // One block; thread d-1 scans the profile row of d GPUs.
 // ---------------------------------------------------------------------------------------
-__global__ void k_setup(Tables t, oob_profile prof) {
+__global__ void k_setup(Tables t, oob_profile prof, int force_plain) {
     const int L = t.sh.L, M = t.sh.M, W = L + 1;
     __shared__ long long s_worst[OOB_MAX_GPUS + 1];
     __shared__ int s_bad;
@@ -116,11 +118,13 @@ __global__ void k_setup(Tables t, oob_profile prof) {
         }
         s_worst[0] = xs;
         if (bad) atomicMax(&s_bad, bad);
-        long long tab = 0;
+        long long tab = 0, seg = 0;
         for (int S = 1; S <= t.sh.Smax + 1; ++S) {
             t.lvl_tab[S] = tab;
+            t.seg_off[S] = seg;
             const int nd = dhi_of(S, M, t.sh.n_max) - dlo_of(S, M) + 1;
             if (S <= t.sh.Smax && nd > 0) tab += nd;
+            if (S >= 2 && S <= t.sh.Smax) seg += seg_count(L, S);
         }
     }
     __syncthreads();
@@ -141,7 +145,7 @@ __global__ void k_setup(Tables t, oob_profile prof) {
             const long long mult = nb + 4LL * t.sh.Smax + 4;
             if (worst >= kExactBound / mult) st = OOB_EOVERFLOW;
             // a total and a split point k <= L fit one double as total * 2^kbits + k
-            t.flags[0] = worst < (kExactBound >> key_bits(L)) / mult;
+            t.flags[0] = !force_plain && worst < (kExactBound >> key_bits(L)) / mult;
         }
         if (st != OOB_OK) t.flags[0] = 0;
         *t.status = st;
@@ -328,19 +332,61 @@ __global__ void __launch_bounds__(512) k_split(Tables t, int Sp, int fam, int NT
 // and yields, per (s, state), the smallest total and the first k reaching it at once.
 // ---------------------------------------------------------------------------------------
 constexpr int kKeyTargets = 64;
-constexpr int kFillBatch = 4; // records a thread has in flight while staging
+constexpr int kFillBatch = 3; // records a thread has in flight while staging
 
-template <int PCS>
-__global__ void __launch_bounds__(512) k_split_key(Tables t, int Sp, int fam, int NT, int NAall) {
-    HIP_DYNAMIC_SHARED(double2, s_pair) // [nA + 8 nmb][PC][8] pairs | double tmax[same] | u64 acc[na][64]
+// Record e of the staging order for split point k: [left tables][u] then [right tables][v].
+struct Stage {
+    const Rec *rec;
+    long long tabA, tabB; // table index of left unit count 0 / right unit count 0
+    int tab_recs, NB, ub, vb, nA, nB, fillA, fill;
+    double cl, cr;
+};
+struct Rec24 { double2 a; double tm; }; // (T, T1), tmax: the 24 bytes of a record the splits need
+
+__device__ __forceinline__ Rec24 stage_load(const Stage &g, int k, int e) {
+    Rec24 rc = {make_double2(kNone, kNone), 0.0};
+    const Rec *p = nullptr;
+    if (e < g.fillA) {       // left child (s, u, k, m): row u of block (ub, k/8)
+        p = g.rec + (g.tabA + (e >> 3)) * g.tab_recs + (long long)tri_index(g.ub, k >> 3, g.NB) * 64 + ((e & 7) << 3) + (k & 7);
+    } else if (e < g.fill) { // right child (r, k, v, m'): row k of block (k/8, vb)
+        const int e2 = e - g.fillA;
+        if ((e2 >> 3) < g.nB)
+            p = g.rec + (g.tabB + (e2 >> 3)) * g.tab_recs + (long long)tri_index(k >> 3, g.vb, g.NB) * 64 + ((k & 7) << 3) + (e2 & 7);
+    }
+    if (p) {
+        rc.a = *(const double2 *)p;
+        rc.tm = p->tmax;
+    }
+    return rc;
+}
+// LDS order = staging order; values pre-combined with the level's coefficients.
+__device__ __forceinline__ void stage_store(const Stage &g, double2 *pair, double *tm, int e, const Rec24 &rc) {
+    if (e < g.fillA) {
+        pair[e] = make_double2(rc.a.x + g.cl * rc.tm, rc.a.y);
+        tm[e] = rc.tm;
+    } else if (e < g.fill) {
+        pair[e] = make_double2(2.0 * rc.a.y, rc.a.x + g.cr * rc.tm);
+        tm[e] = rc.tm;
+    }
+}
+
+// One split point per pass, two LDS buffers: while the waves work on k from one buffer, every
+// thread has the records of k+1 in flight from HBM/L2 and drops them into the other buffer
+// before the single barrier of the pass.
+template <int NTAB, int NA>
+__global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, int NT, int NAall, int halves) {
+    // Static, separate arrays: the compiler then knows that the key merges (atomics on s_acc) never
+    // touch the staged records, and keeps the reads of the next step ahead of them.
+    __shared__ double2 s_pair[2][NTAB * 8]; // [buffer][table][u or v]: (T + cl tmax, T1) / (2 T1, T + cr tmax)
+    __shared__ double s_tm[2][NTAB * 8];    // tmax
+    __shared__ unsigned long long s_acc[(NA + 2) * 64]; // keys, rows 1..na
     if (t.flags[0] == 0) return;        // keys do not fit: k_split handles this job
     const int L = t.sh.L, M = t.sh.M, n_max = t.sh.n_max;
     const int s = blockIdx.y + 1, r = Sp - s;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const int ul = lane >> 3, vl = lane & 7;
-    constexpr int pcs = PCS, PC = 1 << PCS, TS = PC * 8; // k values staged per pass, records per table and pass
-    int tile, ub, vb, seg;
-    seg_decode(L, Sp, blockIdx.x, &tile, &ub, &vb, &seg);
+    const int2 sg = t.seg_tab[t.seg_off[Sp] + blockIdx.x]; // x: tile index, y: ub | vb << 8 | seg << 16
+    const int tile = sg.x, ub = sg.y & 255, vb = (sg.y >> 8) & 255, seg = sg.y >> 16;
     const int fam_base = fam ? M - 2 : -1;
     int t_lo, t_hi;
     target_units(fam, Sp, M, n_max, &t_lo, &t_hi);
@@ -353,87 +399,76 @@ __global__ void __launch_bounds__(512) k_split_key(Tables t, int Sp, int fam, in
     const int mB0 = imax(B_lo, a_g0 - A_hi), mB1 = imin(B_hi, a_g1 - A_lo);
     // this workgroup's segment of the split points of the block
     const int kmin = ub * 8 + s + seg * kSegK, kmax = imin(imin(vb * 8 + 7, L) - r, kmin + kSegK - 1);
-    const bool work = mA0 <= mA1 && mB0 <= mB1 && kmin <= kmax;
-    if (!work) return;                  // nothing to merge: the keys stay "no such state"
+    if (!(mA0 <= mA1 && mB0 <= mB1 && kmin <= kmax)) return; // nothing to merge
     const int nA = mA1 - mA0 + 1, nB = mB1 - mB0 + 1, nmb = cdiv(nB, 8);
-    const int ntab = nA + 8 * nmb;
-    double *s_tm = (double *)(s_pair + (size_t)ntab * TS);
-    unsigned long long *s_acc = (unsigned long long *)(s_tm + (size_t)ntab * TS);
+    const int ntab = nA + 8 * nmb, TS = ntab * 8;
     const unsigned long long kNoneBits = 0x7FF0000000000000ull;
-    const int kbits = key_bits(L);
-    const double KS = (double)(1 << kbits);
+    const double KS = (double)(1 << key_bits(L));
+
+    Stage g;
+    g.rec = t.rec;
+    g.tabA = t.lvl_tab[s] - dlo_of(s, M) + fam_base + mA0;
+    g.tabB = t.lvl_tab[r] - dlo_of(r, M) + fam_base + mB0;
+    g.tab_recs = t.tab_recs; g.NB = t.NB; g.ub = ub; g.vb = vb; g.nA = nA; g.nB = nB;
+    g.fillA = nA * 8; g.fill = TS;
+    g.cl = t.sh.Nb > 0 ? -(double)r : 3.0 * r;
+    g.cr = t.sh.Nb > 0 ? 0.0 : 4.0 * s;
 
     // rows 1..na are the targets; rows 0 and na+1 swallow the minima of targets outside the group
     for (int e = threadIdx.x; e < (na + 2) * 64; e += blockDim.x) s_acc[e] = kNoneBits;
-    {
-        const double cl = t.sh.Nb > 0 ? -(double)r : 3.0 * r, cr = t.sh.Nb > 0 ? 0.0 : 4.0 * s;
-        const long long tabA = t.lvl_tab[s] - dlo_of(s, M) + fam_base, tabB = t.lvl_tab[r] - dlo_of(r, M) + fam_base;
-        const int fillA = nA * TS, fill = ntab * TS;
-        const int kb_lo = kmin >> 3, kb_hi = kmax >> 3; // 8-blocks of k that hold states of both children
-        // record e of the staging order for the pass starting at kc: [left tables][u][k] then
-        // [right tables][k][v]; k outside the 8-blocks that hold states reads as "no such state"
-        auto load = [&](int kc, int e) -> Rec {
-            Rec rc = {kNone, kNone, 0.0, 0.0};
-            if (e < fillA) {       // left child (s, u, k, m): row u of block (ub, k/8)
-                const int tab = e / TS, rem = e - tab * TS, u_l = rem >> pcs, k = kc + (rem & (PC - 1));
-                if ((k >> 3) >= kb_lo && (k >> 3) <= kb_hi)
-                    rc = t.rec[(tabA + mA0 + tab) * t.tab_recs + (long long)tri_index(ub, k >> 3, t.NB) * 64 +
-                               (u_l << 3) + (k & 7)];
-            } else if (e < fill) { // right child (r, k, v, m'): row k of block (k/8, vb)
-                const int e2 = e - fillA, tab = e2 / TS, rem = e2 - tab * TS, k = kc + (rem >> 3);
-                if (tab < nB && (k >> 3) >= kb_lo && (k >> 3) <= kb_hi)
-                    rc = t.rec[(tabB + mB0 + tab) * t.tab_recs + (long long)tri_index(k >> 3, vb, t.NB) * 64 +
-                               ((k & 7) << 3) + (rem & 7)];
-            }
-            return rc;
-        };
-        auto store = [&](int e, const Rec &rc) {
-            if (e < fillA) {
-                const int tab = e / TS, rem = e - tab * TS, u_l = rem >> pcs, k_l = rem & (PC - 1);
-                const int o = (tab * PC + k_l) * 8 + u_l;
-                s_pair[o] = make_double2(rc.T + cl * rc.tmax, rc.T1);
-                s_tm[o] = rc.tmax;
-            } else if (e < fill) { // same order in LDS as in the staging order: [table][k][v]
-                s_pair[e] = make_double2(2.0 * rc.T1, rc.T + cr * rc.tmax);
-                s_tm[e] = rc.tmax;
-            }
-        };
-        for (int kc = (kmin >> pcs) << pcs; kc <= kmax; kc += PC) {
-            __syncthreads(); // previous pass fully consumed (first pass: acc initialised)
-            for (int e0 = threadIdx.x; e0 < fill; e0 += blockDim.x * kFillBatch) {
-                Rec rc[kFillBatch];
+    Rec24 pre[kFillBatch];
 #pragma unroll
-                for (int q = 0; q < kFillBatch; ++q) rc[q] = load(kc, e0 + q * blockDim.x); // loads first
+    for (int q = 0; q < kFillBatch; ++q) pre[q] = stage_load(g, kmin, threadIdx.x + q * blockDim.x);
 #pragma unroll
-                for (int q = 0; q < kFillBatch; ++q) store(e0 + q * blockDim.x, rc[q]);
+    for (int q = 0; q < kFillBatch; ++q) stage_store(g, s_pair[0], s_tm[0], threadIdx.x + q * blockDim.x, pre[q]);
+    for (int e = threadIdx.x + kFillBatch * blockDim.x; e < TS; e += blockDim.x)
+        stage_store(g, s_pair[0], s_tm[0], e, stage_load(g, kmin, e));
+    __syncthreads();
+
+    const int nitems = nmb * halves;
+    for (int k = kmin; k <= kmax; ++k) {
+        const int cur = (k - kmin) & 1;
+        const double2 *pair = s_pair[cur];
+        const double *tmv = s_tm[cur];
+        if (k < kmax) { // records of the next split point: in flight during this pass
+#pragma unroll
+            for (int q = 0; q < kFillBatch; ++q) pre[q] = stage_load(g, k + 1, threadIdx.x + q * blockDim.x);
+        }
+        for (int item = wave; item < nitems; item += nw) {
+            const int mb = item / halves, hf = item - mb * halves;
+            const int mp0 = mB0 + 8 * mb;                       // first m' of the block
+            int mlo = imax(mA0, a_g0 - (mp0 + 7)), mhi = imin(mA1, a_g1 - mp0);
+            if (halves == 2) { // two items per block of m': lower and upper half of the m range
+                const int mid = mlo + ((mhi - mlo + 1) >> 1);
+                if (hf == 0) mhi = mid - 1; else mlo = mid;
             }
-            __syncthreads();
-            const int kl0 = imax(0, kmin - kc), nk = imin(PC - 1, kmax - kc) - kl0 + 1;
-            for (int item = wave; item < nk * nmb; item += nw) {
-                const int kq = item / nmb, mb = item - kq * nmb, kl = kl0 + kq, k = kc + kl;
-                const int mp0 = mB0 + 8 * mb;                       // first m' of the block
-                const int mlo = imax(mA0, a_g0 - (mp0 + 7)), mhi = imin(mA1, a_g1 - mp0);
-                if (mlo > mhi) continue;
-                double bb2[8], bbt[8], btm[8], acc[8];
+            if (mlo > mhi) continue;
+            double bb2[8], bbt[8], btm[8], acc[8];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int o = ((nA + 8 * mb + i) * PC + kl) * 8 + vl;
-                    const double2 p = s_pair[o];
-                    bb2[i] = p.x; bbt[i] = p.y; btm[i] = s_tm[o];
-                    acc[i] = kNone;
-                }
-                const double kd = (double)k;
-                const int len = mhi - mlo + 1, j0 = (8 - (len & 7)) & 7;
-                int mbase = mlo - j0; // step j of a group handles m = mbase + j; the first group may start at j0
-                const int aoff = mp0 - a_g0;
-                // one step: candidates (m, m'0 + i), i = 0..7, into the rotating minima; then the minimum
-                // of target m + m'0 is complete for this item
+            for (int i = 0; i < 8; ++i) {
+                const int o = (nA + 8 * mb + i) * 8 + vl;
+                const double2 p = pair[o];
+                bb2[i] = p.x; bbt[i] = p.y; btm[i] = tmv[o];
+                acc[i] = kNone;
+            }
+            const double kd = (double)k;
+            const int len = mhi - mlo + 1, j0 = (8 - (len & 7)) & 7;
+            int mbase = mlo - j0; // step j of a group handles m = mbase + j; the first group may start at j0
+            const int aoff = mp0 - a_g0;
+            // one step: candidates (m, m'0 + i), i = 0..7, into the rotating minima; then the minimum
+            // of target m + m'0 is complete for this item.  The left record of the NEXT step is
+            // read before this step's atomic, so that its latency hides behind the arithmetic
+            // (LDS operations complete in order, and the compiler may not move a read over an atomic).
+            const double2 *pa = pair + (mlo - mA0) * 8 + ul; // left record of the next step
+            const double *ta = tmv + (mlo - mA0) * 8 + ul;
+            double2 p = *pa;
+            double atm = *ta;
 #define OOB_STEP(j)                                                                                   \
     {                                                                                                 \
         const int m = mbase + (j);                                                                    \
-        const int o = ((m - mA0) * PC + kl) * 8 + ul;                                                 \
-        const double2 p = s_pair[o];                                                                  \
-        const double atm = s_tm[o];                                                                   \
+        pa += 8; ta += 8;                                                                             \
+        const double2 pn = *pa; /* may read one record past the last m: staged memory, unused */      \
+        const double tn = *ta;                                                                        \
         _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                               \
             const double T = atm >= btm[i] ? p.x + bb2[i] : p.y + bbt[i];                             \
             acc[((j) + i) & 7] = fmin(acc[((j) + i) & 7], T);                                         \
@@ -441,28 +476,35 @@ __global__ void __launch_bounds__(512) k_split_key(Tables t, int Sp, int fam, in
         const int row = imin(imax(m + aoff, -1), na) + 1;                                             \
         atomicMin(&s_acc[row * 64 + lane], (unsigned long long)__double_as_longlong(fma(acc[(j)], KS, kd))); \
         acc[(j)] = kNone;                                                                             \
+        p = pn; atm = tn;                                                                             \
     }
-                if (j0) {
+            if (j0) {
 #pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (j >= j0) OOB_STEP(j)
-                    mbase += 8;
-                }
-                for (; mbase <= mhi; mbase += 8) {
+                for (int j = 0; j < 8; ++j)
+                    if (j >= j0) OOB_STEP(j)
+                mbase += 8;
+            }
+            for (; mbase <= mhi; mbase += 8) {
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) OOB_STEP(j)
-                }
+                for (int j = 0; j < 8; ++j) OOB_STEP(j)
+            }
 #undef OOB_STEP
-                // the last step was j = 7 with m = mhi: minima 0..6 belong to targets mhi + m'0 + 1 + i
+            // the last step was j = 7 with m = mhi: minima 0..6 belong to targets mhi + m'0 + 1 + i
 #pragma unroll
-                for (int i = 0; i < 7; ++i) {
-                    const int row = imin(imax(mhi + 1 + i + aoff, -1), na) + 1;
-                    atomicMin(&s_acc[row * 64 + lane], (unsigned long long)__double_as_longlong(fma(acc[i], KS, kd)));
-                }
+            for (int i = 0; i < 7; ++i) {
+                const int row = imin(imax(mhi + 1 + i + aoff, -1), na) + 1;
+                atomicMin(&s_acc[row * 64 + lane], (unsigned long long)__double_as_longlong(fma(acc[i], KS, kd)));
             }
         }
+        if (k < kmax) {
+#pragma unroll
+            for (int q = 0; q < kFillBatch; ++q)
+                stage_store(g, s_pair[cur ^ 1], s_tm[cur ^ 1], threadIdx.x + q * blockDim.x, pre[q]);
+            for (int e = threadIdx.x + kFillBatch * blockDim.x; e < TS; e += blockDim.x)
+                stage_store(g, s_pair[cur ^ 1], s_tm[cur ^ 1], e, stage_load(g, k + 1, e));
+        }
+        __syncthreads(); // buffer cur fully consumed, buffer cur^1 complete
     }
-    __syncthreads();
     // merge into the level's keys: other segments of the same block do the same
     for (int e = threadIdx.x; e < na * 64; e += blockDim.x) {
         const unsigned long long key = s_acc[64 + e];
@@ -471,6 +513,20 @@ __global__ void __launch_bounds__(512) k_split_key(Tables t, int Sp, int fam, in
         const long long slot = ((long long)(s - 1) * NAall + aidx) * NT + tile;
         atomicMin(&t.partKey[slot * 64 + (e & 63)], key);
     }
+}
+
+// Per level: the list of (block, segment) workgroup tasks, written once per call.
+__global__ void k_seg_tab(Tables t) {
+    const int S = blockIdx.x + 2;
+    if (S > t.sh.Smax || threadIdx.x != 0) return;
+    const int L = t.sh.L, NB = nblocks_of(L), ubmax = (L - S) / 8;
+    int2 *out = t.seg_tab + t.seg_off[S];
+    int tt = 0, n = 0;
+    for (int d = NB - 1; d >= tile_dmin(S); --d)
+        for (int u = 0; u <= imin(ubmax, NB - 1 - d); ++u, ++tt) {
+            const int c = cdiv(tile_krange(L, S, u, u + d), kSegK);
+            for (int j = 0; j < c; ++j) out[n++] = make_int2(tt, u | ((u + d) << 8) | (j << 16));
+        }
 }
 
 // Sets n keys to "no such state".
@@ -702,7 +758,7 @@ long long part_slots(int L, int M, int n_max, int Nb) {
 }
 
 struct Carve {
-    size_t lvl_tab, PT, PF, PM, rec, kstar, choice, partT, partK, stack, flags, total;
+    size_t lvl_tab, PT, PF, PM, rec, kstar, choice, partT, partK, stack, flags, seg_tab, seg_off, total;
     long long recs, slots;
 };
 // Byte offsets of the workspace arrays, sized for the handle's maxima.
@@ -724,6 +780,10 @@ Carve carve(int L, int nodes, int M) {
     c.partK = o;   o = align_up(o + sizeof(int) * (size_t)c.slots * 64);
     c.stack = o;   o = align_up(o + sizeof(int) * ((size_t)nodes * (Smax + 1) * 4 + nodes + 2));
     c.flags = o;   o = align_up(o + sizeof(int) * 64);
+    long long segs = 0;
+    for (int S = 2; S <= Smax; ++S) segs += seg_count(L, S);
+    c.seg_tab = o; o = align_up(o + sizeof(int2) * (size_t)(segs + 1));
+    c.seg_off = o; o = align_up(o + sizeof(long long) * (OOB_MAX_L + 3));
     c.total = o;
     return c;
 }
@@ -755,7 +815,7 @@ constexpr size_t kLdsLimit = 160 * 1024; // gfx950: 160 KB of LDS per workgroup
 constexpr size_t kLdsPrefer = 64 * 1024; // at least two workgroups per compute unit
 
 // Launch shape of k_split for one family of one level.
-struct SplitPlan { int waves, groups, pc; size_t lds; };
+struct SplitPlan { int waves, groups, pc, cls, ntab, na; size_t lds; };
 bool plan_split(const Shape &sh, int Sp, int fam, SplitPlan *p) {
     int t_lo, t_hi;
     target_units(fam, Sp, sh.M, sh.n_max, &t_lo, &t_hi);
@@ -782,14 +842,13 @@ bool plan_split(const Shape &sh, int Sp, int fam, SplitPlan *p) {
     return true;
 }
 
-// Launch shape of k_split_key for one family of one level: pc = log2 of the k values per pass.
+// Launch shape of k_split_key for one family of one level.
 static int env_or(const char *name, int dflt) {
     const char *v = getenv(name);
     return v && *v ? atoi(v) : dflt;
 }
-static const size_t kKeyLdsPrefer = (size_t)env_or("OOB_TUNE_KEY_LDS_KB", 78) * 1024;
-static const int kKeyWaves = env_or("OOB_TUNE_KEY_WAVES", 6);
-static const int kKeyMaxPcs = env_or("OOB_TUNE_KEY_MAXPCS", 3);
+static const int kKeyWaves = env_or("OOB_TUNE_KEY_WAVES", 4);
+static const int kKeyHalves = env_or("OOB_TUNE_KEY_HALVES", 2);
 bool plan_split_key(const Shape &sh, int Sp, int fam, SplitPlan *p) {
     int t_lo, t_hi;
     target_units(fam, Sp, sh.M, sh.n_max, &t_lo, &t_hi);
@@ -809,12 +868,10 @@ bool plan_split_key(const Shape &sh, int Sp, int fam, SplitPlan *p) {
             if (mA0 <= mA1 && mB0 <= mB1) ntab = imax(ntab, mA1 - mA0 + 1 + 8 * cdiv(mB1 - mB0 + 1, 8));
         }
     }
-    const size_t acc = (size_t)(imin(cnt, kKeyTargets) + 2) * 64 * 8, per_k = (size_t)ntab * 8 * 24;
-    const int krange = imin(kSegK, sh.L - Sp + 2); // split points a workgroup handles
-    int pcs = 0;
-    while (pcs < kKeyMaxPcs && (1 << pcs) < krange && acc + (per_k << (pcs + 1)) <= kKeyLdsPrefer) ++pcs;
-    p->pc = pcs;
-    p->lds = acc + (per_k << pcs);
+    p->pc = kKeyHalves;
+    p->ntab = ntab;
+    p->na = imin(cnt, kKeyTargets);
+    p->lds = 0; // static LDS: see the capacity classes at the launch site
     p->waves = kKeyWaves;
     return true;
 }
@@ -898,6 +955,8 @@ static Tables make_tables(const oob_plan *h, const Shape &sh, int *status) {
     t.partK = (int *)(h->ws + h->cv.partK);
     t.stack = (int *)(h->ws + h->cv.stack);
     t.flags = (int *)(h->ws + h->cv.flags);
+    t.seg_tab = (int2 *)(h->ws + h->cv.seg_tab);
+    t.seg_off = (long long *)(h->ws + h->cv.seg_off);
     t.status = status;
     return t;
 }
@@ -908,22 +967,28 @@ static bool out_ok(const oob_templates *o) {
            o->status;
 }
 
-template <int PCS>
-static void launch_split_key_pc(const Tables &t, int S, int fam, const SplitPlan &sp, int NT, int NAall,
-                                hipStream_t st) {
-    if (sp.lds > kLdsPrefer)
-        (void)hipFuncSetAttribute((const void *)k_split_key<PCS>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)kLdsLimit);
-    hipLaunchKernelGGL(k_split_key<PCS>, dim3(seg_count(t.sh.L, S), S - 1, sp.groups), dim3(sp.waves * 64), sp.lds,
-                       st, t, S, fam, NT, NAall);
+template <int NTAB, int NA>
+static void launch_split_key_c(const Tables &t, int S, int fam, const SplitPlan &sp, int NT, int NAall,
+                               hipStream_t st) {
+    hipLaunchKernelGGL((k_split_key<NTAB, NA>), dim3(seg_count(t.sh.L, S), S - 1, sp.groups), dim3(sp.waves * 64), 0,
+                       st, t, S, fam, NT, NAall, sp.pc);
+}
+// LDS capacity classes of k_split_key: (tables staged, targets); the smallest that fits is used.
+static const int kKeyClasses[][2] = {{24, 16}, {48, 40}, {64, 48}, {96, 48}, {96, 64}, {136, 64}};
+static int key_class(int ntab, int na) {
+    for (int c = 0; c < 6; ++c)
+        if (ntab <= kKeyClasses[c][0] && na <= kKeyClasses[c][1]) return c;
+    return -1;
 }
 static void launch_split_key(const Tables &t, int S, int fam, const SplitPlan &sp, int NT, int NAall,
                              hipStream_t st) {
-    switch (sp.pc) {
-    case 0: launch_split_key_pc<0>(t, S, fam, sp, NT, NAall, st); break;
-    case 1: launch_split_key_pc<1>(t, S, fam, sp, NT, NAall, st); break;
-    case 2: launch_split_key_pc<2>(t, S, fam, sp, NT, NAall, st); break;
-    default: launch_split_key_pc<3>(t, S, fam, sp, NT, NAall, st); break;
+    switch (sp.cls) {
+    case 0: launch_split_key_c<24, 16>(t, S, fam, sp, NT, NAall, st); break;
+    case 1: launch_split_key_c<48, 40>(t, S, fam, sp, NT, NAall, st); break;
+    case 2: launch_split_key_c<64, 48>(t, S, fam, sp, NT, NAall, st); break;
+    case 3: launch_split_key_c<96, 48>(t, S, fam, sp, NT, NAall, st); break;
+    case 4: launch_split_key_c<96, 64>(t, S, fam, sp, NT, NAall, st); break;
+    default: launch_split_key_c<136, 64>(t, S, fam, sp, NT, NAall, st); break;
     }
 }
 
@@ -955,19 +1020,21 @@ extern "C" int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L
     sh.cap = mem_cap; sh.count = n_max - n_min + 1;
     sh.Smax = smax_of(L, n_max, M, microbatches);
     // launch shapes first, so that nothing is enqueued when a level cannot be staged in LDS
+    int force_plain = 0; // a level's tables exceed the keyed kernel's LDS classes: plain kernel everywhere
     for (int S = 2; S <= sh.Smax; ++S)
         for (int fam = 0; fam < 2; ++fam) {
             SplitPlan sp;
             if (plan_split(sh, S, fam, &sp) && sp.lds > kLdsLimit) return OOB_ECAPACITY;
-            if (plan_split_key(sh, S, fam, &sp) && sp.lds > kLdsLimit) return OOB_ECAPACITY;
+            if (plan_split_key(sh, S, fam, &sp) && key_class(sp.ntab, sp.na) < 0) force_plain = 1;
         }
     const Tables t = make_tables(h, sh, (int *)out->status);
     hipStream_t st = (hipStream_t)stream;
     work_counts(sh, (long long *)&out->states, (long long *)&out->candidates);
 
-    hipLaunchKernelGGL(k_setup, dim3(1), dim3(OOB_MAX_GPUS + 1), 0, st, t, *profile);
+    hipLaunchKernelGGL(k_setup, dim3(1), dim3(OOB_MAX_GPUS + 1), 0, st, t, *profile, force_plain);
     hipLaunchKernelGGL(k_level1, dim3(tile_count(L, 1), M), dim3(64), 0, st, t,
                        (const long long *)profile->boundary_ns);
+    if (sh.Smax >= 2) hipLaunchKernelGGL(k_seg_tab, dim3(sh.Smax - 1), dim3(64), 0, st, t);
     {
         const long long nkeys = part_slots(L, M, n_max, microbatches) * 64;
         hipLaunchKernelGGL(k_fill_keys, dim3((unsigned)((nkeys + 255) / 256)), dim3(256), 0, st, t.partKey, nkeys);
@@ -981,7 +1048,8 @@ extern "C" int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L
             SplitPlan sp, kp;
             if (!plan_split(sh, S, fam, &sp) || !plan_split_key(sh, S, fam, &kp)) continue;
             // exactly one of the two does the work: the set-up kernel decides (flags[0])
-            launch_split_key(t, S, fam, kp, NT, NAall, st);
+            kp.cls = key_class(kp.ntab, kp.na);
+            if (!force_plain) launch_split_key(t, S, fam, kp, NT, NAall, st);
             if (sp.pc == 4) launch_split<4>(t, S, fam, sp, NT, NAall, st);
             else if (sp.pc == 2) launch_split<2>(t, S, fam, sp, NT, NAall, st);
             else launch_split<1>(t, S, fam, sp, NT, NAall, st);
