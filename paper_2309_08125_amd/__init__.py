@@ -2,5 +2,6 @@
 from .binding import (  # noqa: F401
     OOB_ECAPACITY, OOB_EHIP, OOB_EINVAL, OOB_EOVERFLOW, OOB_FORBIDDEN, OOB_OK, SYMBOLS,
     DeviceProfile, DeviceTemplates, Planner, load, oob_plan_create, oob_plan_destroy,
-    oob_plan_max_stages, oob_plan_templates, oob_plan_workspace_size, template_stages,
+    oob_plan_max_stages, oob_plan_templates, oob_plan_templates_batch, oob_plan_workspace_size,
+    template_stages,
 )

@@ -106,6 +106,22 @@ def oob_plan_templates(h, profile: oob_profile, L, n_min, n_max, gpus_per_node, 
                                      C.c_void_p(stream_ptr))
 
 
+def oob_plan_templates_batch(h, profiles, Ls, n_mins, n_maxs, gpus, microbatches, mem_caps, fs, outs,
+                             stream_ptr) -> int:
+    """profiles: list of oob_profile, outs: list of oob_templates (filled in place), the rest
+    lists of ints."""
+    n = len(profiles)
+    prof_arr = (oob_profile * n)(*profiles)
+    out_arr = (oob_templates * n)(*outs)
+    ints = lambda xs: (C.c_int * n)(*xs)
+    rc = load().oob_plan_templates_batch(h, n, prof_arr, ints(Ls), ints(n_mins), ints(n_maxs), ints(gpus),
+                                         ints(microbatches), (C.c_int64 * n)(*mem_caps), ints(fs), out_arr,
+                                         C.c_void_p(stream_ptr))
+    for i in range(n):  # host fields written by the library
+        outs[i].states, outs[i].candidates = out_arr[i].states, out_arr[i].candidates
+    return rc
+
+
 def oob_plan_destroy(h) -> int:
     return load().oob_plan_destroy(h)
 
@@ -202,6 +218,23 @@ class Planner:
                                 inp.microbatches, inp.mem_cap, inp.f, out.c, s.cuda_stream)
         check(rc, "oob_plan_templates")
         self.last_L = inp.L
+
+    def plan_batch(self, inps) -> List[Dict[str, "object"]]:
+        """Independent jobs through oob_plan_templates_batch (one after the other on the stream)."""
+        import torch
+
+        profs = [DeviceProfile(inp, self.device) for inp in inps]
+        outs = [self.new_outputs(inp) for inp in inps]
+        s = torch.cuda.current_stream(self.device)
+        rc = oob_plan_templates_batch(self.h, [p.c for p in profs], [i.L for i in inps],
+                                      [i.n_min for i in inps], [i.n_max for i in inps],
+                                      [i.gpus_per_node for i in inps], [i.microbatches for i in inps],
+                                      [i.mem_cap for i in inps], [i.f for i in inps],
+                                      [o.c for o in outs], s.cuda_stream)
+        check(rc, "oob_plan_templates_batch")
+        self.last_L = inps[-1].L if inps else 0
+        torch.cuda.synchronize(self.device)
+        return [o.to_host() for o in outs]
 
     def plan(self, inp) -> Dict[str, "object"]:
         import torch

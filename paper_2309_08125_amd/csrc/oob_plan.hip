@@ -63,7 +63,7 @@ struct Tables {
     int *partK;           // same shape: first k reaching the minimum
     int *stack;           // backtracking stacks / coverage ring
     int2 *seg_tab;        // per level: (tile index, ub | vb << 8 | segment << 16) of every split task
-    long long *seg_off;   // [Smax+2] first entry of level S' in seg_tab
+    int seg_stride;       // entries reserved per level in seg_tab (level S' starts at (S'-2) * seg_stride)
     int *flags;           // [0] 1: (total, k) keys fit a double (k_split_key runs), 0: k_split runs
     int *status;
 };
@@ -118,13 +118,11 @@ __global__ void k_setup(Tables t, oob_profile prof, int force_plain) {
         }
         s_worst[0] = xs;
         if (bad) atomicMax(&s_bad, bad);
-        long long tab = 0, seg = 0;
+        long long tab = 0;
         for (int S = 1; S <= t.sh.Smax + 1; ++S) {
             t.lvl_tab[S] = tab;
-            t.seg_off[S] = seg;
             const int nd = dhi_of(S, M, t.sh.n_max) - dlo_of(S, M) + 1;
             if (S <= t.sh.Smax && nd > 0) tab += nd;
-            if (S >= 2 && S <= t.sh.Smax) seg += seg_count(L, S);
         }
     }
     __syncthreads();
@@ -385,7 +383,7 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
     const int s = blockIdx.y + 1, r = Sp - s;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const int ul = lane >> 3, vl = lane & 7;
-    const int2 sg = t.seg_tab[t.seg_off[Sp] + blockIdx.x]; // x: tile index, y: ub | vb << 8 | seg << 16
+    const int2 sg = t.seg_tab[(long long)(Sp - 2) * t.seg_stride + blockIdx.x]; // x: tile index, y: ub | vb << 8 | seg << 16
     const int tile = sg.x, ub = sg.y & 255, vb = (sg.y >> 8) & 255, seg = sg.y >> 16;
     const int fam_base = fam ? M - 2 : -1;
     int t_lo, t_hi;
@@ -520,7 +518,7 @@ __global__ void k_seg_tab(Tables t) {
     const int S = blockIdx.x + 2;
     if (S > t.sh.Smax || threadIdx.x != 0) return;
     const int L = t.sh.L, NB = nblocks_of(L), ubmax = (L - S) / 8;
-    int2 *out = t.seg_tab + t.seg_off[S];
+    int2 *out = t.seg_tab + (long long)(S - 2) * t.seg_stride;
     int tt = 0, n = 0;
     for (int d = NB - 1; d >= tile_dmin(S); --d)
         for (int u = 0; u <= imin(ubmax, NB - 1 - d); ++u, ++tt) {
@@ -550,12 +548,12 @@ __global__ void __launch_bounds__(64) k_select(Tables t, int Sp, int NT, int NAa
         const double KS = (double)(1 << key_bits(L)), inv = 1.0 / KS;
         const long long o0 = ((long long)aidx * NT + blockIdx.x) * 64 + lane, os = (long long)NAall * NT * 64;
         double bkey = kNone;
-        for (int s0 = 1; s0 < Sp; s0 += 8) { // eight independent loads in flight
-            double key[8];
+        for (int s0 = 1; s0 < Sp; s0 += 16) { // sixteen independent loads in flight
+            double key[16];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) key[q] = s0 + q < Sp ? t.partT[o0 + (s0 + q - 1) * os] : kNone;
+            for (int q = 0; q < 16; ++q) key[q] = s0 + q < Sp ? t.partT[o0 + (s0 + q - 1) * os] : kNone;
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
+            for (int q = 0; q < 16; ++q) {
                 const double T = floor(key[q] * inv); // +inf stays +inf
                 if (T < best) { best = T; bs = s0 + q; bkey = key[q]; }
             }
@@ -579,11 +577,25 @@ __global__ void __launch_bounds__(64) k_select(Tables t, int Sp, int NT, int NAa
         const double cl = t.sh.Nb > 0 ? -(double)r : 3.0 * r, cr = t.sh.Nb > 0 ? 0.0 : 4.0 * bs;
         int bm = 0;
         Rec a = out, b = out;
-        for (int m = mlo; m <= mhi; ++m) { // first m whose candidate equals the minimum
-            a = t.rec[rec_index(t, bs, fam.fam_base + m, u, bk)];
-            b = t.rec[rec_index(t, r, fam.fam_base + fam.units - m, bk, v)];
-            const double T = a.tmax >= b.tmax ? (a.T + cl * a.tmax) + 2.0 * b.T1 : a.T1 + (b.T + cr * b.tmax);
-            if (T == best) { bm = m; break; }
+        // first m whose candidate equals the minimum; four candidates' records in flight at a time
+        const long long tabA = (t.lvl_tab[bs] - dlo_of(bs, M) + fam.fam_base) * (long long)t.tab_recs +
+                               (long long)tri_index(u >> 3, bk >> 3, t.NB) * 64 + ((u & 7) << 3) + (bk & 7);
+        const long long tabB = (t.lvl_tab[r] - dlo_of(r, M) + fam.fam_base + fam.units) * (long long)t.tab_recs +
+                               (long long)tri_index(bk >> 3, v >> 3, t.NB) * 64 + ((bk & 7) << 3) + (v & 7);
+        for (int m0 = mlo; m0 <= mhi && bm == 0; m0 += 4) {
+            Rec ra[4], rb[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int m = imin(m0 + q, mhi);
+                ra[q] = t.rec[tabA + (long long)m * t.tab_recs];
+                rb[q] = t.rec[tabB - (long long)m * t.tab_recs];
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const double T = ra[q].tmax >= rb[q].tmax ? (ra[q].T + cl * ra[q].tmax) + 2.0 * rb[q].T1
+                                                          : ra[q].T1 + (rb[q].T + cr * rb[q].tmax);
+                if (bm == 0 && m0 + q <= mhi && T == best) { bm = m0 + q; a = ra[q]; b = rb[q]; }
+            }
         }
         if (bm == 0) {
 #ifdef OOB_EMU_DEBUG
@@ -758,7 +770,7 @@ long long part_slots(int L, int M, int n_max, int Nb) {
 }
 
 struct Carve {
-    size_t lvl_tab, PT, PF, PM, rec, kstar, choice, partT, partK, stack, flags, seg_tab, seg_off, total;
+    size_t lvl_tab, PT, PF, PM, rec, kstar, choice, partT, partK, stack, flags, seg_tab, total;
     long long recs, slots;
 };
 // Byte offsets of the workspace arrays, sized for the handle's maxima.
@@ -780,10 +792,8 @@ Carve carve(int L, int nodes, int M) {
     c.partK = o;   o = align_up(o + sizeof(int) * (size_t)c.slots * 64);
     c.stack = o;   o = align_up(o + sizeof(int) * ((size_t)nodes * (Smax + 1) * 4 + nodes + 2));
     c.flags = o;   o = align_up(o + sizeof(int) * 64);
-    long long segs = 0;
-    for (int S = 2; S <= Smax; ++S) segs += seg_count(L, S);
-    c.seg_tab = o; o = align_up(o + sizeof(int2) * (size_t)(segs + 1));
-    c.seg_off = o; o = align_up(o + sizeof(long long) * (OOB_MAX_L + 3));
+    // the task list of a level is longest at S' = 2; every level gets that many entries
+    c.seg_tab = o; o = align_up(o + sizeof(int2) * ((size_t)imax(Smax - 1, 1) * seg_count(L, 2) + 1));
     c.total = o;
     return c;
 }
@@ -956,7 +966,7 @@ static Tables make_tables(const oob_plan *h, const Shape &sh, int *status) {
     t.stack = (int *)(h->ws + h->cv.stack);
     t.flags = (int *)(h->ws + h->cv.flags);
     t.seg_tab = (int2 *)(h->ws + h->cv.seg_tab);
-    t.seg_off = (long long *)(h->ws + h->cv.seg_off);
+    t.seg_stride = seg_count(sh.L, 2);
     t.status = status;
     return t;
 }
