@@ -48,6 +48,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=4, help="workload 1-4 (default: headline 4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="before the steps, run one device-to-device copy of this many MiB (a plain "
+                         "copy kernel of known size, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build plans on ONE GPU (no collectives); run with --gpus 1. "
@@ -67,6 +70,11 @@ def main():
     out = planner.new_outputs(inp)
     planner.level_timing(True)
 
+    if args.calibrate_copy_mib > 0:
+        src = torch.ones(args.calibrate_copy_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         planner.enqueue(prof, out)
     torch.cuda.synchronize()

@@ -371,12 +371,12 @@ __device__ __forceinline__ void stage_store(const Stage &g, double2 *pair, doubl
 // One split point per pass, two LDS buffers: while the waves work on k from one buffer, every
 // thread has the records of k+1 in flight from HBM/L2 and drops them into the other buffer
 // before the single barrier of the pass.
-template <int NTAB, int NA>
+template <int NTAB, int NA, int NBUF>
 __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, int NT, int NAall, int halves) {
     // Static, separate arrays: the compiler then knows that the key merges (atomics on s_acc) never
     // touch the staged records, and keeps the reads of the next step ahead of them.
-    __shared__ double2 s_pair[2][NTAB * 8]; // [buffer][table][u or v]: (T + cl tmax, T1) / (2 T1, T + cr tmax)
-    __shared__ double s_tm[2][NTAB * 8];    // tmax
+    __shared__ double2 s_pair[NBUF][NTAB * 8]; // [buffer][table][u or v]: (T + cl tmax, T1) / (2 T1, T + cr tmax)
+    __shared__ double s_tm[NBUF][NTAB * 8];    // tmax
     __shared__ unsigned long long s_acc[(NA + 2) * 64]; // keys, rows 1..na
     if (t.flags[0] == 0) return;        // keys do not fit: k_split handles this job
     const int L = t.sh.L, M = t.sh.M, n_max = t.sh.n_max;
@@ -425,7 +425,7 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
 
     const int nitems = nmb * halves;
     for (int k = kmin; k <= kmax; ++k) {
-        const int cur = (k - kmin) & 1;
+        const int cur = NBUF == 2 ? (k - kmin) & 1 : 0, nxt = NBUF == 2 ? cur ^ 1 : 0;
         const double2 *pair = s_pair[cur];
         const double *tmv = s_tm[cur];
         if (k < kmax) { // records of the next split point: in flight during this pass
@@ -494,12 +494,13 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
                 atomicMin(&s_acc[row * 64 + lane], (unsigned long long)__double_as_longlong(fma(acc[i], KS, kd)));
             }
         }
+        if (NBUF == 1) __syncthreads(); // one buffer: everybody is done reading it before it is refilled
         if (k < kmax) {
 #pragma unroll
             for (int q = 0; q < kFillBatch; ++q)
-                stage_store(g, s_pair[cur ^ 1], s_tm[cur ^ 1], threadIdx.x + q * blockDim.x, pre[q]);
+                stage_store(g, s_pair[nxt], s_tm[nxt], threadIdx.x + q * blockDim.x, pre[q]);
             for (int e = threadIdx.x + kFillBatch * blockDim.x; e < TS; e += blockDim.x)
-                stage_store(g, s_pair[cur ^ 1], s_tm[cur ^ 1], e, stage_load(g, k + 1, e));
+                stage_store(g, s_pair[nxt], s_tm[nxt], e, stage_load(g, k + 1, e));
         }
         __syncthreads(); // buffer cur fully consumed, buffer cur^1 complete
     }
@@ -853,7 +854,7 @@ bool plan_split(const Shape &sh, int Sp, int fam, SplitPlan *p) {
 }
 
 // Launch shape of k_split_key for one family of one level.
-static int env_or(const char *name, int dflt) {
+int env_or(const char *name, int dflt) {
     const char *v = getenv(name);
     return v && *v ? atoi(v) : dflt;
 }
@@ -980,8 +981,13 @@ static bool out_ok(const oob_templates *o) {
 template <int NTAB, int NA>
 static void launch_split_key_c(const Tables &t, int S, int fam, const SplitPlan &sp, int NT, int NAall,
                                hipStream_t st) {
-    hipLaunchKernelGGL((k_split_key<NTAB, NA>), dim3(seg_count(t.sh.L, S), S - 1, sp.groups), dim3(sp.waves * 64), 0,
-                       st, t, S, fam, NT, NAall, sp.pc);
+    static const int nbuf = env_or("OOB_TUNE_KEY_NBUF", 1);
+    if (nbuf == 2)
+        hipLaunchKernelGGL((k_split_key<NTAB, NA, 2>), dim3(seg_count(t.sh.L, S), S - 1, sp.groups),
+                           dim3(sp.waves * 64), 0, st, t, S, fam, NT, NAall, sp.pc);
+    else
+        hipLaunchKernelGGL((k_split_key<NTAB, NA, 1>), dim3(seg_count(t.sh.L, S), S - 1, sp.groups),
+                           dim3(sp.waves * 64), 0, st, t, S, fam, NT, NAall, sp.pc);
 }
 // LDS capacity classes of k_split_key: (tables staged, targets); the smallest that fits is used.
 static const int kKeyClasses[][2] = {{24, 16}, {48, 40}, {64, 48}, {96, 48}, {96, 64}, {136, 64}};
