@@ -381,7 +381,9 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
     if (t.flags[0] == 0) return;        // keys do not fit: k_split handles this job
     const int L = t.sh.L, M = t.sh.M, n_max = t.sh.n_max;
     const int s = blockIdx.y + 1, r = Sp - s;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    // the wave index is the same in all lanes: say so, and everything derived from it (work item,
+    // m range, key row) is scalar arithmetic and scalar branches
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
     const int ul = lane >> 3, vl = lane & 7;
     const int2 sg = t.seg_tab[(long long)(Sp - 2) * t.seg_stride + blockIdx.x]; // x: tile index, y: ub | vb << 8 | seg << 16
     const int tile = sg.x, ub = sg.y & 255, vb = (sg.y >> 8) & 255, seg = sg.y >> 16;
