@@ -425,7 +425,12 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
         stage_store(g, s_pair[0], s_tm[0], e, stage_load(g, kmin, e));
     __syncthreads();
 
-    const int nitems = nmb * halves;
+    // Work items of a split point: the 8-blocks of m'.  Whole blocks go round robin over the waves;
+    // the blocks left over after the last full round are cut into `parts` pieces of their m range so
+    // that every wave gets one (halves = 0 disables the cutting).
+    const int rem = nmb % nw, full = nmb - rem;
+    const int parts = (halves && rem) ? imax(1, nw / rem) : 1;
+    const int nitems = full + rem * parts;
     for (int k = kmin; k <= kmax; ++k) {
         const int cur = NBUF == 2 ? (k - kmin) & 1 : 0, nxt = NBUF == 2 ? cur ^ 1 : 0;
         const double2 *pair = s_pair[cur];
@@ -435,12 +440,14 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
             for (int q = 0; q < kFillBatch; ++q) pre[q] = stage_load(g, k + 1, threadIdx.x + q * blockDim.x);
         }
         for (int item = wave; item < nitems; item += nw) {
-            const int mb = item / halves, hf = item - mb * halves;
+            const int cut = item >= full, jj = item - full;
+            const int mb = cut ? full + jj / parts : item, part = cut ? jj % parts : 0, np = cut ? parts : 1;
             const int mp0 = mB0 + 8 * mb;                       // first m' of the block
             int mlo = imax(mA0, a_g0 - (mp0 + 7)), mhi = imin(mA1, a_g1 - mp0);
-            if (halves == 2) { // two items per block of m': lower and upper half of the m range
-                const int mid = mlo + ((mhi - mlo + 1) >> 1);
-                if (hf == 0) mhi = mid - 1; else mlo = mid;
+            if (np > 1 && mlo <= mhi) { // piece `part` of `np` of the m range
+                const int len = mhi - mlo + 1, lo = mlo + len * part / np;
+                mhi = mlo + len * (part + 1) / np - 1;
+                mlo = lo;
             }
             if (mlo > mhi) continue;
             double bb2[8], bbt[8], btm[8], acc[8];
