@@ -19,23 +19,31 @@ sys.path.insert(0, ROOT)
 
 # Arithmetic per candidate split (s, k, m) in the int64 formulation of Eq. 1-3: 4 adds, one
 # 64-bit compare with 3 selects, one 64x32 multiply, one (cost, index) compare-and-select;
-# about 9 int64-class operations = 30 32-bit lane operations.  The kernels need fewer (see
-# the design doc); the roofline figure is quoted on this algorithmic count.
+# about 9 int64-class operations = 30 32-bit lane operations.  The kernels need fewer (6 fp64
+# vector instructions per executed candidate); the roofline figure is quoted on this
+# algorithmic count.
 OPS_PER_CANDIDATE = 30
 PEAK_LANE_OPS = 256 * 64 * 2.4e9  # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T 32-bit lane-ops/s
+# HBM bytes of the level kernels of one call on configuration 4, from the two rocprofv3 --pmc
+# runs (FETCH_SIZE, WRITE_SIZE) summarised in profiles/k_split_key_config4.md, scaled by what
+# the same counters read for a 256 MiB copy: 21.34 GB read + 5.68 GB written.
+HBM_BYTES_PER_CALL_CONFIG4 = 21.34e9 + 5.68e9
 
 
 def cpu_baseline(inp):
     """The CPU oracle, as it stands, on a bounded sample of the same workload."""
     from oracle import capi
 
-    sample = dataclasses.replace(inp, n_max=min(inp.n_max, 16))
+    cores = capi.lib().oob_oracle_threads()
+    # about 10 s of oracle time on 16 cores for the whole headline workload; fewer cores take
+    # the first nine node counts only
+    sample = inp if cores >= 16 else dataclasses.replace(inp, n_max=min(inp.n_max, 16))
     t0 = time.time()
     o = capi.Oracle(sample)
     dt = time.time() - t0
-    res = {"value": o.states / dt, "unit": "states/s", "cores": capi.lib().oob_oracle_threads(),
+    res = {"value": o.states / dt, "unit": "states/s", "cores": cores,
            "kind": "oracle", "seconds": round(dt, 2), "candidates_per_s": o.candidates / dt,
-           "sample": f"same profile, templates for {sample.n_min}..{sample.n_max} nodes only: "
+           "sample": f"same profile, templates for {sample.n_min}..{sample.n_max} nodes: "
                      f"{o.states} states, {o.candidates} candidates"}
     o.close()
     return res
@@ -93,6 +101,7 @@ def main():
     launches = max(1, Smax - 1)
     lvl_ms = sum(level_ms) / len(level_ms)
     achieved = cands * OPS_PER_CANDIDATE / (lvl_ms * 1e-3)
+    traffic = HBM_BYTES_PER_CALL_CONFIG4 / launches if args.config == 4 else None
     line = {
         "metric": "DP states/sec (wall-ms per full template set in ms_per_step)",
         "value": states * args.steps / elapsed,
@@ -107,7 +116,8 @@ def main():
                                f"N_b={inp.microbatches}, f={inp.f}",
                    "states": states, "candidates": cands, "levels": Smax},
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12,
-                     "unit": "T lane-op/s", "frac": achieved / PEAK_LANE_OPS, "traffic": None,
+                     "unit": "T lane-op/s", "frac": achieved / PEAK_LANE_OPS, "traffic": traffic,
+                     "traffic_unit": "HBM bytes per level (one launch group), rocprofv3 --pmc",
                      "kernel": "level kernels S'>=2 (divide/combine, Eq. 1-3)",
                      "ops_per_candidate": OPS_PER_CANDIDATE, "launches": launches,
                      "avg_launch_ms": lvl_ms / launches, "levels_ms_per_step": lvl_ms,
