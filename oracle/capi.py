@@ -16,7 +16,7 @@ def lib():
     global _lib
     if _lib is None:
         path = _build.LIB
-        if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
+        if not os.path.exists(path) or os.path.getmtime(path) < max(os.path.getmtime(x) for x in _build.SRCS):
             path = _build.build()
         L = C.CDLL(path)
         i64p, i32p = C.POINTER(C.c_int64), C.POINTER(C.c_int32)
@@ -42,6 +42,9 @@ def lib():
         L.oob_oracle_templates.restype = None
         L.oob_oracle_coverage.argtypes = [i32p, C.c_int, C.c_int, C.c_int, i32p, i32p, C.c_int]
         L.oob_oracle_coverage.restype = None
+        L.oob_oracle_instantiate.argtypes = [i32p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_uint16),
+                                             C.c_int64, C.POINTER(C.c_int64)]
+        L.oob_oracle_instantiate.restype = C.c_int64
         _lib = L
     return _lib
 
