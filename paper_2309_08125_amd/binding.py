@@ -21,6 +21,7 @@ _ERR = {OOB_EINVAL: "OOB_EINVAL", OOB_ECAPACITY: "OOB_ECAPACITY", OOB_EOVERFLOW:
 SYMBOLS = ["oob_plan_max_stages", "oob_plan_workspace_size", "oob_plan_create",
            "oob_plan_templates", "oob_plan_templates_batch", "oob_plan_destroy", "oob_plan_export_block",
            "oob_plan_level_timing", "oob_plan_last_level_ms", "oob_plan_export_flags"]
+INST_SYMBOLS = ["oob_inst_workspace_size", "oob_inst_count", "oob_inst_enumerate"]
 
 
 class oob_profile(C.Structure):
@@ -74,6 +75,13 @@ def load():
         L.oob_plan_export_flags.restype = C.c_int
         L.oob_plan_export_block.argtypes = [C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 7
         L.oob_plan_export_block.restype = C.c_int
+        L.oob_inst_workspace_size.argtypes = [C.c_int] * 3
+        L.oob_inst_workspace_size.restype = C.c_size_t
+        spec = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t]
+        L.oob_inst_count.argtypes = spec + [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oob_inst_count.restype = C.c_int
+        L.oob_inst_enumerate.argtypes = spec + [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oob_inst_enumerate.restype = C.c_int
         _lib = L
     return _lib
 
@@ -124,6 +132,25 @@ def oob_plan_templates_batch(h, profiles, Ls, n_mins, n_maxs, gpus, microbatches
 
 def oob_plan_destroy(h) -> int:
     return load().oob_plan_destroy(h)
+
+
+def oob_inst_workspace_size(p, N_hi, f) -> int:
+    return load().oob_inst_workspace_size(p, N_hi, f)
+
+
+def oob_inst_count(sizes_ptr, p, n0, N_lo, N_hi, f, dev_workspace_ptr, workspace_bytes, offsets_ptr,
+                   status_ptr, stream_ptr) -> int:
+    return load().oob_inst_count(C.c_void_p(sizes_ptr), p, n0, N_lo, N_hi, f, C.c_void_p(dev_workspace_ptr),
+                                 workspace_bytes, C.c_void_p(offsets_ptr), C.c_void_p(status_ptr),
+                                 C.c_void_p(stream_ptr))
+
+
+def oob_inst_enumerate(sizes_ptr, p, n0, N_lo, N_hi, f, dev_workspace_ptr, workspace_bytes, x_ptr, capacity,
+                       offsets_ptr, status_ptr, stream_ptr) -> int:
+    return load().oob_inst_enumerate(C.c_void_p(sizes_ptr), p, n0, N_lo, N_hi, f,
+                                     C.c_void_p(dev_workspace_ptr), workspace_bytes, C.c_void_p(x_ptr),
+                                     capacity, C.c_void_p(offsets_ptr), C.c_void_p(status_ptr),
+                                     C.c_void_p(stream_ptr))
 
 
 # ---- convenience layer over torch device memory ------------------------------------------
@@ -273,6 +300,61 @@ class Planner:
         if rc != OOB_OK:
             return None
         return {k: v.cpu().numpy().reshape(n, n) for k, v in bufs.items()}
+
+
+class Instantiator:
+    """Device buffers for oob_inst_count / oob_inst_enumerate of one (sizes, N' range, f)."""
+
+    def __init__(self, sizes, N_lo: int, N_hi: int, f: int, n0: int = 0, p: int = 0, device="cuda:0"):
+        """sizes: list of template sizes, or None for the consecutive sizes n0 .. n0+p-1."""
+        import torch
+
+        self.device = torch.device(device)
+        self.sizes = None if sizes is None else torch.tensor(list(sizes), dtype=torch.int32, device=self.device)
+        self.p = p if sizes is None else len(sizes)
+        self.n0, self.N_lo, self.N_hi, self.f = n0, N_lo, N_hi, f
+        nbytes = oob_inst_workspace_size(self.p, N_hi, f)
+        if nbytes == 0:
+            raise ValueError("oob_inst_workspace_size: arguments out of range")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.offsets = torch.zeros(N_hi - N_lo + 2, dtype=torch.int64, device=self.device)
+        self.status = torch.zeros(1, dtype=torch.int32, device=self.device)
+
+    def _spec(self):
+        return (self.sizes.data_ptr() if self.sizes is not None else 0, self.p, self.n0, self.N_lo, self.N_hi,
+                self.f, self.workspace.data_ptr(), self.workspace.numel())
+
+    def count(self):
+        """Offsets per N' (host array, last entry = total) and the device status."""
+        import torch
+
+        s = torch.cuda.current_stream(self.device)
+        check(oob_inst_count(*self._spec(), self.offsets.data_ptr(), self.status.data_ptr(), s.cuda_stream),
+              "oob_inst_count")
+        torch.cuda.synchronize(self.device)
+        return self.offsets.cpu().numpy(), int(self.status.item())
+
+    def enqueue(self, x, capacity: int) -> None:
+        """oob_inst_enumerate into the 16-bit tensor x ([p, capacity], read as uint16) on the current stream."""
+        import torch
+
+        s = torch.cuda.current_stream(self.device)
+        check(oob_inst_enumerate(*self._spec(), x.data_ptr() if x is not None else 0, capacity,
+                                 self.offsets.data_ptr(), self.status.data_ptr(), s.cuda_stream),
+              "oob_inst_enumerate")
+
+    def enumerate(self):
+        """(offsets, vectors [total, p] as a host array in list order, status)."""
+        import torch
+
+        off, st = self.count()
+        total = int(off[-1])
+        if st != OOB_OK:
+            return off, None, st
+        x = torch.empty((self.p, max(total, 1)), dtype=torch.int16, device=self.device)  # uint16 bits
+        self.enqueue(x, total)
+        torch.cuda.synchronize(self.device)
+        return off, x.cpu().numpy().view("uint16")[:, :total].T.copy(), int(self.status.item())
 
 
 def template_stages(r: dict, i: int):

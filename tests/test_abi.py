@@ -10,10 +10,10 @@ from paper_2309_08125_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "oob_plan.h")).read()
+def declared_symbols(header="oob_plan.h", prefix="oob_plan_"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(oob_plan_\w+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(" + prefix + r"\w+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -23,6 +23,37 @@ def test_library_exports_every_declared_symbol():
     for name in names:
         assert hasattr(lib, name), name
     assert sorted(B.SYMBOLS) == names
+    inst = declared_symbols("oob_inst.h", "oob_inst_")
+    assert len(inst) == 3
+    for name in inst:
+        assert hasattr(lib, name), name
+    assert sorted(B.INST_SYMBOLS) == inst
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["oob_inst.h", "oob_plan.h"]
+
+
+def test_instantiation_entry_points_validate_arguments_without_touching_the_gpu():
+    ws = P.oob_inst_workspace_size(57, 128, 8)
+    assert ws >= 58 * 129 * 10 * 8 and ws % 256 == 0
+    assert P.oob_inst_workspace_size(0, 10, 1) == 0
+    assert P.oob_inst_workspace_size(3, 5000, 1) == 0
+    assert P.oob_inst_workspace_size(3, 10, 255) == 0
+    fake = 0x10000  # never dereferenced: every call below fails its host-side checks
+    call = lambda **kw: P.oob_inst_count(kw.get("sizes", fake), kw.get("p", 3), kw.get("n0", 0),
+                                         kw.get("N_lo", 0), kw.get("N_hi", 10), kw.get("f", 1),
+                                         kw.get("ws", fake), kw.get("nbytes", 1 << 20), kw.get("off", fake),
+                                         kw.get("st", fake), 0)
+    assert call(p=0) == P.OOB_EINVAL
+    assert call(N_lo=11) == P.OOB_EINVAL
+    assert call(N_hi=4096) == P.OOB_EINVAL
+    assert call(f=-1) == P.OOB_EINVAL
+    assert call(ws=0) == P.OOB_EINVAL
+    assert call(ws=0x10001) == P.OOB_EINVAL          # not 256-byte aligned
+    assert call(off=0) == P.OOB_EINVAL
+    assert call(st=0) == P.OOB_EINVAL
+    assert call(sizes=0, n0=0) == P.OOB_EINVAL        # consecutive sizes need n0 >= 1
+    assert call(nbytes=64) == P.OOB_ECAPACITY
+    rc = P.oob_inst_enumerate(fake, 3, 0, 0, 10, 1, fake, 1 << 20, 0, 5, fake, fake, 0)
+    assert rc == P.OOB_EINVAL                        # capacity > 0 without an output array
 
 
 def test_max_stages_and_workspace_size():
