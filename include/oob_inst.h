@@ -33,10 +33,11 @@ extern "C" {
 
 /* Bytes of device workspace (256-byte aligned) the two calls below need: the table of list
  * lengths |X(p', N')| restricted to "at least q more pipelines", q = 0..f+1
- * ((p+1) (N_hi+1) (f+2) 64-bit counts).  0 if an argument is out of range. */
+ * ((N_hi+1) (f+2) rows of p+1 64-bit counts, rows padded to a multiple of 8).  0 if an
+ * argument is out of range. */
 size_t oob_inst_workspace_size(int p, int N_hi, int f);
 
-/* List lengths (Eq. 5 with lists replaced by their lengths).
+/* First call: list lengths (Eq. 5 with every list replaced by its length).
  *   sizes     [p] template sizes, strictly increasing, >= 1; NULL selects the consecutive
  *             sizes n0, n0+1, ..., n0+p-1 of the node specification (Section 4.1.1)
  *   N_lo..N_hi cluster sizes N' to enumerate (0 <= N_lo <= N_hi <= OOB_INST_MAX_N)
@@ -44,21 +45,25 @@ size_t oob_inst_workspace_size(int p, int N_hi, int f);
  *             (exclusive prefix sum); the last entry is the total
  *   status    [1] out: OOB_OK; OOB_EINVAL (sizes not positive and strictly increasing);
  *             OOB_EOVERFLOW (a list is longer than 2^62)
- * One workgroup; the work is p (N_hi+1) (f+2) table entries. */
+ * Fills the workspace with the table.  One workgroup; the work is p (N_hi+1) (f+2) table
+ * entries of at most N_hi / n terms each. */
 int oob_inst_count(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, int f,
                    void *dev_workspace, size_t workspace_bytes,
                    int64_t *offsets, int32_t *status, void *stream);
 
-/* The vectors themselves, structure-of-arrays: vector i of the concatenated lists (N' = N_lo
- * first; offsets[] as above tells where each N' starts) has its counts at
+/* Second call: the vectors themselves.  Requires oob_inst_count with the SAME sizes, p, n0,
+ * N_lo, N_hi, f, workspace, offsets and status earlier on the same stream (or completed), and
+ * the workspace and offsets untouched since: the caller reads offsets' last entry in between to
+ * size x.  Structure-of-arrays: vector i of the concatenated lists (N' = N_lo first;
+ * offsets[] tells where each N' starts) has its counts at
  *     x[j * capacity + i],  j = 0..p-1                     (uint16: x_j <= N_hi)
- * so that the count of one template over consecutive vectors is contiguous.  Recomputes the
- * list lengths (the call is self-contained), then every vector is produced independently from
- * its position in the list.  If the total exceeds `capacity` nothing is written and *status =
- * OOB_ECAPACITY; offsets[] is valid in either case.  Entries i >= total are left untouched. */
+ * so that the count of one template over consecutive vectors is contiguous.  Every vector is
+ * produced independently from its position in the list.  Does nothing unless *status is
+ * OOB_OK; if the total exceeds `capacity` nothing is written and *status = OOB_ECAPACITY.
+ * Entries i >= total are left untouched. */
 int oob_inst_enumerate(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, int f,
                        void *dev_workspace, size_t workspace_bytes,
-                       uint16_t *x, int64_t capacity, int64_t *offsets, int32_t *status,
+                       uint16_t *x, int64_t capacity, const int64_t *offsets, int32_t *status,
                        void *stream);
 
 #ifdef __cplusplus

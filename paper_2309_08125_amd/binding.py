@@ -335,7 +335,8 @@ class Instantiator:
         return self.offsets.cpu().numpy(), int(self.status.item())
 
     def enqueue(self, x, capacity: int) -> None:
-        """oob_inst_enumerate into the 16-bit tensor x ([p, capacity], read as uint16) on the current stream."""
+        """oob_inst_enumerate into the 16-bit tensor x ([p, capacity], read as uint16) on the current stream;
+        count() must have run for this object before."""
         import torch
 
         s = torch.cuda.current_stream(self.device)

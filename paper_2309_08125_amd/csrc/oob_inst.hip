@@ -20,85 +20,103 @@
 namespace oob_inst {
 
 constexpr long long kSat = 1ll << 62; // counts saturate here; a saturated total is an error
+constexpr int kGroup = 8;             // counts a lane reads at once (64 bytes)
 
+// Count table: row (N', q) holds C(j, N', q) for j = 0..p, padded to whole groups, so that the
+// counts a position is compared with (same N', same q, descending j) are contiguous.
 struct Spec {
     const int *sizes; // may be null: consecutive from n0
-    int p, n0, N_lo, N_hi, Q; // Q = f + 1
-    long long *cnt;           // [(p+1)][(N_hi+1)][(Q+1)]
+    int p, n0, N_lo, N_hi, Q, R; // Q = f + 1; R = row length
+    long long *cnt;              // [(N_hi+1)][(Q+1)][R]
 };
 
+__host__ __device__ inline int row_len(int p) { return (p + 1 + kGroup - 1) / kGroup * kGroup; }
 __device__ __forceinline__ int size_of(const Spec &s, int j) { return s.sizes ? s.sizes[j] : s.n0 + j; }
-__device__ __forceinline__ long long cnt_index(const Spec &s, int j, int N, int q) {
-    return ((long long)j * (s.N_hi + 1) + N) * (s.Q + 1) + q;
-}
 __device__ __forceinline__ long long sat_add(long long a, long long b) {
     const unsigned long long c = (unsigned long long)a + (unsigned long long)b; // both <= 2^62: fits 64 bits
     return c > (unsigned long long)kSat ? kSat : (long long)c;
 }
 
-// One workgroup.  Plane j of the table needs plane j-1 only, and inside a plane the recurrence
-// along N' unrolls into a sum over the number i of size-n pipelines:
+// One workgroup.  Plane j of the table (all N', q) needs plane j-1 only, and inside a plane the
+// recurrence along N' unrolls into a sum over the number i of size-n pipelines:
 //     C(j, N', q) = sum_{i >= 0, i n <= N'} C(j-1, N' - i n, max(q - i, 0)),
-// so all entries of a plane are independent: one barrier per template size.
-__global__ void __launch_bounds__(1024) k_inst_count(Spec s, long long capacity, long long *offsets, int *status) {
+// so all entries of a plane are independent: one barrier per template size.  With IN_LDS the
+// previous and the current plane live in LDS (two planes of (N_hi+1)(Q+1) counts); otherwise
+// the previous plane is read back from the table.
+template <bool IN_LDS>
+__global__ void __launch_bounds__(1024) k_inst_count(Spec s, long long *offsets, int *status) {
+    HIP_DYNAMIC_SHARED(long long, s_dyn) // IN_LDS: two planes; then reused for the prefix sum
     __shared__ int s_bad;
-    __shared__ long long s_tot[OOB_INST_MAX_N + 2];
-    const int plane = (s.N_hi + 1) * (s.Q + 1);
+    const int QQ = s.Q + 1, plane = (s.N_hi + 1) * QQ, len = s.N_hi - s.N_lo + 1;
     if (threadIdx.x == 0) s_bad = 0;
     __syncthreads();
     for (int j = threadIdx.x; j < s.p; j += blockDim.x) {
         const int n = size_of(s, j);
         if (n < 1 || (j > 0 && n <= size_of(s, j - 1))) s_bad = 1;
     }
-    for (int e = threadIdx.x; e < plane; e += blockDim.x) s.cnt[e] = e == 0 ? 1 : 0; // C(0, ., .)
+    for (int e = threadIdx.x; e < plane; e += blockDim.x) { // C(0, ., .)
+        const long long c = e == 0 ? 1 : 0;
+        s.cnt[(long long)e * s.R] = c;
+        if (IN_LDS) s_dyn[e] = c;
+    }
     __syncthreads();
     if (s_bad) { // uniform: every thread leaves here
-        for (int i = threadIdx.x; i <= s.N_hi - s.N_lo + 1; i += blockDim.x) offsets[i] = 0;
+        for (int i = threadIdx.x; i <= len; i += blockDim.x) offsets[i] = 0;
         if (threadIdx.x == 0) *status = OOB_EINVAL;
         return;
     }
     for (int j = 1; j <= s.p; ++j) {
         const int n = size_of(s, j - 1);
-        const long long *prev = s.cnt + (long long)(j - 1) * plane;
-        long long *cur = s.cnt + (long long)j * plane;
+        const long long *prev = IN_LDS ? s_dyn + ((j - 1) & 1) * plane : s.cnt + (j - 1);
+        const long long pstride = IN_LDS ? 1 : s.R;
+        long long *cur = s_dyn + (j & 1) * plane;
         for (int e = threadIdx.x; e < plane; e += blockDim.x) {
-            const int N = e / (s.Q + 1), q = e - N * (s.Q + 1);
+            const int N = e / QQ, q = e - N * QQ;
             long long sum = 0;
             for (int i = 0, Ni = N; Ni >= 0; ++i, Ni -= n) {
                 const int qi = q - i > 0 ? q - i : 0;
-                sum = sat_add(sum, prev[Ni * (s.Q + 1) + qi]);
+                sum = sat_add(sum, prev[(long long)(Ni * QQ + qi) * pstride]);
             }
-            cur[e] = sum;
+            s.cnt[(long long)e * s.R + j] = sum;
+            if (IN_LDS) cur[e] = sum;
         }
-        __syncthreads(); // plane j complete (global memory, same workgroup)
+        __syncthreads(); // plane j complete (LDS, or global memory written by this workgroup)
     }
     // exclusive prefix over N' = N_lo..N_hi of the filtered list lengths C(p, N', f+1)
-    const int len = s.N_hi - s.N_lo + 1;
     for (int i = threadIdx.x; i < len; i += blockDim.x)
-        s_tot[i] = s.cnt[cnt_index(s, s.p, s.N_lo + i, s.Q)];
+        s_dyn[i] = s.cnt[((long long)(s.N_lo + i) * QQ + s.Q) * s.R + s.p];
     __syncthreads();
     if (threadIdx.x == 0) {
         long long run = 0;
         for (int i = 0; i < len; ++i) {
-            const long long c = s_tot[i];
-            s_tot[i] = run;
+            const long long c = s_dyn[i];
+            s_dyn[i] = run;
             run = sat_add(run, c);
         }
-        s_tot[len] = run;
-        *status = run >= kSat ? OOB_EOVERFLOW : (capacity >= 0 && run > capacity ? OOB_ECAPACITY : OOB_OK);
+        s_dyn[len] = run;
+        *status = run >= kSat ? OOB_EOVERFLOW : OOB_OK;
     }
     __syncthreads();
-    for (int i = threadIdx.x; i <= len; i += blockDim.x) offsets[i] = s_tot[i];
+    for (int i = threadIdx.x; i <= len; i += blockDim.x) offsets[i] = s_dyn[i];
 }
 
-// One lane per output vector (grid-stride).  Lanes of a wave hold consecutive list positions,
-// which share most of their path through the table: the count loads are mostly broadcasts and
-// the stores of one template are 128 contiguous bytes per wave.
-__global__ void __launch_bounds__(256) k_inst_unrank(Spec s, const long long *offsets, const int *status,
+// One lane per output vector (grid-stride).  A vector at position rho of the list of (N', q)
+// over the first j sizes has its highest non-zero count at the largest i < j with
+// C(i, N', q) <= rho (the lists over fewer sizes are prefixes of the list over more); it then
+// continues at position rho - C(i, N', q) of (N' - n_i, q - 1) over the first i+1 sizes.  The
+// sizes are visited in groups of kGroup from the top: all lanes take the same trip through
+// the groups, so the kGroup counts of a group are stored by whole waves (128 contiguous bytes
+// per template), and a lane's 64-byte read fetches every count it must compare with in that
+// group.  Lanes of a wave hold consecutive positions and mostly read the same rows.
+__global__ void __launch_bounds__(256) k_inst_unrank(Spec s, const long long *offsets, int *status,
                                                      unsigned short *x, long long capacity) {
     if (*status != OOB_OK) return;
-    const int len = s.N_hi - s.N_lo + 1;
+    const int len = s.N_hi - s.N_lo + 1, QQ = s.Q + 1;
     const long long total = offsets[len];
+    if (total > capacity) { // uniform: nothing is written
+        if (blockIdx.x == 0 && threadIdx.x == 0) *status = OOB_ECAPACITY;
+        return;
+    }
     const long long stride = (long long)gridDim.x * blockDim.x;
     for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
         int lo = 0, hi = len - 1; // last N' whose list starts at or before idx
@@ -108,18 +126,40 @@ __global__ void __launch_bounds__(256) k_inst_unrank(Spec s, const long long *of
         }
         int N = s.N_lo + lo, q = s.Q;
         long long rho = idx - offsets[lo];
-        for (int j = s.p; j >= 1; --j) {
-            const int n = size_of(s, j - 1);
-            int xj = 0;
-            while (N >= n) { // position inside the copy of X(j-1, N)?  else theta: one more pipeline
-                const long long c = s.cnt[cnt_index(s, j - 1, N, q)];
-                if (rho < c) break;
-                rho -= c;
-                ++xj;
-                N -= n;
+        int ilim = s.p - 1; // sizes 0..ilim may still get a pipeline
+        for (int g = (s.p - 1) / kGroup; g >= 0; --g) {
+            const int base = g * kGroup;
+            int nsz[kGroup];
+#pragma unroll
+            for (int k = 0; k < kGroup; ++k) nsz[k] = base + k < s.p ? size_of(s, base + k) : 0;
+            unsigned __int128 xs = 0; // kGroup 16-bit counts
+            while (true) {
+                const long long *row = s.cnt + ((long long)N * QQ + q) * s.R + base;
+                long long c[kGroup];
+#pragma unroll
+                for (int k = 0; k < kGroup; ++k) c[k] = row[k];
+                int ks = -1; // largest k with base + k <= ilim and C <= rho
+#pragma unroll
+                for (int k = 0; k < kGroup; ++k)
+                    if (base + k <= ilim && c[k] <= rho) ks = k;
+                if (ks < 0) break;
+                long long ck = 0;
+                int nk = 0;
+#pragma unroll
+                for (int k = 0; k < kGroup; ++k)
+                    if (k == ks) { ck = c[k]; nk = nsz[k]; }
+                if (nk > N) break; // cannot happen with a consistent table; keeps the loop finite
+                rho -= ck;
+                N -= nk;
                 q = q > 0 ? q - 1 : 0;
+                ilim = base + ks;
+                xs += (unsigned __int128)1 << (16 * ks);
             }
-            x[(long long)(j - 1) * capacity + idx] = (unsigned short)xj;
+#pragma unroll
+            for (int k = 0; k < kGroup; ++k)
+                if (base + k < s.p)
+                    x[(long long)(base + k) * capacity + idx] = (unsigned short)(xs >> (16 * k));
+            if (ilim > base - 1) ilim = base - 1;
         }
     }
 }
@@ -129,27 +169,21 @@ static bool args_ok(int p, int N_lo, int N_hi, int f) {
            f <= OOB_INST_MAX_F;
 }
 
-static int run(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, int f, void *ws, size_t ws_bytes,
-               uint16_t *x, int64_t capacity, int64_t *offsets, int32_t *status, void *stream, bool enumerate) {
+static size_t table_bytes(int p, int N_hi, int f) {
+    const size_t n = (size_t)(N_hi + 1) * (size_t)(f + 2) * (size_t)row_len(p) * sizeof(long long);
+    return (n + 255) & ~(size_t)255;
+}
+
+static int check_spec(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, int f, void *ws, size_t ws_bytes,
+                      int64_t *offsets, int32_t *status, Spec *s) {
     if (!args_ok(p, N_lo, N_hi, f) || !ws || !offsets || !status) return OOB_EINVAL;
     if (!sizes && n0 < 1) return OOB_EINVAL;
     if (((uintptr_t)ws & 255) != 0) return OOB_EINVAL;
-    if (enumerate && (capacity < 0 || (capacity > 0 && !x))) return OOB_EINVAL;
-    if (ws_bytes < oob_inst_workspace_size(p, N_hi, f)) return OOB_ECAPACITY;
-    Spec s;
-    s.sizes = sizes; s.p = p; s.n0 = n0; s.N_lo = N_lo; s.N_hi = N_hi; s.Q = f + 1;
-    s.cnt = (long long *)ws;
-    hipStream_t st = (hipStream_t)stream;
-    hipLaunchKernelGGL(k_inst_count, dim3(1), dim3(1024), 0, st, s, enumerate ? (long long)capacity : -1ll,
-                       (long long *)offsets, status);
-    if (enumerate && capacity > 0) {
-        // enough lanes to keep every CU busy; the kernel strides over the list
-        const long long want = (capacity + 255) / 256;
-        const int grid = (int)(want < 1 ? 1 : (want > 256 * 16 ? 256 * 16 : want));
-        hipLaunchKernelGGL(k_inst_unrank, dim3(grid), dim3(256), 0, st, s, (const long long *)offsets, status,
-                           (unsigned short *)x, (long long)capacity);
-    }
-    return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
+    if (ws_bytes < table_bytes(p, N_hi, f)) return OOB_ECAPACITY;
+    s->sizes = sizes; s->p = p; s->n0 = n0; s->N_lo = N_lo; s->N_hi = N_hi; s->Q = f + 1;
+    s->R = row_len(p);
+    s->cnt = (long long *)ws;
+    return OOB_OK;
 }
 
 } // namespace oob_inst
@@ -158,21 +192,47 @@ extern "C" {
 
 size_t oob_inst_workspace_size(int p, int N_hi, int f) {
     if (!oob_inst::args_ok(p, 0, N_hi, f)) return 0;
-    const size_t n = (size_t)(p + 1) * (size_t)(N_hi + 1) * (size_t)(f + 2) * sizeof(long long);
-    return (n + 255) & ~(size_t)255;
+    return oob_inst::table_bytes(p, N_hi, f);
 }
 
 int oob_inst_count(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, int f, void *dev_workspace,
                    size_t workspace_bytes, int64_t *offsets, int32_t *status, void *stream) {
-    return oob_inst::run(sizes, p, n0, N_lo, N_hi, f, dev_workspace, workspace_bytes, nullptr, 0, offsets, status,
-                         stream, false);
+    using namespace oob_inst;
+    Spec s;
+    const int rc = check_spec(sizes, p, n0, N_lo, N_hi, f, dev_workspace, workspace_bytes, offsets, status, &s);
+    if (rc != OOB_OK) return rc;
+    const size_t plane = (size_t)(N_hi + 1) * (f + 2) * sizeof(long long);
+    const size_t scan = (size_t)(N_hi - N_lo + 2) * sizeof(long long);
+    if (2 * plane <= 128 * 1024) {
+        const size_t lds = 2 * plane > scan ? 2 * plane : scan;
+        if (lds > 64 * 1024 &&
+            hipFuncSetAttribute((const void *)k_inst_count<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return OOB_EHIP;
+        hipLaunchKernelGGL(k_inst_count<true>, dim3(1), dim3(1024), lds, (hipStream_t)stream, s,
+                           (long long *)offsets, status);
+    } else {
+        hipLaunchKernelGGL(k_inst_count<false>, dim3(1), dim3(1024), scan, (hipStream_t)stream, s,
+                           (long long *)offsets, status);
+    }
+    return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
 }
 
 int oob_inst_enumerate(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, int f, void *dev_workspace,
-                       size_t workspace_bytes, uint16_t *x, int64_t capacity, int64_t *offsets, int32_t *status,
-                       void *stream) {
-    return oob_inst::run(sizes, p, n0, N_lo, N_hi, f, dev_workspace, workspace_bytes, x, capacity, offsets, status,
-                         stream, true);
+                       size_t workspace_bytes, uint16_t *x, int64_t capacity, const int64_t *offsets,
+                       int32_t *status, void *stream) {
+    using namespace oob_inst;
+    Spec s;
+    const int rc = check_spec(sizes, p, n0, N_lo, N_hi, f, dev_workspace, workspace_bytes, (int64_t *)offsets,
+                              status, &s);
+    if (rc != OOB_OK) return rc;
+    if (capacity < 0 || (capacity > 0 && !x)) return OOB_EINVAL;
+    // one lane per vector of the capacity; the kernel strides if the grid limit cuts that short
+    const long long want = (capacity + 255) / 256;
+    const int grid = (int)(want < 1 ? 1 : (want > (1 << 22) ? (1 << 22) : want));
+    hipLaunchKernelGGL(k_inst_unrank, dim3(grid), dim3(256), 0, (hipStream_t)stream, s, (const long long *)offsets,
+                       status, (unsigned short *)x, (long long)capacity);
+    return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
 }
 
 } // extern "C"

@@ -70,6 +70,15 @@ def test_node_specifications_of_the_planning_workloads(P, n0, n_hi, f):
         assert total == 1343380
 
 
+def test_large_cluster_sizes_take_the_table_from_global_memory(P):
+    """Two planes of the count table exceed the LDS here: the counting kernel's other path."""
+    print("sizes 500,700,900", flush=True)
+    assert compare(P, [500, 700, 900], 1900, 2000, 3) > 0
+    sizes = list(range(90, 130, 3))
+    print("sizes", sizes, flush=True)
+    assert compare(P, sizes, 1000, 1100, 2) > 1000
+
+
 def test_status_codes_and_capacity(P):
     import torch
 
@@ -96,6 +105,7 @@ def test_capacity_larger_than_total_leaves_the_tail_untouched(P):
     import torch
 
     inst = P.Instantiator([2, 3, 4], 13, 13, 0)
+    assert inst.count()[1] == P.OOB_OK
     x = torch.full((3, 64), 7777, dtype=torch.int16, device="cuda")
     inst.enqueue(x, 64)
     torch.cuda.synchronize()
