@@ -33,8 +33,8 @@ extern "C" {
 
 /* Bytes of device workspace (256-byte aligned) the two calls below need: the table of list
  * lengths |X(p', N')| restricted to "at least q more pipelines", q = 0..f+1
- * ((N_hi+1) (f+2) rows of p+1 64-bit counts, rows padded to a multiple of 8).  0 if an
- * argument is out of range. */
+ * ((N_hi+1) (f+2) rows of p+1 64-bit counts, rows padded to a multiple of 8, and a 32-bit
+ * copy used while every count is below 2^32).  0 if an argument is out of range. */
 size_t oob_inst_workspace_size(int p, int N_hi, int f);
 
 /* First call: list lengths (Eq. 5 with every list replaced by its length).

@@ -13,6 +13,9 @@
 // structure-of-arrays so that a wave writes 128 contiguous bytes per template.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
+
+#include <type_traits>
 
 #include "oob_inst.h"
 #include "oob_plan.h"
@@ -20,7 +23,8 @@
 namespace oob_inst {
 
 constexpr long long kSat = 1ll << 62; // counts saturate here; a saturated total is an error
-constexpr int kGroup = 8;             // counts a lane reads at once (64 bytes)
+constexpr int kGroup = 8;             // counts a lane reads at once
+constexpr int kWalks = 1;             // vectors a lane produces side by side (2 measured slower: the kernel is bound by instruction issue, not by read latency)
 
 // Count table: row (N', q) holds C(j, N', q) for j = 0..p, padded to whole groups, so that the
 // counts a position is compared with (same N', same q, descending j) are contiguous.
@@ -28,7 +32,10 @@ struct Spec {
     const int *sizes; // may be null: consecutive from n0
     int p, n0, N_lo, N_hi, Q, R; // Q = f + 1; R = row length
     long long *cnt;              // [(N_hi+1)][(Q+1)][R]
+    unsigned *cnt32;             // the same table in 32 bits, valid if *narrow
+    int *narrow;                 // [1] every count is below 2^32
 };
+constexpr size_t kHeaderBytes = 256; // the workspace starts with `narrow`, the two tables follow
 
 __host__ __device__ inline int row_len(int p) { return (p + 1 + kGroup - 1) / kGroup * kGroup; }
 __device__ __forceinline__ int size_of(const Spec &s, int j) { return s.sizes ? s.sizes[j] : s.n0 + j; }
@@ -44,11 +51,12 @@ __device__ __forceinline__ long long sat_add(long long a, long long b) {
 // previous and the current plane live in LDS (two planes of (N_hi+1)(Q+1) counts); otherwise
 // the previous plane is read back from the table.
 template <bool IN_LDS>
-__global__ void __launch_bounds__(1024) k_inst_count(Spec s, long long *offsets, int *status) {
+__global__ void __launch_bounds__(1024) k_inst_count(Spec s, long long *offsets, int *status, int keep_wide) {
     HIP_DYNAMIC_SHARED(long long, s_dyn) // IN_LDS: two planes; then reused for the prefix sum
     __shared__ int s_bad;
+    __shared__ unsigned long long s_max;
     const int QQ = s.Q + 1, plane = (s.N_hi + 1) * QQ, len = s.N_hi - s.N_lo + 1;
-    if (threadIdx.x == 0) s_bad = 0;
+    if (threadIdx.x == 0) { s_bad = 0; s_max = 0; }
     __syncthreads();
     for (int j = threadIdx.x; j < s.p; j += blockDim.x) {
         const int n = size_of(s, j);
@@ -58,13 +66,16 @@ __global__ void __launch_bounds__(1024) k_inst_count(Spec s, long long *offsets,
         const long long c = e == 0 ? 1 : 0;
         s.cnt[(long long)e * s.R] = c;
         if (IN_LDS) s_dyn[e] = c;
+        // the padding of a row compares greater than any list position
+        for (int j = s.p + 1; j < s.R; ++j) s.cnt[(long long)e * s.R + j] = 0x7FFFFFFFFFFFFFFFll;
     }
     __syncthreads();
     if (s_bad) { // uniform: every thread leaves here
         for (int i = threadIdx.x; i <= len; i += blockDim.x) offsets[i] = 0;
-        if (threadIdx.x == 0) *status = OOB_EINVAL;
+        if (threadIdx.x == 0) { *status = OOB_EINVAL; *s.narrow = 0; }
         return;
     }
+    long long mine = 1; // largest count this thread has written
     for (int j = 1; j <= s.p; ++j) {
         const int n = size_of(s, j - 1);
         const long long *prev = IN_LDS ? s_dyn + ((j - 1) & 1) * plane : s.cnt + (j - 1);
@@ -79,6 +90,7 @@ __global__ void __launch_bounds__(1024) k_inst_count(Spec s, long long *offsets,
             }
             s.cnt[(long long)e * s.R + j] = sum;
             if (IN_LDS) cur[e] = sum;
+            mine = sum > mine ? sum : mine;
         }
         __syncthreads(); // plane j complete (LDS, or global memory written by this workgroup)
     }
@@ -98,68 +110,123 @@ __global__ void __launch_bounds__(1024) k_inst_count(Spec s, long long *offsets,
     }
     __syncthreads();
     for (int i = threadIdx.x; i <= len; i += blockDim.x) offsets[i] = s_dyn[i];
+    // While every count is below 2^32 a second copy of the table in 32 bits halves what a lane
+    // reads per comparison step (the reads bound the enumeration kernel); padding stays maximal.
+    atomicMax(&s_max, (unsigned long long)mine);
+    __syncthreads();
+    const bool narrow = s_max < (1ull << 32) && !keep_wide;
+    if (narrow)
+        for (long long e = threadIdx.x; e < (long long)plane * s.R; e += blockDim.x) {
+            const long long v = s.cnt[e];
+            s.cnt32[e] = v == 0x7FFFFFFFFFFFFFFFll ? 0xFFFFFFFFu : (unsigned)v;
+        }
+    if (threadIdx.x == 0) *s.narrow = narrow;
 }
 
-// One lane per output vector (grid-stride).  A vector at position rho of the list of (N', q)
+// Every output vector is produced on its own (kWalks per lane).  A vector at position rho of the list of (N', q)
 // over the first j sizes has its highest non-zero count at the largest i < j with
 // C(i, N', q) <= rho (the lists over fewer sizes are prefixes of the list over more); it then
 // continues at position rho - C(i, N', q) of (N' - n_i, q - 1) over the first i+1 sizes.  The
 // sizes are visited in groups of kGroup from the top: all lanes take the same trip through
 // the groups, so the kGroup counts of a group are stored by whole waves (128 contiguous bytes
-// per template), and a lane's 64-byte read fetches every count it must compare with in that
-// group.  Lanes of a wave hold consecutive positions and mostly read the same rows.
+// per template), and one read of kGroup counts fetches every count a lane must compare with in
+// that group.  C is non-decreasing along a row, so the number of entries <= rho locates i without
+// a search.
+template <typename CT> // long long, or unsigned when the counting kernel could narrow the table
 __global__ void __launch_bounds__(256) k_inst_unrank(Spec s, const long long *offsets, int *status,
                                                      unsigned short *x, long long capacity) {
-    if (*status != OOB_OK) return;
+    if (*status != OOB_OK || (*s.narrow != 0) != (sizeof(CT) == 4)) return;
     const int len = s.N_hi - s.N_lo + 1, QQ = s.Q + 1;
     const long long total = offsets[len];
     if (total > capacity) { // uniform: nothing is written
         if (blockIdx.x == 0 && threadIdx.x == 0) *status = OOB_ECAPACITY;
         return;
     }
+    // A lane walks kWalks vectors at once (positions i, i + slab, ...): their reads are
+    // independent, so the latency of one dependent chain of reads hides behind the others.
+    const long long slab = (total + kWalks - 1) / kWalks;
     const long long stride = (long long)gridDim.x * blockDim.x;
-    for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
-        int lo = 0, hi = len - 1; // last N' whose list starts at or before idx
-        while (lo < hi) {
-            const int mid = (lo + hi + 1) >> 1;
-            if (offsets[mid] <= idx) lo = mid; else hi = mid - 1;
+    const CT *tab = sizeof(CT) == 4 ? (const CT *)s.cnt32 : (const CT *)s.cnt;
+    for (long long i0 = (long long)blockIdx.x * blockDim.x + threadIdx.x; i0 < slab; i0 += stride) {
+        long long idx[kWalks];
+        bool valid[kWalks];
+        int N[kWalks], q[kWalks];
+        CT rho[kWalks];
+#pragma unroll
+        for (int w = 0; w < kWalks; ++w) {
+            idx[w] = i0 + w * slab;
+            valid[w] = idx[w] < total;
+            int lo = 0, hi = valid[w] ? len - 1 : 0; // last N' whose list starts at or before idx
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (offsets[mid] <= idx[w]) lo = mid; else hi = mid - 1;
+            }
+            N[w] = s.N_lo + lo;
+            q[w] = s.Q;
+            rho[w] = valid[w] ? (CT)(idx[w] - offsets[lo]) : (CT)0;
         }
-        int N = s.N_lo + lo, q = s.Q;
-        long long rho = idx - offsets[lo];
-        int ilim = s.p - 1; // sizes 0..ilim may still get a pipeline
         for (int g = (s.p - 1) / kGroup; g >= 0; --g) {
             const int base = g * kGroup;
             int nsz[kGroup];
 #pragma unroll
             for (int k = 0; k < kGroup; ++k) nsz[k] = base + k < s.p ? size_of(s, base + k) : 0;
-            unsigned __int128 xs = 0; // kGroup 16-bit counts
+            int kcap[kWalks]; // sizes base..base+kcap may get a pipeline
+            unsigned long long xlo[kWalks], xhi[kWalks]; // kGroup 16-bit counts
+            bool act[kWalks];
+#pragma unroll
+            for (int w = 0; w < kWalks; ++w) {
+                kcap[w] = s.p - 1 - base < kGroup - 1 ? s.p - 1 - base : kGroup - 1;
+                xlo[w] = xhi[w] = 0;
+                act[w] = valid[w];
+            }
             while (true) {
-                const long long *row = s.cnt + ((long long)N * QQ + q) * s.R + base;
-                long long c[kGroup];
+                bool any = false;
 #pragma unroll
-                for (int k = 0; k < kGroup; ++k) c[k] = row[k];
-                int ks = -1; // largest k with base + k <= ilim and C <= rho
+                for (int w = 0; w < kWalks; ++w) any |= act[w];
+                if (!any) break;
+                CT c[kWalks][kGroup];
 #pragma unroll
-                for (int k = 0; k < kGroup; ++k)
-                    if (base + k <= ilim && c[k] <= rho) ks = k;
-                if (ks < 0) break;
-                long long ck = 0;
-                int nk = 0;
+                for (int w = 0; w < kWalks; ++w) { // a finished walk re-reads its last row (in bounds, unused)
+                    const CT *row = tab + ((long long)N[w] * QQ + q[w]) * s.R + base;
 #pragma unroll
-                for (int k = 0; k < kGroup; ++k)
-                    if (k == ks) { ck = c[k]; nk = nsz[k]; }
-                if (nk > N) break; // cannot happen with a consistent table; keeps the loop finite
-                rho -= ck;
-                N -= nk;
-                q = q > 0 ? q - 1 : 0;
-                ilim = base + ks;
-                xs += (unsigned __int128)1 << (16 * ks);
+                    for (int k = 0; k < kGroup; ++k) c[w][k] = row[k];
+                }
+#pragma unroll
+                for (int w = 0; w < kWalks; ++w) {
+                    int m = 0; // entries <= rho: a prefix of the row
+#pragma unroll
+                    for (int k = 0; k < kGroup; ++k) m += c[w][k] <= rho[w] ? 1 : 0;
+                    const int ks = m - 1 < kcap[w] ? m - 1 : kcap[w];
+                    // c[ks], nsz[ks] by halving (no indexed registers)
+                    const bool b0 = ks & 1, b1 = ks & 2, b2 = ks & 4;
+                    const CT c01 = b0 ? c[w][1] : c[w][0], c23 = b0 ? c[w][3] : c[w][2];
+                    const CT c45 = b0 ? c[w][5] : c[w][4], c67 = b0 ? c[w][7] : c[w][6];
+                    const CT c03 = b1 ? c23 : c01, c47 = b1 ? c67 : c45;
+                    const CT ck = b2 ? c47 : c03;
+                    const int n01 = b0 ? nsz[1] : nsz[0], n23 = b0 ? nsz[3] : nsz[2];
+                    const int n45 = b0 ? nsz[5] : nsz[4], n67 = b0 ? nsz[7] : nsz[6];
+                    const int n03 = b1 ? n23 : n01, n47 = b1 ? n67 : n45;
+                    const int nk = b2 ? n47 : n03;
+                    // m = 0: nothing (more) in this group; nk > N cannot happen with a consistent
+                    // table, the test keeps the loop finite and the next row inside the table
+                    act[w] = act[w] && m > 0 && nk <= N[w];
+                    if (act[w]) {
+                        rho[w] -= ck;
+                        N[w] -= nk;
+                        q[w] = q[w] > 0 ? q[w] - 1 : 0;
+                        kcap[w] = ks;
+                        const unsigned long long one = 1ull << (16 * (ks & 3));
+                        if (b2) xhi[w] += one; else xlo[w] += one;
+                    }
+                }
             }
 #pragma unroll
-            for (int k = 0; k < kGroup; ++k)
-                if (base + k < s.p)
-                    x[(long long)(base + k) * capacity + idx] = (unsigned short)(xs >> (16 * k));
-            if (ilim > base - 1) ilim = base - 1;
+            for (int w = 0; w < kWalks; ++w)
+#pragma unroll
+                for (int k = 0; k < kGroup; ++k)
+                    if (valid[w] && base + k < s.p)
+                        x[(long long)(base + k) * capacity + idx[w]] =
+                            (unsigned short)((k < 4 ? xlo[w] : xhi[w]) >> (16 * (k & 3)));
         }
     }
 }
@@ -169,9 +236,12 @@ static bool args_ok(int p, int N_lo, int N_hi, int f) {
            f <= OOB_INST_MAX_F;
 }
 
-static size_t table_bytes(int p, int N_hi, int f) {
+static size_t wide_bytes(int p, int N_hi, int f) {
     const size_t n = (size_t)(N_hi + 1) * (size_t)(f + 2) * (size_t)row_len(p) * sizeof(long long);
     return (n + 255) & ~(size_t)255;
+}
+static size_t table_bytes(int p, int N_hi, int f) { // header, 64-bit table, 32-bit table
+    return kHeaderBytes + wide_bytes(p, N_hi, f) + wide_bytes(p, N_hi, f) / 2 + 256;
 }
 
 static int check_spec(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, int f, void *ws, size_t ws_bytes,
@@ -182,7 +252,9 @@ static int check_spec(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, i
     if (ws_bytes < table_bytes(p, N_hi, f)) return OOB_ECAPACITY;
     s->sizes = sizes; s->p = p; s->n0 = n0; s->N_lo = N_lo; s->N_hi = N_hi; s->Q = f + 1;
     s->R = row_len(p);
-    s->cnt = (long long *)ws;
+    s->narrow = (int *)ws;
+    s->cnt = (long long *)((char *)ws + kHeaderBytes);
+    s->cnt32 = (unsigned *)((char *)ws + kHeaderBytes + wide_bytes(p, N_hi, f));
     return OOB_OK;
 }
 
@@ -201,6 +273,9 @@ int oob_inst_count(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, int 
     Spec s;
     const int rc = check_spec(sizes, p, n0, N_lo, N_hi, f, dev_workspace, workspace_bytes, offsets, status, &s);
     if (rc != OOB_OK) return rc;
+    // debug knob: never use the 32-bit copy of the table (tests of the 64-bit path)
+    const char *ev = getenv("OOB_TUNE_INST_INT64");
+    const int keep_wide = ev && atoi(ev) != 0;
     const size_t plane = (size_t)(N_hi + 1) * (f + 2) * sizeof(long long);
     const size_t scan = (size_t)(N_hi - N_lo + 2) * sizeof(long long);
     if (2 * plane <= 128 * 1024) {
@@ -210,10 +285,10 @@ int oob_inst_count(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, int 
                                 (int)lds) != hipSuccess)
             return OOB_EHIP;
         hipLaunchKernelGGL(k_inst_count<true>, dim3(1), dim3(1024), lds, (hipStream_t)stream, s,
-                           (long long *)offsets, status);
+                           (long long *)offsets, status, keep_wide);
     } else {
         hipLaunchKernelGGL(k_inst_count<false>, dim3(1), dim3(1024), scan, (hipStream_t)stream, s,
-                           (long long *)offsets, status);
+                           (long long *)offsets, status, keep_wide);
     }
     return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
 }
@@ -227,11 +302,14 @@ int oob_inst_enumerate(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, 
                               status, &s);
     if (rc != OOB_OK) return rc;
     if (capacity < 0 || (capacity > 0 && !x)) return OOB_EINVAL;
-    // one lane per vector of the capacity; the kernel strides if the grid limit cuts that short
-    const long long want = (capacity + 255) / 256;
+    // one lane per kWalks vectors of the capacity; the kernel strides if the grid limit cuts that short
+    const long long want = ((capacity + kWalks - 1) / kWalks + 255) / 256;
     const int grid = (int)(want < 1 ? 1 : (want > (1 << 22) ? (1 << 22) : want));
-    hipLaunchKernelGGL(k_inst_unrank, dim3(grid), dim3(256), 0, (hipStream_t)stream, s, (const long long *)offsets,
-                       status, (unsigned short *)x, (long long)capacity);
+    // the table's number type is known on the device only: the launch of the other type returns at once
+    hipLaunchKernelGGL(k_inst_unrank<unsigned>, dim3(grid), dim3(256), 0, (hipStream_t)stream, s,
+                       (const long long *)offsets, status, (unsigned short *)x, (long long)capacity);
+    hipLaunchKernelGGL(k_inst_unrank<long long>, dim3(grid), dim3(256), 0, (hipStream_t)stream, s,
+                       (const long long *)offsets, status, (unsigned short *)x, (long long)capacity);
     return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
 }
 

@@ -79,6 +79,15 @@ def test_large_cluster_sizes_take_the_table_from_global_memory(P):
     assert compare(P, sizes, 1000, 1100, 2) > 1000
 
 
+def test_integer_table_path(P, monkeypatch):
+    """Counts of 2^53 and more keep the table in int64 (no case the oracle could enumerate gets
+    there): the knob forces that path on ordinary cases."""
+    monkeypatch.setenv("OOB_TUNE_INST_INT64", "1")
+    assert compare(P, [2, 3, 4], 0, 13, 0) > 0
+    assert compare(P, None, 20, 48, 4, consecutive=(4, 29)) == 10251
+    assert compare(P, list(range(90, 130, 3)), 1000, 1100, 2) > 1000
+
+
 def test_status_codes_and_capacity(P):
     import torch
 
