@@ -49,6 +49,43 @@ def cpu_baseline(inp):
     return res
 
 
+def bench_instantiation(P, inp, res, reps=20):
+    """Section 4.2.1 on the node specification the planner just produced: every count vector for
+    every N' from (f+1) n0 to N.  Timed with events on the stream the kernels are launched on."""
+    import torch
+
+    n0, n_hi, p, N = (int(v) for v in res["cover_hdr"][:4])
+    if p < 1:
+        return None
+    inst = P.Instantiator(None, (inp.f + 1) * n0, N, inp.f, n0=n0, p=p)
+    off, st = inst.count()
+    total = int(off[-1])
+    if st != P.OOB_OK or total == 0:
+        return {"status": st, "vectors": total}
+    cap = (total + 63) // 64 * 64  # rows of x start on 128-byte lines
+    x = torch.empty((p, cap), dtype=torch.int16, device="cuda")
+    stream = torch.cuda.current_stream()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    inst.enqueue(x, cap)
+    torch.cuda.synchronize()
+    ev[0].record(stream)
+    for _ in range(reps):
+        P.oob_inst_count(*inst._spec(), inst.offsets.data_ptr(), inst.status.data_ptr(), stream.cuda_stream)
+    ev[1].record(stream)
+    for _ in range(reps):
+        inst.enqueue(x, cap)
+    ev[2].record(stream)
+    torch.cuda.synchronize()
+    t_count, t_enum = ev[0].elapsed_time(ev[1]) / reps * 1e-3, ev[1].elapsed_time(ev[2]) / reps * 1e-3
+    nbytes = 2.0 * p * total  # algorithmic: every count of every vector written once (uint16)
+    return {"workload": f"template sizes {n0}..{n_hi}, f={inp.f}, N'={(inp.f + 1) * n0}..{N}",
+            "vectors": total, "templates": p, "count_us": t_count * 1e6, "enumerate_us": t_enum * 1e6,
+            "value": total / t_enum, "unit": "count vectors/s",
+            "roofline": {"bound": "hbm", "achieved": nbytes / t_enum / 1e9, "peak": 8000.0, "unit": "GB/s",
+                         "frac": nbytes / t_enum / 8e12, "traffic": None,
+                         "kernel": "k_inst_unrank", "bytes_per_vector": 2 * p}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -123,6 +160,7 @@ def main():
                      "avg_launch_ms": lvl_ms / launches, "levels_ms_per_step": lvl_ms,
                      "candidates_per_s": cands / (lvl_ms * 1e-3)},
     }
+    line["instantiation"] = bench_instantiation(P, inp, res)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(inp)
     print(json.dumps(line))
