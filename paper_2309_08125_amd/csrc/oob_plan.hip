@@ -29,6 +29,8 @@
 //   k_select per state: first s with the smallest partial minimum, then the first m at that
 //            (s, k) whose candidate equals it -- the smallest (T, s, k, m) -- and the record.
 #include <hip/hip_runtime.h>
+
+#include <vector>
 #include <math.h>
 #include <new>
 #include <stdint.h>
@@ -64,7 +66,9 @@ struct Tables {
     int *stack;           // backtracking stacks / coverage ring
     int2 *seg_tab;        // per level: (tile index, ub | vb << 8 | segment << 16) of every split task
     int seg_stride;       // entries reserved per level in seg_tab (level S' starts at (S'-2) * seg_stride)
-    int *flags;           // [0] 1: (total, k) keys fit a double (k_split_key runs), 0: k_split runs
+    int *flags;           // [0] 1: (total, k) keys fit a double and k_split_key runs
+                          // [1] 1: the host chose the plain split kernel k_split for this job (then [0] = 0)
+                          // [0] = [1] = 0: k_select evaluates every candidate itself
     int *status;
 };
 
@@ -146,6 +150,7 @@ __global__ void k_setup(Tables t, oob_profile prof, int force_plain) {
             t.flags[0] = !force_plain && worst < (kExactBound >> key_bits(L)) / mult;
         }
         if (st != OOB_OK) t.flags[0] = 0;
+        t.flags[1] = force_plain;
         *t.status = st;
     }
 }
@@ -195,7 +200,7 @@ __global__ void __launch_bounds__(64) k_level1(Tables t, const long long *X) {
 template <int PC>
 __global__ void __launch_bounds__(512) k_split(Tables t, int Sp, int fam, int NT, int NAall) {
     HIP_DYNAMIC_SHARED(double2, s_pair) // [ntab][PC][8] (x, y) pairs, then double tmax[ntab][PC][8]
-    if (t.flags[0] != 0) return;        // the keyed kernel handles this job
+    if (t.flags[1] == 0) return;        // only when the host chose this kernel (it then launches no other)
     const int L = t.sh.L, M = t.sh.M, n_max = t.sh.n_max;
     const int s = blockIdx.y + 1, r = Sp - s;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
@@ -372,15 +377,16 @@ __device__ __forceinline__ void stage_store(const Stage &g, double2 *pair, doubl
 // thread has the records of k+1 in flight from HBM/L2 and drops them into the other buffer
 // before the single barrier of the pass.
 template <int NTAB, int NA, int NBUF>
-__global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, int NT, int NAall, int halves) {
+__global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, int NT, int NAall, int halves,
+                                                   int s0, int sstep) {
     // Static, separate arrays: the compiler then knows that the key merges (atomics on s_acc) never
     // touch the staged records, and keeps the reads of the next step ahead of them.
     __shared__ double2 s_pair[NBUF][NTAB * 8]; // [buffer][table][u or v]: (T + cl tmax, T1) / (2 T1, T + cr tmax)
     __shared__ double s_tm[NBUF][NTAB * 8];    // tmax
     __shared__ unsigned long long s_acc[(NA + 2) * 64]; // keys, rows 1..na
-    if (t.flags[0] == 0) return;        // keys do not fit: k_split handles this job
+    if (t.flags[0] == 0) return;        // keys do not fit: k_select evaluates the candidates itself
     const int L = t.sh.L, M = t.sh.M, n_max = t.sh.n_max;
-    const int s = blockIdx.y + 1, r = Sp - s;
+    const int s = s0 + blockIdx.y * sstep, r = Sp - s; // a launch covers the splits s0, s0 + sstep, ...
     // the wave index is the same in all lanes: say so, and everything derived from it (work item,
     // m range, key row) is scalar arithmetic and scalar branches
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
@@ -570,7 +576,7 @@ __global__ void __launch_bounds__(64) k_select(Tables t, int Sp, int NT, int NAa
         }
         if (best < kNone) bk = (int)(bkey - best * KS);
         for (int s = 1; s < Sp; ++s) t.partT[o0 + (s - 1) * os] = kNone;
-    } else {
+    } else if (t.flags[1]) {
         for (int s = 1; s < Sp; ++s) { // first s with the smallest minimum
             const long long o = (((long long)(s - 1) * NAall + aidx) * NT + blockIdx.x) * 64 + lane;
             const double T = t.partT[o];
@@ -579,14 +585,32 @@ __global__ void __launch_bounds__(64) k_select(Tables t, int Sp, int NT, int NAa
     }
     Rec out = {kNone, kNone, 0.0, 0.0};
     int ks = 0, ch = 0;
-    if (best < kNone) {
-        const Family fam = family_of(delta, M);
+    const Family fam = family_of(delta, M);
+    int bm = 0;
+    Rec a = out, b = out;
+    if (!t.flags[0] && !t.flags[1]) {
+        // Totals too large for keys (decided by the set-up kernel from the profile): every candidate
+        // (s, k, m) of this state in that order with a strict-minimum update.  Slow, exact, rare.
+        if (v <= L && v - u >= Sp)
+            for (int s = 1; s < Sp; ++s) {
+                const int r = Sp - s;
+                int mlo, mhi;
+                m_range(fam.fam, fam.units, s, r, M, t.sh.n_max, &mlo, &mhi);
+                const double cl = t.sh.Nb > 0 ? -(double)r : 3.0 * r, cr = t.sh.Nb > 0 ? 0.0 : 4.0 * s;
+                for (int k = u + s; k <= v - r; ++k)
+                    for (int m = mlo; m <= mhi; ++m) {
+                        const Rec ra = t.rec[rec_index(t, s, fam.fam_base + m, u, k)];
+                        const Rec rb = t.rec[rec_index(t, r, fam.fam_base + fam.units - m, k, v)];
+                        const double T = ra.tmax >= rb.tmax ? (ra.T + cl * ra.tmax) + 2.0 * rb.T1
+                                                            : ra.T1 + (rb.T + cr * rb.tmax);
+                        if (T < best) { best = T; bs = s; bk = k; bm = m; a = ra; b = rb; }
+                    }
+            }
+    } else if (best < kNone) {
         const int r = Sp - bs;
         int mlo, mhi;
         m_range(fam.fam, fam.units, bs, r, M, t.sh.n_max, &mlo, &mhi);
         const double cl = t.sh.Nb > 0 ? -(double)r : 3.0 * r, cr = t.sh.Nb > 0 ? 0.0 : 4.0 * bs;
-        int bm = 0;
-        Rec a = out, b = out;
         // first m whose candidate equals the minimum; four candidates' records in flight at a time
         const long long tabA = (t.lvl_tab[bs] - dlo_of(bs, M) + fam.fam_base) * (long long)t.tab_recs +
                                (long long)tri_index(u >> 3, bk >> 3, t.NB) * 64 + ((u & 7) << 3) + (bk & 7);
@@ -607,12 +631,15 @@ __global__ void __launch_bounds__(64) k_select(Tables t, int Sp, int NT, int NAa
                 if (bm == 0 && m0 + q <= mhi && T == best) { bm = m0 + q; a = ra[q]; b = rb[q]; }
             }
         }
+    }
+    if (best < kNone) {
         if (bm == 0) {
 #ifdef OOB_EMU_DEBUG
-            fprintf(stderr, "select fail Sp=%d delta=%d u=%d v=%d best=%g bs=%d bk=%d mlo=%d mhi=%d\n", Sp, delta, u, v, best, bs, bk, mlo, mhi);
+            fprintf(stderr, "select fail Sp=%d delta=%d u=%d v=%d best=%g bs=%d bk=%d\n", Sp, delta, u, v, best, bs, bk);
 #endif
             *t.status = kInternalError;
         } else {
+            const int r = Sp - bs;
             const long long oa = rec_index(t, bs, fam.fam_base + bm, u, bk);
             const long long ob = rec_index(t, r, fam.fam_base + fam.units - bm, bk, v);
             out.T = best;
@@ -798,8 +825,9 @@ Carve carve(int L, int nodes, int M) {
     c.rec = o;     o = align_up(o + sizeof(Rec) * E);
     c.kstar = o;   o = align_up(o + sizeof(int) * E);
     c.choice = o;  o = align_up(o + sizeof(int) * E);
-    c.partT = o;   o = align_up(o + sizeof(double) * (size_t)c.slots * 64);
-    c.partK = o;   o = align_up(o + sizeof(int) * (size_t)c.slots * 64);
+    // two of each: consecutive levels are evaluated side by side (see oob_plan_templates)
+    c.partT = o;   o = align_up(o + 2 * sizeof(double) * (size_t)c.slots * 64);
+    c.partK = o;   o = align_up(o + 2 * sizeof(int) * (size_t)c.slots * 64);
     c.stack = o;   o = align_up(o + sizeof(int) * ((size_t)nodes * (Smax + 1) * 4 + nodes + 2));
     c.flags = o;   o = align_up(o + sizeof(int) * 64);
     // the task list of a level is longest at S' = 2; every level gets that many entries
@@ -909,6 +937,8 @@ struct oob_plan {
     bool have_last;
     hipEvent_t ev_begin, ev_end; // optional: recorded around the level launches
     bool timed;
+    hipStream_t aux;             // second stream for the odd levels (null: everything on the caller's stream)
+    std::vector<hipEvent_t> ev_level; // [S'] "level S' selected"; ev_level[0], [1]: fork and join
 };
 
 #define OOB_HIP_CHECK(expr)                                                                   \
@@ -947,6 +977,7 @@ extern "C" int oob_plan_create(oob_plan **h, int max_L, int max_nodes, int max_g
     p->max_L = max_L; p->max_nodes = max_nodes; p->max_M = max_gpus_per_node;
     p->ws = (char *)dev_workspace; p->ws_bytes = workspace_bytes; p->cv = cv; p->have_last = false;
     p->ev_begin = nullptr; p->ev_end = nullptr; p->timed = false;
+    p->aux = nullptr;
     *h = p;
     return OOB_OK;
 }
@@ -954,6 +985,8 @@ extern "C" int oob_plan_create(oob_plan **h, int max_L, int max_nodes, int max_g
 extern "C" int oob_plan_destroy(oob_plan *h) {
     if (!h) return OOB_EINVAL;
     if (h->ev_begin) { (void)hipEventDestroy(h->ev_begin); (void)hipEventDestroy(h->ev_end); }
+    for (hipEvent_t e : h->ev_level) (void)hipEventDestroy(e);
+    if (h->aux) (void)hipStreamDestroy(h->aux);
     delete h;
     return OOB_OK;
 }
@@ -987,16 +1020,18 @@ static bool out_ok(const oob_templates *o) {
            o->status;
 }
 
+// The splits s0, s0 + sstep, ... (scount of them) of level S.
+struct SplitRange { int s0, sstep, scount; };
 template <int NTAB, int NA>
 static void launch_split_key_c(const Tables &t, int S, int fam, const SplitPlan &sp, int NT, int NAall,
-                               hipStream_t st) {
+                               SplitRange sr, hipStream_t st) {
     static const int nbuf = env_or("OOB_TUNE_KEY_NBUF", 1);
     if (nbuf == 2)
-        hipLaunchKernelGGL((k_split_key<NTAB, NA, 2>), dim3(seg_count(t.sh.L, S), S - 1, sp.groups),
-                           dim3(sp.waves * 64), 0, st, t, S, fam, NT, NAall, sp.pc);
+        hipLaunchKernelGGL((k_split_key<NTAB, NA, 2>), dim3(seg_count(t.sh.L, S), sr.scount, sp.groups),
+                           dim3(sp.waves * 64), 0, st, t, S, fam, NT, NAall, sp.pc, sr.s0, sr.sstep);
     else
-        hipLaunchKernelGGL((k_split_key<NTAB, NA, 1>), dim3(seg_count(t.sh.L, S), S - 1, sp.groups),
-                           dim3(sp.waves * 64), 0, st, t, S, fam, NT, NAall, sp.pc);
+        hipLaunchKernelGGL((k_split_key<NTAB, NA, 1>), dim3(seg_count(t.sh.L, S), sr.scount, sp.groups),
+                           dim3(sp.waves * 64), 0, st, t, S, fam, NT, NAall, sp.pc, sr.s0, sr.sstep);
 }
 // LDS capacity classes of k_split_key: (tables staged, targets); the smallest that fits is used.
 static const int kKeyClasses[][2] = {{24, 16}, {48, 40}, {64, 48}, {96, 48}, {96, 64}, {136, 64}};
@@ -1006,14 +1041,15 @@ static int key_class(int ntab, int na) {
     return -1;
 }
 static void launch_split_key(const Tables &t, int S, int fam, const SplitPlan &sp, int NT, int NAall,
-                             hipStream_t st) {
+                             SplitRange sr, hipStream_t st) {
+    if (sr.scount < 1) return;
     switch (sp.cls) {
-    case 0: launch_split_key_c<24, 16>(t, S, fam, sp, NT, NAall, st); break;
-    case 1: launch_split_key_c<48, 40>(t, S, fam, sp, NT, NAall, st); break;
-    case 2: launch_split_key_c<64, 48>(t, S, fam, sp, NT, NAall, st); break;
-    case 3: launch_split_key_c<96, 48>(t, S, fam, sp, NT, NAall, st); break;
-    case 4: launch_split_key_c<96, 64>(t, S, fam, sp, NT, NAall, st); break;
-    default: launch_split_key_c<136, 64>(t, S, fam, sp, NT, NAall, st); break;
+    case 0: launch_split_key_c<24, 16>(t, S, fam, sp, NT, NAall, sr, st); break;
+    case 1: launch_split_key_c<48, 40>(t, S, fam, sp, NT, NAall, sr, st); break;
+    case 2: launch_split_key_c<64, 48>(t, S, fam, sp, NT, NAall, sr, st); break;
+    case 3: launch_split_key_c<96, 48>(t, S, fam, sp, NT, NAall, sr, st); break;
+    case 4: launch_split_key_c<96, 64>(t, S, fam, sp, NT, NAall, sr, st); break;
+    default: launch_split_key_c<136, 64>(t, S, fam, sp, NT, NAall, sr, st); break;
     }
 }
 
@@ -1045,13 +1081,20 @@ extern "C" int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L
     sh.cap = mem_cap; sh.count = n_max - n_min + 1;
     sh.Smax = smax_of(L, n_max, M, microbatches);
     // launch shapes first, so that nothing is enqueued when a level cannot be staged in LDS
-    int force_plain = 0; // a level's tables exceed the keyed kernel's LDS classes: plain kernel everywhere
+    // a level's tables exceed the keyed kernel's LDS classes (or the debug knob says so): plain kernel everywhere
+    const char *fp_env = getenv("OOB_TUNE_FORCE_PLAIN");
+    int force_plain = fp_env && atoi(fp_env) != 0;
     for (int S = 2; S <= sh.Smax; ++S)
         for (int fam = 0; fam < 2; ++fam) {
             SplitPlan sp;
-            if (plan_split(sh, S, fam, &sp) && sp.lds > kLdsLimit) return OOB_ECAPACITY;
             if (plan_split_key(sh, S, fam, &sp) && key_class(sp.ntab, sp.na) < 0) force_plain = 1;
         }
+    if (force_plain)
+        for (int S = 2; S <= sh.Smax; ++S)
+            for (int fam = 0; fam < 2; ++fam) {
+                SplitPlan sp;
+                if (plan_split(sh, S, fam, &sp) && sp.lds > kLdsLimit) return OOB_ECAPACITY;
+            }
     const Tables t = make_tables(h, sh, (int *)out->status);
     hipStream_t st = (hipStream_t)stream;
     work_counts(sh, (long long *)&out->states, (long long *)&out->candidates);
@@ -1060,27 +1103,66 @@ extern "C" int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L
     hipLaunchKernelGGL(k_level1, dim3(tile_count(L, 1), M), dim3(64), 0, st, t,
                        (const long long *)profile->boundary_ns);
     if (sh.Smax >= 2) hipLaunchKernelGGL(k_seg_tab, dim3(sh.Smax - 1), dim3(64), 0, st, t);
-    {
-        const long long nkeys = part_slots(L, M, n_max, microbatches) * 64;
-        hipLaunchKernelGGL(k_fill_keys, dim3((unsigned)((nkeys + 255) / 256)), dim3(256), 0, st, t.partKey, nkeys);
+    const long long slot_stride = h->cv.slots * 64; // distance between the two buffers of per-split minima
+    hipLaunchKernelGGL(k_fill_keys, dim3((unsigned)((2 * slot_stride + 255) / 256)), dim3(256), 0, st, t.partKey,
+                       2 * slot_stride);
+    // Levels.  The splits 2 <= s <= S'-2 of level S' need the levels up to S'-2 only, so they may
+    // start while level S'-1 is still being finished: even levels run on the caller's stream, odd
+    // ones on the handle's second stream, each level waiting for the other stream's last select
+    // only before its two outer splits (s = 1 and S'-1).  Two levels side by side fill the idle
+    // tails of each other's launches.  Each stream has its own buffer of per-split minima.
+    static const int want_overlap = env_or("OOB_TUNE_OVERLAP", 1);
+    bool overlap = want_overlap && !force_plain && sh.Smax >= 4;
+    if (overlap && !h->aux && hipStreamCreateWithFlags(&h->aux, hipStreamNonBlocking) != hipSuccess) {
+        h->aux = nullptr;
+        (void)hipGetLastError();
     }
+    if (overlap && h->aux) {
+        while ((int)h->ev_level.size() < sh.Smax + 1) {
+            hipEvent_t e;
+            if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); break; }
+            h->ev_level.push_back(e);
+        }
+    }
+    overlap = overlap && h->aux && (int)h->ev_level.size() >= sh.Smax + 1;
     if (h->ev_begin) OOB_HIP_CHECK(hipEventRecord(h->ev_begin, st));
+    if (overlap) { // the second stream starts after everything enqueued so far
+        OOB_HIP_CHECK(hipEventRecord(h->ev_level[0], st));
+        OOB_HIP_CHECK(hipStreamWaitEvent(h->aux, h->ev_level[0], 0));
+    }
     for (int S = 2; S <= sh.Smax; ++S) {
         const int NAall = dhi_of(S, M, n_max) - dlo_of(S, M) + 1;
         if (NAall <= 0) continue;
         const int NT = tile_count(L, S);
+        hipStream_t sx = overlap && (S & 1) ? h->aux : st;
+        Tables tl = t; // this level's buffer of per-split minima
+        tl.partT = t.partT + (S & 1) * slot_stride;
+        tl.partKey = t.partKey + (S & 1) * slot_stride;
+        tl.partK = t.partK + (S & 1) * slot_stride;
+        SplitPlan sp[2], kp[2];
+        bool have[2];
         for (int fam = 0; fam < 2; ++fam) {
-            SplitPlan sp, kp;
-            if (!plan_split(sh, S, fam, &sp) || !plan_split_key(sh, S, fam, &kp)) continue;
-            // exactly one of the two does the work: the set-up kernel decides (flags[0])
-            kp.cls = key_class(kp.ntab, kp.na);
-            if (!force_plain) launch_split_key(t, S, fam, kp, NT, NAall, st);
-            if (sp.pc == 4) launch_split<4>(t, S, fam, sp, NT, NAall, st);
-            else if (sp.pc == 2) launch_split<2>(t, S, fam, sp, NT, NAall, st);
-            else launch_split<1>(t, S, fam, sp, NT, NAall, st);
+            have[fam] = plan_split(sh, S, fam, &sp[fam]) && plan_split_key(sh, S, fam, &kp[fam]);
+            if (have[fam]) kp[fam].cls = key_class(kp[fam].ntab, kp[fam].na);
         }
-        hipLaunchKernelGGL(k_select, dim3(NT, NAall), dim3(64), 0, st, t, S, NT, NAall);
+        if (overlap) {
+            for (int fam = 0; fam < 2; ++fam) // inner splits: in order behind this stream's level S'-2
+                if (have[fam]) launch_split_key(tl, S, fam, kp[fam], NT, NAall, SplitRange{2, 1, S - 3}, sx);
+            if (S >= 3) OOB_HIP_CHECK(hipStreamWaitEvent(sx, h->ev_level[S - 1], 0));
+        }
+        for (int fam = 0; fam < 2; ++fam) {
+            if (!have[fam]) continue;
+            const SplitRange sr = overlap ? SplitRange{1, imax(S - 2, 1), S == 2 ? 1 : 2} : SplitRange{1, 1, S - 1};
+            if (!force_plain) launch_split_key(tl, S, fam, kp[fam], NT, NAall, sr, sx);
+            else if (sp[fam].pc == 4) launch_split<4>(tl, S, fam, sp[fam], NT, NAall, sx);
+            else if (sp[fam].pc == 2) launch_split<2>(tl, S, fam, sp[fam], NT, NAall, sx);
+            else launch_split<1>(tl, S, fam, sp[fam], NT, NAall, sx);
+        }
+        hipLaunchKernelGGL(k_select, dim3(NT, NAall), dim3(64), 0, sx, tl, S, NT, NAall);
+        if (overlap) OOB_HIP_CHECK(hipEventRecord(h->ev_level[S], sx));
     }
+    if (overlap) // whatever the second stream did last is awaited on the caller's stream
+        OOB_HIP_CHECK(hipStreamWaitEvent(st, h->ev_level[sh.Smax & 1 ? sh.Smax : sh.Smax - 1], 0));
     if (h->ev_end) { OOB_HIP_CHECK(hipEventRecord(h->ev_end, st)); h->timed = true; }
     hipLaunchKernelGGL(k_pick, dim3((sh.count + 63) / 64), dim3(64), 0, st, t, *out);
     hipLaunchKernelGGL(k_backtrack, dim3((sh.count + 1 + 63) / 64), dim3(64), 0, st, t, *out);

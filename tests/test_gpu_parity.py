@@ -153,10 +153,11 @@ def test_device_status_reports_bad_profile_values(P):
     planner.close()
 
 
-def test_large_times_stay_exact_both_split_kernels(P):
+def test_large_times_stay_exact_on_both_paths(P):
     """Times near the top of the exactly representable range.  Up to a bound the set-up
     kernel checks, (total, split point) pairs fit one double and the keyed split kernel runs;
-    above it the plain split kernel runs.  Both must match the oracle bit for bit."""
+    above it the select kernel evaluates every candidate itself.  Both must match the oracle
+    bit for bit."""
     planner = P.Planner(12, 4, 3)
     seen = set()
     for seed in range(4):
@@ -166,9 +167,24 @@ def test_large_times_stay_exact_both_split_kernels(P):
                     inputs.random_small(40 + seed, 9, 2, 1, 3, 7, t_lo=(1 << 30), t_hi=(1 << 31)),
                     inputs.random_small(50 + seed, 12, 3, 1, 4, 9)):
             full_check(P, planner, inp)
-            seen.add(planner.flags()[0])
-    assert seen == {0, 1}, "both split kernels must have been exercised"
+            seen.add(tuple(planner.flags()[:2]))
+    assert seen == {(0, 0), (1, 0)}, "keyed kernel and in-select evaluation must both have run"
     planner.close()
+
+
+def test_plain_split_kernel(P, monkeypatch):
+    """The tiled split kernel without keys serves shapes whose tables exceed the keyed kernel's
+    LDS classes (hundreds of nodes); the knob routes ordinary shapes through it."""
+    monkeypatch.setenv("OOB_TUNE_FORCE_PLAIN", "1")
+    for inp in (inputs.config(1), inputs.config(2),
+                inputs.random_small(3, 37, 3, 1, 5, 9, f=1, tight_mem=True),
+                inputs.random_small(4, 30, 3, 2, 30, 0, f=2),
+                inputs.random_small(21, 9, 2, 1, 3, 7, t_lo=(1 << 38), t_hi=(1 << 39))):
+        print("plain", inp.name, inp.L, flush=True)
+        planner = P.Planner(inp.L, inp.n_max, inp.gpus_per_node)
+        full_check(P, planner, inp)
+        assert planner.flags()[:2] == [0, 1]
+        planner.close()
 
 
 def test_two_calls_same_answer(P):
