@@ -26,8 +26,8 @@ OPS_PER_CANDIDATE = 30
 PEAK_LANE_OPS = 256 * 64 * 2.4e9  # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T 32-bit lane-ops/s
 # HBM bytes of the level kernels of one call on configuration 4, from the two rocprofv3 --pmc
 # runs (FETCH_SIZE, WRITE_SIZE) summarised in profiles/k_split_key_config4.md, scaled by what
-# the same counters read for a 256 MiB copy: 21.34 GB read + 5.68 GB written.
-HBM_BYTES_PER_CALL_CONFIG4 = 21.34e9 + 5.68e9
+# the same counters read for a 256 MiB copy: 21.18 GB read + 5.72 GB written.
+HBM_BYTES_PER_CALL_CONFIG4 = 21.18e9 + 5.72e9
 
 
 def cpu_baseline(inp):

@@ -825,9 +825,9 @@ Carve carve(int L, int nodes, int M) {
     c.rec = o;     o = align_up(o + sizeof(Rec) * E);
     c.kstar = o;   o = align_up(o + sizeof(int) * E);
     c.choice = o;  o = align_up(o + sizeof(int) * E);
-    // two of each: consecutive levels are evaluated side by side (see oob_plan_templates)
+    // two buffers of minima: consecutive levels are evaluated side by side (see oob_plan_templates)
     c.partT = o;   o = align_up(o + 2 * sizeof(double) * (size_t)c.slots * 64);
-    c.partK = o;   o = align_up(o + 2 * sizeof(int) * (size_t)c.slots * 64);
+    c.partK = o;   o = align_up(o + sizeof(int) * (size_t)c.slots * 64); // plain kernel only: one stream
     c.stack = o;   o = align_up(o + sizeof(int) * ((size_t)nodes * (Smax + 1) * 4 + nodes + 2));
     c.flags = o;   o = align_up(o + sizeof(int) * 64);
     // the task list of a level is longest at S' = 2; every level gets that many entries
@@ -1138,7 +1138,6 @@ extern "C" int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L
         Tables tl = t; // this level's buffer of per-split minima
         tl.partT = t.partT + (S & 1) * slot_stride;
         tl.partKey = t.partKey + (S & 1) * slot_stride;
-        tl.partK = t.partK + (S & 1) * slot_stride;
         SplitPlan sp[2], kp[2];
         bool have[2];
         for (int fam = 0; fam < 2; ++fam) {
