@@ -138,6 +138,7 @@ def main():
     launches = max(1, Smax - 1)
     lvl_ms = sum(level_ms) / len(level_ms)
     achieved = cands * OPS_PER_CANDIDATE / (lvl_ms * 1e-3)
+    measured_peak = planner.valu_peak()  # add / compare / select microbenchmark on this GPU
     traffic = HBM_BYTES_PER_CALL_CONFIG4 / launches if args.config == 4 else None
     line = {
         "metric": "DP states/sec (wall-ms per full template set in ms_per_step)",
@@ -154,6 +155,7 @@ def main():
                    "states": states, "candidates": cands, "levels": Smax},
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12,
                      "unit": "T lane-op/s", "frac": achieved / PEAK_LANE_OPS, "traffic": traffic,
+                     "measured_peak": measured_peak / 1e12, "frac_of_measured_peak": achieved / measured_peak,
                      "traffic_unit": "HBM bytes per level (one launch group), rocprofv3 --pmc",
                      "kernel": "level kernels S'>=2 (divide/combine, Eq. 1-3)",
                      "ops_per_candidate": OPS_PER_CANDIDATE, "launches": launches,

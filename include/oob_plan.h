@@ -131,6 +131,12 @@ int oob_plan_destroy(oob_plan *h);
 int oob_plan_level_timing(oob_plan *h, int enable);
 int oob_plan_last_level_ms(oob_plan *h, float *ms /* HOST */);
 
+/* Measurement hook: runs a short microbenchmark (independent chains of 32-bit add, compare,
+ * select in every lane of every compute unit) on `stream`, waits for it, and returns the
+ * measured rate in lane-operations per second: the machine's own figure for the vector-ALU roof
+ * that the level kernels are priced against. */
+int oob_plan_valu_peak(oob_plan *h, void *stream, double *lane_ops_per_s /* HOST */);
+
 /* Introspection for tests: copies the records of (S', delta) left in the workspace by the last
  * oob_plan_templates call into dense DEVICE arrays of n*n entries, n = L - S' + 1, record
  * (u, v) at index u*n + (v - S') (v - u >= S'; other entries read as "no such state").

@@ -20,7 +20,7 @@ _ERR = {OOB_EINVAL: "OOB_EINVAL", OOB_ECAPACITY: "OOB_ECAPACITY", OOB_EOVERFLOW:
 
 SYMBOLS = ["oob_plan_max_stages", "oob_plan_workspace_size", "oob_plan_create",
            "oob_plan_templates", "oob_plan_templates_batch", "oob_plan_destroy", "oob_plan_export_block",
-           "oob_plan_level_timing", "oob_plan_last_level_ms", "oob_plan_export_flags"]
+           "oob_plan_level_timing", "oob_plan_last_level_ms", "oob_plan_export_flags", "oob_plan_valu_peak"]
 INST_SYMBOLS = ["oob_inst_workspace_size", "oob_inst_count", "oob_inst_enumerate"]
 
 
@@ -75,6 +75,8 @@ def load():
         L.oob_plan_export_flags.restype = C.c_int
         L.oob_plan_export_block.argtypes = [C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 7
         L.oob_plan_export_block.restype = C.c_int
+        L.oob_plan_valu_peak.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
+        L.oob_plan_valu_peak.restype = C.c_int
         L.oob_inst_workspace_size.argtypes = [C.c_int] * 3
         L.oob_inst_workspace_size.restype = C.c_size_t
         spec = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t]
@@ -230,6 +232,15 @@ class Planner:
         ms = C.c_float()
         check(load().oob_plan_last_level_ms(self.h, C.byref(ms)), "oob_plan_last_level_ms")
         return float(ms.value)
+
+    def valu_peak(self) -> float:
+        """Measured 32-bit lane-operations per second (oob_plan_valu_peak)."""
+        import torch
+
+        v = C.c_double()
+        s = torch.cuda.current_stream(self.device)
+        check(load().oob_plan_valu_peak(self.h, C.c_void_p(s.cuda_stream), C.byref(v)), "oob_plan_valu_peak")
+        return float(v.value)
 
     def new_outputs(self, inp) -> DeviceTemplates:
         Smax = oob_plan_max_stages(inp.L, inp.n_max, inp.gpus_per_node, inp.microbatches)

@@ -1208,6 +1208,25 @@ extern "C" int oob_plan_last_level_ms(oob_plan *h, float *ms) {
     return OOB_OK;
 }
 
+// Measurement: sixteen independent chains of 32-bit add / compare / select per lane, the
+// operation mix the roofline of the level kernels is quoted in.  3 lane-operations per chain step.
+__global__ void __launch_bounds__(256) k_valu_peak(int *sink, int iters, int a, int b) {
+    int v[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = threadIdx.x + i * a;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int w = v[i] + a;
+            v[i] = w > b ? w : v[i];
+        }
+    }
+    int r = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) r ^= v[i];
+    if (r == 0x7fffffff) sink[0] = r; // keeps the chains alive; practically never taken
+}
+
 // Copies flags[0..3] of the last call to a device array (tests: which split kernel ran).
 __global__ void k_export_flags(const int *flags, int *dst) {
     if (threadIdx.x < 4) dst[threadIdx.x] = flags[threadIdx.x];
@@ -1232,5 +1251,28 @@ extern "C" int oob_plan_export_block(oob_plan *h, int S, int delta, double *T, d
     hipLaunchKernelGGL(k_export, dim3((n * n + 255) / 256), dim3(256), 0, (hipStream_t)stream, t, S, delta, T,
                        T1, tmax, T3, (int *)kstar, (int *)choice);
     OOB_HIP_CHECK(hipGetLastError());
+    return OOB_OK;
+}
+
+// Measured vector-ALU peak of this GPU in 32-bit lane-operations per second (add, compare,
+// select), for comparison with the nominal 256 CUs x 64 lanes x clock.
+extern "C" int oob_plan_valu_peak(oob_plan *h, void *stream, double *lane_ops_per_s) {
+    if (!h || !lane_ops_per_s) return OOB_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t e0, e1;
+    OOB_HIP_CHECK(hipEventCreate(&e0));
+    OOB_HIP_CHECK(hipEventCreate(&e1));
+    const int iters = 20000, grid = 256 * 32; // 32 workgroups of 4 waves per compute unit
+    int *sink = (int *)(h->ws + h->cv.flags) + 32; // spare words of the flags array
+    hipLaunchKernelGGL(k_valu_peak, dim3(grid), dim3(256), 0, st, sink, 100, 1, 1 << 30); // warm-up
+    OOB_HIP_CHECK(hipEventRecord(e0, st));
+    hipLaunchKernelGGL(k_valu_peak, dim3(grid), dim3(256), 0, st, sink, iters, 1, 1 << 30);
+    OOB_HIP_CHECK(hipEventRecord(e1, st));
+    OOB_HIP_CHECK(hipEventSynchronize(e1));
+    float ms = 0.f;
+    OOB_HIP_CHECK(hipEventElapsedTime(&ms, e0, e1));
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    *lane_ops_per_s = (double)grid * 256 * 16 * 3 * iters / (ms * 1e-3);
     return OOB_OK;
 }
