@@ -102,6 +102,8 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=4, help="workload 1-4 (default: headline 4)")
+    ap.add_argument("--paper-nb", action="store_true",
+                    help="N_b = 4 S' per state (the paper's planning-time choice) instead of the configuration's N_b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="before the steps, run one device-to-device copy of this many MiB (a plain "
@@ -120,6 +122,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     inp = inputs.config(args.config)
+    if args.paper_nb:
+        inp = dataclasses.replace(inp, microbatches=0, name=inp.name + "_paper_nb")
     planner = P.Planner(inp.L, inp.n_max, inp.gpus_per_node)
     prof = P.DeviceProfile(inp)
     out = planner.new_outputs(inp)
@@ -161,7 +165,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"config {args.config}: {inp.name}, L={inp.L} profile entries, "
                                f"templates n={inp.n_min}..{inp.n_max} x {inp.gpus_per_node} GPUs, "
-                               f"N_b={inp.microbatches}, f={inp.f}",
+                               f"N_b={inp.microbatches if inp.microbatches else '4S (per state)'}, f={inp.f}",
                    "states": states, "candidates": cands, "levels": Smax},
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12,
                      "unit": "T lane-op/s", "frac": achieved / PEAK_LANE_OPS, "traffic": traffic,

@@ -6,6 +6,7 @@ stage-count level over the canonical form of every state record of that level
 (tests/parity_util.canonical_oracle_block).  Takes minutes for configuration 4.
 
     python tests/golden/make_golden.py cfg4
+    python tests/golden/make_golden.py cfg4_paper_nb     (configuration 4 with N_b = 4 S' per state)
     python tests/golden/make_golden.py cfg5 <instance> [<instance> ...]
 """
 import hashlib
@@ -53,6 +54,11 @@ def main():
     if which == "cfg4":
         inp = inputs.config(4)
         json.dump(expected(inp), open(os.path.join(HERE, "cfg4_expected.json"), "w"))
+    elif which == "cfg4_paper_nb":
+        import dataclasses
+
+        inp = dataclasses.replace(inputs.config(4), microbatches=0, name="cfg4_gpt175b_paper_nb")
+        json.dump(expected(inp), open(os.path.join(HERE, "cfg4_paper_nb_expected.json"), "w"))
     elif which == "cfg5":
         insts = inputs.config(5)
         for idx in map(int, sys.argv[2:]):

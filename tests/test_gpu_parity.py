@@ -137,6 +137,19 @@ def test_config4_full_size_against_stored_oracle_results(P):
     assert (got["states"], got["candidates"]) == (3724666, 16232508904)
 
 
+@pytest.mark.timeout(900)
+def test_config4_with_the_papers_microbatch_choice_against_stored_oracle_results(P):
+    """Configuration 4 with N_b = 4 S' per state (the paper's planning-time choice, Section
+    4.1.2): the cost coefficients then differ per level (cl = 3 r, cr = 4 s).  Stored results
+    written by tests/golden/make_golden.py cfg4_paper_nb (oracle only)."""
+    import dataclasses
+
+    inp = dataclasses.replace(inputs.config(4), microbatches=0, name="cfg4_gpt175b_paper_nb")
+    say("config 4, N_b = 4 S'")
+    got = check_against_golden(P, inp, os.path.join(GOLD, "cfg4_paper_nb_expected.json"))
+    assert (got["states"], got["candidates"]) == (3724666, 16232508904)
+
+
 def test_device_status_reports_bad_profile_values(P):
     import torch
 
