@@ -24,7 +24,6 @@ namespace oob_inst {
 
 constexpr long long kSat = 1ll << 62; // counts saturate here; a saturated total is an error
 constexpr int kGroup = 8;             // counts a lane reads at once
-constexpr int kWalks = 1;             // vectors a lane produces side by side (2 measured slower: the kernel is bound by instruction issue, not by read latency)
 
 // Count table: row (N', q) holds C(j, N', q) for j = 0..p, padded to whole groups, so that the
 // counts a position is compared with (same N', same q, descending j) are contiguous.
@@ -123,7 +122,7 @@ __global__ void __launch_bounds__(1024) k_inst_count(Spec s, long long *offsets,
     if (threadIdx.x == 0) *s.narrow = narrow;
 }
 
-// Every output vector is produced on its own (kWalks per lane).  A vector at position rho of the list of (N', q)
+// One lane per output vector (grid-stride).  A vector at position rho of the list of (N', q)
 // over the first j sizes has its highest non-zero count at the largest i < j with
 // C(i, N', q) <= rho (the lists over fewer sizes are prefixes of the list over more); it then
 // continues at position rho - C(i, N', q) of (N' - n_i, q - 1) over the first i+1 sizes.  The
@@ -133,102 +132,71 @@ __global__ void __launch_bounds__(1024) k_inst_count(Spec s, long long *offsets,
 // that group.  C is non-decreasing along a row, so the number of entries <= rho locates i without
 // a search.
 template <typename CT> // long long, or unsigned when the counting kernel could narrow the table
+__device__ __forceinline__ void unrank_all(const Spec &s, const long long *offsets, unsigned short *x,
+                                           long long capacity, long long total) {
+    const int len = s.N_hi - s.N_lo + 1, QQ = s.Q + 1;
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    const CT *tab = sizeof(CT) == 4 ? (const CT *)s.cnt32 : (const CT *)s.cnt;
+    for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
+        int lo = 0, hi = len - 1; // last N' whose list starts at or before idx
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (offsets[mid] <= idx) lo = mid; else hi = mid - 1;
+        }
+        int N = s.N_lo + lo, q = s.Q;
+        CT rho = (CT)(idx - offsets[lo]);
+        for (int g = (s.p - 1) / kGroup; g >= 0; --g) {
+            const int base = g * kGroup;
+            int kcap = s.p - 1 - base < kGroup - 1 ? s.p - 1 - base : kGroup - 1; // sizes base..base+kcap may get a pipeline
+            unsigned long long xlo = 0, xhi = 0; // kGroup 16-bit counts
+            while (true) {
+                const CT *row = tab + ((long long)N * QQ + q) * s.R + base;
+                CT c[kGroup];
+#pragma unroll
+                for (int k = 0; k < kGroup; ++k) c[k] = row[k];
+                if (c[0] > rho) break; // nothing (more) in this group: the usual case for the large sizes
+                int m = 0;             // entries <= rho: a prefix of the row
+#pragma unroll
+                for (int k = 0; k < kGroup; ++k) m += c[k] <= rho ? 1 : 0;
+                const int ks = m - 1 < kcap ? m - 1 : kcap;
+                // c[ks] by halving (no indexed registers)
+                const bool b0 = ks & 1, b1 = ks & 2, b2 = ks & 4;
+                const CT c01 = b0 ? c[1] : c[0], c23 = b0 ? c[3] : c[2], c45 = b0 ? c[5] : c[4], c67 = b0 ? c[7] : c[6];
+                const CT c03 = b1 ? c23 : c01, c47 = b1 ? c67 : c45;
+                const CT ck = b2 ? c47 : c03;
+                const int nk = size_of(s, base + ks); // consecutive sizes: arithmetic; a list: one cached read
+                if (nk > N) break; // cannot happen with a consistent table; keeps the loop finite
+                rho -= ck;
+                N -= nk;
+                q = q > 0 ? q - 1 : 0;
+                kcap = ks;
+                const unsigned long long one = 1ull << (16 * (ks & 3));
+                if (b2) xhi += one; else xlo += one;
+            }
+            unsigned short *xr = x + (long long)base * capacity + idx; // row `base` of the output, this lane's column
+            if (base + kGroup <= s.p) { // whole group: no per-template test
+#pragma unroll
+                for (int k = 0; k < kGroup; ++k, xr += capacity)
+                    *xr = (unsigned short)((k < 4 ? xlo : xhi) >> (16 * (k & 3)));
+            } else {
+#pragma unroll
+                for (int k = 0; k < kGroup; ++k, xr += capacity)
+                    if (base + k < s.p) *xr = (unsigned short)((k < 4 ? xlo : xhi) >> (16 * (k & 3)));
+            }
+        }
+    }
+}
+
 __global__ void __launch_bounds__(256) k_inst_unrank(Spec s, const long long *offsets, int *status,
                                                      unsigned short *x, long long capacity) {
-    if (*status != OOB_OK || (*s.narrow != 0) != (sizeof(CT) == 4)) return;
-    const int len = s.N_hi - s.N_lo + 1, QQ = s.Q + 1;
-    const long long total = offsets[len];
+    if (*status != OOB_OK) return;
+    const long long total = offsets[s.N_hi - s.N_lo + 1];
     if (total > capacity) { // uniform: nothing is written
         if (blockIdx.x == 0 && threadIdx.x == 0) *status = OOB_ECAPACITY;
         return;
     }
-    // A lane walks kWalks vectors at once (positions i, i + slab, ...): their reads are
-    // independent, so the latency of one dependent chain of reads hides behind the others.
-    const long long slab = (total + kWalks - 1) / kWalks;
-    const long long stride = (long long)gridDim.x * blockDim.x;
-    const CT *tab = sizeof(CT) == 4 ? (const CT *)s.cnt32 : (const CT *)s.cnt;
-    for (long long i0 = (long long)blockIdx.x * blockDim.x + threadIdx.x; i0 < slab; i0 += stride) {
-        long long idx[kWalks];
-        bool valid[kWalks];
-        int N[kWalks], q[kWalks];
-        CT rho[kWalks];
-#pragma unroll
-        for (int w = 0; w < kWalks; ++w) {
-            idx[w] = i0 + w * slab;
-            valid[w] = idx[w] < total;
-            int lo = 0, hi = valid[w] ? len - 1 : 0; // last N' whose list starts at or before idx
-            while (lo < hi) {
-                const int mid = (lo + hi + 1) >> 1;
-                if (offsets[mid] <= idx[w]) lo = mid; else hi = mid - 1;
-            }
-            N[w] = s.N_lo + lo;
-            q[w] = s.Q;
-            rho[w] = valid[w] ? (CT)(idx[w] - offsets[lo]) : (CT)0;
-        }
-        for (int g = (s.p - 1) / kGroup; g >= 0; --g) {
-            const int base = g * kGroup;
-            int nsz[kGroup];
-#pragma unroll
-            for (int k = 0; k < kGroup; ++k) nsz[k] = base + k < s.p ? size_of(s, base + k) : 0;
-            int kcap[kWalks]; // sizes base..base+kcap may get a pipeline
-            unsigned long long xlo[kWalks], xhi[kWalks]; // kGroup 16-bit counts
-            bool act[kWalks];
-#pragma unroll
-            for (int w = 0; w < kWalks; ++w) {
-                kcap[w] = s.p - 1 - base < kGroup - 1 ? s.p - 1 - base : kGroup - 1;
-                xlo[w] = xhi[w] = 0;
-                act[w] = valid[w];
-            }
-            while (true) {
-                bool any = false;
-#pragma unroll
-                for (int w = 0; w < kWalks; ++w) any |= act[w];
-                if (!any) break;
-                CT c[kWalks][kGroup];
-#pragma unroll
-                for (int w = 0; w < kWalks; ++w) { // a finished walk re-reads its last row (in bounds, unused)
-                    const CT *row = tab + ((long long)N[w] * QQ + q[w]) * s.R + base;
-#pragma unroll
-                    for (int k = 0; k < kGroup; ++k) c[w][k] = row[k];
-                }
-#pragma unroll
-                for (int w = 0; w < kWalks; ++w) {
-                    int m = 0; // entries <= rho: a prefix of the row
-#pragma unroll
-                    for (int k = 0; k < kGroup; ++k) m += c[w][k] <= rho[w] ? 1 : 0;
-                    const int ks = m - 1 < kcap[w] ? m - 1 : kcap[w];
-                    // c[ks], nsz[ks] by halving (no indexed registers)
-                    const bool b0 = ks & 1, b1 = ks & 2, b2 = ks & 4;
-                    const CT c01 = b0 ? c[w][1] : c[w][0], c23 = b0 ? c[w][3] : c[w][2];
-                    const CT c45 = b0 ? c[w][5] : c[w][4], c67 = b0 ? c[w][7] : c[w][6];
-                    const CT c03 = b1 ? c23 : c01, c47 = b1 ? c67 : c45;
-                    const CT ck = b2 ? c47 : c03;
-                    const int n01 = b0 ? nsz[1] : nsz[0], n23 = b0 ? nsz[3] : nsz[2];
-                    const int n45 = b0 ? nsz[5] : nsz[4], n67 = b0 ? nsz[7] : nsz[6];
-                    const int n03 = b1 ? n23 : n01, n47 = b1 ? n67 : n45;
-                    const int nk = b2 ? n47 : n03;
-                    // m = 0: nothing (more) in this group; nk > N cannot happen with a consistent
-                    // table, the test keeps the loop finite and the next row inside the table
-                    act[w] = act[w] && m > 0 && nk <= N[w];
-                    if (act[w]) {
-                        rho[w] -= ck;
-                        N[w] -= nk;
-                        q[w] = q[w] > 0 ? q[w] - 1 : 0;
-                        kcap[w] = ks;
-                        const unsigned long long one = 1ull << (16 * (ks & 3));
-                        if (b2) xhi[w] += one; else xlo[w] += one;
-                    }
-                }
-            }
-#pragma unroll
-            for (int w = 0; w < kWalks; ++w)
-#pragma unroll
-                for (int k = 0; k < kGroup; ++k)
-                    if (valid[w] && base + k < s.p)
-                        x[(long long)(base + k) * capacity + idx[w]] =
-                            (unsigned short)((k < 4 ? xlo[w] : xhi[w]) >> (16 * (k & 3)));
-        }
-    }
+    if (*s.narrow) unrank_all<unsigned>(s, offsets, x, capacity, total); // the table's type is known here only
+    else unrank_all<long long>(s, offsets, x, capacity, total);
 }
 
 static bool args_ok(int p, int N_lo, int N_hi, int f) {
@@ -302,13 +270,10 @@ int oob_inst_enumerate(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, 
                               status, &s);
     if (rc != OOB_OK) return rc;
     if (capacity < 0 || (capacity > 0 && !x)) return OOB_EINVAL;
-    // one lane per kWalks vectors of the capacity; the kernel strides if the grid limit cuts that short
-    const long long want = ((capacity + kWalks - 1) / kWalks + 255) / 256;
+    // one lane per vector of the capacity; the kernel strides if the grid limit cuts that short
+    const long long want = (capacity + 255) / 256;
     const int grid = (int)(want < 1 ? 1 : (want > (1 << 22) ? (1 << 22) : want));
-    // the table's number type is known on the device only: the launch of the other type returns at once
-    hipLaunchKernelGGL(k_inst_unrank<unsigned>, dim3(grid), dim3(256), 0, (hipStream_t)stream, s,
-                       (const long long *)offsets, status, (unsigned short *)x, (long long)capacity);
-    hipLaunchKernelGGL(k_inst_unrank<long long>, dim3(grid), dim3(256), 0, (hipStream_t)stream, s,
+    hipLaunchKernelGGL(k_inst_unrank, dim3(grid), dim3(256), 0, (hipStream_t)stream, s,
                        (const long long *)offsets, status, (unsigned short *)x, (long long)capacity);
     return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
 }
