@@ -150,6 +150,37 @@ def test_config4_with_the_papers_microbatch_choice_against_stored_oracle_results
     assert (got["states"], got["candidates"]) == (3724666, 16232508904)
 
 
+@pytest.mark.timeout(900)
+def test_config4_repeated_calls_on_one_handle_stay_identical(P):
+    """Levels run on two streams with events between them: five calls back to back on one handle
+    (no host synchronisation in between) must leave exactly the stored oracle results, every
+    time -- a missing dependency between the streams would show up here as a changed record."""
+    import torch
+
+    inp = inputs.config(4)
+    g = json.load(open(os.path.join(GOLD, "cfg4_expected.json")))
+    want = {k: np.array(v) for k, v in g.items() if isinstance(v, list)}
+    want["states"], want["candidates"] = g["states"], g["candidates"]
+    planner = P.Planner(inp.L, inp.n_max, inp.gpus_per_node)
+    prof = P.DeviceProfile(inp)
+    outs = [planner.new_outputs(inp) for _ in range(5)]
+    for o in outs:
+        planner.enqueue(prof, o)
+    torch.cuda.synchronize()
+    for i, o in enumerate(outs):
+        say(f"call {i}")
+        PU.compare_templates(o.to_host(), want, inp.n_max - inp.n_min + 1)
+    D = inp.gpus_per_node - 1 + inp.n_max
+    for S in (2, 3, 17, 50, 51, 97, 98):  # the records the last call left behind
+        h = hashlib.sha256()
+        for delta in range(D):
+            gb = planner.block(S, delta)
+            if gb is not None:
+                h.update(PU.canonical_gpu_block(gb, S, inp.L))
+        assert h.hexdigest() == g["level_sha256"][str(S)], S
+    planner.close()
+
+
 def test_device_status_reports_bad_profile_values(P):
     import torch
 
