@@ -337,52 +337,69 @@ __global__ void __launch_bounds__(512) k_split(Tables t, int Sp, int fam, int NT
 constexpr int kKeyTargets = 64;
 constexpr int kFillBatch = 3; // records a thread has in flight while staging
 
-// Record e of the staging order for split point k: [left tables][u] then [right tables][v].
+// The (m, m') pairs of a split form a rectangle; an item keeps eight records of one side in
+// registers (the STATIONARY side, cut into blocks of eight unit counts, the last one padded) and
+// streams the other side.  Which child is stationary is chosen per workgroup so that the padding
+// is smaller (it is the same work either way).  Staging order for split point k:
+// [streaming tables][lane index], then [stationary tables, padded][lane index]; the lane index
+// is u for records of the left child and v for records of the right child.
 struct Stage {
     const Rec *rec;
-    long long tabA, tabB; // table index of left unit count 0 / right unit count 0
-    int tab_recs, NB, ub, vb, nA, nB, fillA, fill;
+    long long tabY, tabS; // table index of unit count 0 of the streaming / stationary side
+    int tab_recs, NB, ub, vb, nS, fillY, fill;
+    int y_is_left;        // 1: left child streams, right child stationary; 0: the other way round
     double cl, cr;
 };
 struct Rec24 { double2 a; double tm; }; // (T, T1), tmax: the 24 bytes of a record the splits need
 
 __device__ __forceinline__ Rec24 stage_load(const Stage &g, int k, int e) {
     Rec24 rc = {make_double2(kNone, kNone), 0.0};
-    const Rec *p = nullptr;
-    if (e < g.fillA) {       // left child (s, u, k, m): row u of block (ub, k/8)
-        p = g.rec + (g.tabA + (e >> 3)) * g.tab_recs + (long long)tri_index(g.ub, k >> 3, g.NB) * 64 + ((e & 7) << 3) + (k & 7);
-    } else if (e < g.fill) { // right child (r, k, v, m'): row k of block (k/8, vb)
-        const int e2 = e - g.fillA;
-        if ((e2 >> 3) < g.nB)
-            p = g.rec + (g.tabB + (e2 >> 3)) * g.tab_recs + (long long)tri_index(k >> 3, g.vb, g.NB) * 64 + ((k & 7) << 3) + (e2 & 7);
-    }
-    if (p) {
+    const bool stream = e < g.fillY;
+    const int e2 = stream ? e : e - g.fillY, tab = e2 >> 3, idx = e2 & 7;
+    if (e < g.fill && (stream || tab < g.nS)) {
+        const bool left = stream == (g.y_is_left != 0);
+        const long long table = (stream ? g.tabY : g.tabS) + tab;
+        // left child (s, u, k, m): row u of block (ub, k/8); right child (r, k, v, m'): row k of block (k/8, vb)
+        const Rec *p = g.rec + table * g.tab_recs +
+                       (left ? (long long)tri_index(g.ub, k >> 3, g.NB) * 64 + (idx << 3) + (k & 7)
+                             : (long long)tri_index(k >> 3, g.vb, g.NB) * 64 + ((k & 7) << 3) + idx);
         rc.a = *(const double2 *)p;
         rc.tm = p->tmax;
     }
     return rc;
 }
-// LDS order = staging order; values pre-combined with the level's coefficients.
+// LDS order = staging order; values pre-combined with the level's coefficients: left records as
+// (T + cl tmax, T1), right records as (2 T1, T + cr tmax).  The slowest-stage test of Eq. 3 is
+// "left tmax >= right tmax"; the step loop always tests "streaming >= stationary", so when the
+// right child streams both tmax are stored negated.
 __device__ __forceinline__ void stage_store(const Stage &g, double2 *pair, double *tm, int e, const Rec24 &rc) {
-    if (e < g.fillA) {
-        pair[e] = make_double2(rc.a.x + g.cl * rc.tm, rc.a.y);
-        tm[e] = rc.tm;
-    } else if (e < g.fill) {
-        pair[e] = make_double2(2.0 * rc.a.y, rc.a.x + g.cr * rc.tm);
-        tm[e] = rc.tm;
-    }
+    if (e >= g.fill) return;
+    const bool left = (e < g.fillY) == (g.y_is_left != 0);
+    pair[e] = left ? make_double2(rc.a.x + g.cl * rc.tm, rc.a.y) : make_double2(2.0 * rc.a.y, rc.a.x + g.cr * rc.tm);
+    tm[e] = g.y_is_left ? rc.tm : -rc.tm;
 }
 
-// One split point per pass, two LDS buffers: while the waves work on k from one buffer, every
-// thread has the records of k+1 in flight from HBM/L2 and drops them into the other buffer
-// before the single barrier of the pass.
+// Candidate slots an assignment of roles executes: per block of eight stationary unit counts the
+// streaming range that pairs with it (targets a0..a1), times eight.
+__device__ __forceinline__ int role_cost(int y0, int y1, int q0, int q1, int a0, int a1) {
+    int c = 0;
+    for (int qb = q0; qb <= q1; qb += 8) {
+        const int lo = imax(y0, a0 - (qb + 7)), hi = imin(y1, a1 - qb);
+        if (lo <= hi) c += hi - lo + 1;
+    }
+    return c;
+}
+
+// One split point per pass, one LDS buffer: while the waves work on k, every thread has the
+// records of k+1 in flight from HBM/L2 and drops them into the buffer between the two barriers
+// of the pass (NBUF = 2: two buffers and one barrier; needs more LDS, measured slower).
 template <int NTAB, int NA, int NBUF>
 __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, int NT, int NAall, int halves,
                                                    int s0, int sstep) {
     // Static, separate arrays: the compiler then knows that the key merges (atomics on s_acc) never
     // touch the staged records, and keeps the reads of the next step ahead of them.
-    __shared__ double2 s_pair[NBUF][NTAB * 8]; // [buffer][table][u or v]: (T + cl tmax, T1) / (2 T1, T + cr tmax)
-    __shared__ double s_tm[NBUF][NTAB * 8];    // tmax
+    __shared__ double2 s_pair[NBUF][NTAB * 8]; // [buffer][staging order]: pre-combined pairs
+    __shared__ double s_tm[NBUF][NTAB * 8];    // tmax (negated when the right child streams)
     __shared__ unsigned long long s_acc[(NA + 2) * 64]; // keys, rows 1..na
     if (t.flags[0] == 0) return;        // keys do not fit: k_select evaluates the candidates itself
     const int L = t.sh.L, M = t.sh.M, n_max = t.sh.n_max;
@@ -406,17 +423,23 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
     // this workgroup's segment of the split points of the block
     const int kmin = ub * 8 + s + seg * kSegK, kmax = imin(imin(vb * 8 + 7, L) - r, kmin + kSegK - 1);
     if (!(mA0 <= mA1 && mB0 <= mB1 && kmin <= kmax)) return; // nothing to merge
-    const int nA = mA1 - mA0 + 1, nB = mB1 - mB0 + 1, nmb = cdiv(nB, 8);
-    const int ntab = nA + 8 * nmb, TS = ntab * 8;
+    // roles: the left child streams (and the right one is stationary) unless the other way pads less
+    const bool y_left = role_cost(mA0, mA1, mB0, mB1, a_g0, a_g1) <= role_cost(mB0, mB1, mA0, mA1, a_g0, a_g1);
+    const int yM0 = y_left ? mA0 : mB0, yM1 = y_left ? mA1 : mB1; // streaming unit counts
+    const int qM0 = y_left ? mB0 : mA0, qM1 = y_left ? mB1 : mA1; // stationary unit counts
+    const int nY = yM1 - yM0 + 1, nS = qM1 - qM0 + 1, nmb = cdiv(nS, 8);
+    const int yl = y_left ? ul : vl, ql = y_left ? vl : ul; // lane index of a streaming / stationary record
+    const int fillY = nY * 8, TS = fillY + nmb * 64;
     const unsigned long long kNoneBits = 0x7FF0000000000000ull;
     const double KS = (double)(1 << key_bits(L));
 
     Stage g;
     g.rec = t.rec;
-    g.tabA = t.lvl_tab[s] - dlo_of(s, M) + fam_base + mA0;
-    g.tabB = t.lvl_tab[r] - dlo_of(r, M) + fam_base + mB0;
-    g.tab_recs = t.tab_recs; g.NB = t.NB; g.ub = ub; g.vb = vb; g.nA = nA; g.nB = nB;
-    g.fillA = nA * 8; g.fill = TS;
+    const long long tabA = t.lvl_tab[s] - dlo_of(s, M) + fam_base, tabB = t.lvl_tab[r] - dlo_of(r, M) + fam_base;
+    g.tabY = y_left ? tabA + mA0 : tabB + mB0;
+    g.tabS = y_left ? tabB + mB0 : tabA + mA0;
+    g.tab_recs = t.tab_recs; g.NB = t.NB; g.ub = ub; g.vb = vb; g.nS = nS;
+    g.fillY = fillY; g.fill = TS; g.y_is_left = y_left;
     g.cl = t.sh.Nb > 0 ? -(double)r : 3.0 * r;
     g.cr = t.sh.Nb > 0 ? 0.0 : 4.0 * s;
 
@@ -431,9 +454,9 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
         stage_store(g, s_pair[0], s_tm[0], e, stage_load(g, kmin, e));
     __syncthreads();
 
-    // Work items of a split point: the 8-blocks of m'.  Whole blocks go round robin over the waves;
-    // the blocks left over after the last full round are cut into `parts` pieces of their m range so
-    // that every wave gets one (halves = 0 disables the cutting).
+    // Work items of a split point: the 8-blocks of the stationary side.  Whole blocks go round robin
+    // over the waves; the blocks left over after the last full round are cut into `parts` pieces of
+    // their streaming range so that every wave gets one (halves = 0 disables the cutting).
     const int rem = nmb % nw, full = nmb - rem;
     const int parts = (halves && rem) ? imax(1, nw / rem) : 1;
     const int nitems = full + rem * parts;
@@ -448,9 +471,9 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
         for (int item = wave; item < nitems; item += nw) {
             const int cut = item >= full, jj = item - full;
             const int mb = cut ? full + jj / parts : item, part = cut ? jj % parts : 0, np = cut ? parts : 1;
-            const int mp0 = mB0 + 8 * mb;                       // first m' of the block
-            int mlo = imax(mA0, a_g0 - (mp0 + 7)), mhi = imin(mA1, a_g1 - mp0);
-            if (np > 1 && mlo <= mhi) { // piece `part` of `np` of the m range
+            const int q0 = qM0 + 8 * mb;                        // first stationary unit count of the block
+            int mlo = imax(yM0, a_g0 - (q0 + 7)), mhi = imin(yM1, a_g1 - q0); // streaming range
+            if (np > 1 && mlo <= mhi) { // piece `part` of `np` of that range
                 const int len = mhi - mlo + 1, lo = mlo + len * part / np;
                 mhi = mlo + len * (part + 1) / np - 1;
                 mlo = lo;
@@ -459,28 +482,29 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
             double bb2[8], bbt[8], btm[8], acc[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const int o = (nA + 8 * mb + i) * 8 + vl;
+                const int o = fillY + (8 * mb + i) * 8 + ql;
                 const double2 p = pair[o];
                 bb2[i] = p.x; bbt[i] = p.y; btm[i] = tmv[o];
                 acc[i] = kNone;
             }
             const double kd = (double)k;
             const int len = mhi - mlo + 1, j0 = (8 - (len & 7)) & 7;
-            int mbase = mlo - j0; // step j of a group handles m = mbase + j; the first group may start at j0
-            const int aoff = mp0 - a_g0;
-            // one step: candidates (m, m'0 + i), i = 0..7, into the rotating minima; then the minimum
-            // of target m + m'0 is complete for this item.  The left record of the NEXT step is
-            // read before this step's atomic, so that its latency hides behind the arithmetic
-            // (LDS operations complete in order, and the compiler may not move a read over an atomic).
-            const double2 *pa = pair + (mlo - mA0) * 8 + ul; // left record of the next step
-            const double *ta = tmv + (mlo - mA0) * 8 + ul;
+            int mbase = mlo - j0; // step j of a group handles streaming unit count mbase + j; the first group may start at j0
+            const int aoff = q0 - a_g0;
+            // one step: the streaming record y against the eight stationary ones, candidates for the
+            // targets y + q0 + i, into the rotating minima; then the minimum of target y + q0 is
+            // complete for this item.  The streaming record of the NEXT step is read before this
+            // step's atomic, so that its latency hides behind the arithmetic (LDS operations
+            // complete in order, and the compiler may not move a read over an atomic).
+            const double2 *pa = pair + (mlo - yM0) * 8 + yl; // streaming record of the next step
+            const double *ta = tmv + (mlo - yM0) * 8 + yl;
             double2 p = *pa;
             double atm = *ta;
 #define OOB_STEP(j)                                                                                   \
     {                                                                                                 \
         const int m = mbase + (j);                                                                    \
         pa += 8; ta += 8;                                                                             \
-        const double2 pn = *pa; /* may read one record past the last m: staged memory, unused */      \
+        const double2 pn = *pa; /* may read one record past the last one: staged memory, unused */    \
         const double tn = *ta;                                                                        \
         _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                               \
             const double T = atm >= btm[i] ? p.x + bb2[i] : p.y + bbt[i];                             \
@@ -502,7 +526,7 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
                 for (int j = 0; j < 8; ++j) OOB_STEP(j)
             }
 #undef OOB_STEP
-            // the last step was j = 7 with m = mhi: minima 0..6 belong to targets mhi + m'0 + 1 + i
+            // the last step was j = 7 with unit count mhi: minima 0..6 belong to targets mhi + q0 + 1 + i
 #pragma unroll
             for (int i = 0; i < 7; ++i) {
                 const int row = imin(imax(mhi + 1 + i + aoff, -1), na) + 1;
@@ -913,7 +937,10 @@ bool plan_split_key(const Shape &sh, int Sp, int fam, SplitPlan *p) {
             const int a0 = t_lo + g * kKeyTargets, a1 = imin(t_hi, a0 + kKeyTargets - 1);
             const int mA0 = imax(A_lo, a0 - B_hi), mA1 = imin(A_hi, a1 - B_lo);
             const int mB0 = imax(B_lo, a0 - A_hi), mB1 = imin(B_hi, a1 - A_lo);
-            if (mA0 <= mA1 && mB0 <= mB1) ntab = imax(ntab, mA1 - mA0 + 1 + 8 * cdiv(mB1 - mB0 + 1, 8));
+            if (mA0 <= mA1 && mB0 <= mB1) { // either child may be the stationary (padded) side
+                const int nA = mA1 - mA0 + 1, nB = mB1 - mB0 + 1;
+                ntab = imax(ntab, imax(nA + 8 * cdiv(nB, 8), nB + 8 * cdiv(nA, 8)));
+            }
         }
     }
     p->pc = kKeyHalves;
