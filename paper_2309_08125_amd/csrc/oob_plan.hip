@@ -30,6 +30,7 @@
 //            (s, k) whose candidate equals it -- the smallest (T, s, k, m) -- and the record.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
 #include <vector>
 #include <math.h>
 #include <new>
@@ -407,7 +408,6 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
     // the wave index is the same in all lanes: say so, and everything derived from it (work item,
     // m range, key row) is scalar arithmetic and scalar branches
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
-    const int ul = lane >> 3, vl = lane & 7;
     const int2 sg = t.seg_tab[(long long)(Sp - 2) * t.seg_stride + blockIdx.x]; // x: tile index, y: ub | vb << 8 | seg << 16
     const int tile = sg.x, ub = sg.y & 255, vb = (sg.y >> 8) & 255, seg = sg.y >> 16;
     const int fam_base = fam ? M - 2 : -1;
@@ -428,7 +428,6 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
     const int yM0 = y_left ? mA0 : mB0, yM1 = y_left ? mA1 : mB1; // streaming unit counts
     const int qM0 = y_left ? mB0 : mA0, qM1 = y_left ? mB1 : mA1; // stationary unit counts
     const int nY = yM1 - yM0 + 1, nS = qM1 - qM0 + 1, nmb = cdiv(nS, 8);
-    const int yl = y_left ? ul : vl, ql = y_left ? vl : ul; // lane index of a streaming / stationary record
     const int fillY = nY * 8, TS = fillY + nmb * 64;
     const unsigned long long kNoneBits = 0x7FF0000000000000ull;
     const double KS = (double)(1 << key_bits(L));
@@ -454,12 +453,11 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
         stage_store(g, s_pair[0], s_tm[0], e, stage_load(g, kmin, e));
     __syncthreads();
 
-    // Work items of a split point: the 8-blocks of the stationary side.  Whole blocks go round robin
-    // over the waves; the blocks left over after the last full round are cut into `parts` pieces of
-    // their streaming range so that every wave gets one (halves = 0 disables the cutting).
-    const int rem = nmb % nw, full = nmb - rem;
-    const int parts = (halves && rem) ? imax(1, nw / rem) : 1;
-    const int nitems = full + rem * parts;
+    // Work items of a split point: the 8-blocks of the stationary side, `R` of them side by side in a
+    // wave (see below).  Whole items go round robin over the waves; the items left over after the last
+    // full round are cut into `parts` pieces of their streaming range so that every wave gets one
+    // (halves = 0 disables the cutting).
+    const int chi = imin(vb * 8 + 7, L) - vb * 8; // last column of the block that exists
     for (int k = kmin; k <= kmax; ++k) {
         const int cur = NBUF == 2 ? (k - kmin) & 1 : 0, nxt = NBUF == 2 ? cur ^ 1 : 0;
         const double2 *pair = s_pair[cur];
@@ -468,11 +466,42 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
 #pragma unroll
             for (int q = 0; q < kFillBatch; ++q) pre[q] = stage_load(g, k + 1, threadIdx.x + q * blockDim.x);
         }
+        // Lanes of this pass.  Only the rows 0..jr of the block hold states that can be split at k
+        // (u + s <= k), and only the columns chi-jc..chi (k <= v - r): near the ends of the block's
+        // split range most of the 64 states idle.  Then the wave takes R items at once: the rows (or
+        // columns) that matter, padded to a power of two, times R stationary blocks.
+        const int jr = k - (ub * 8 + s), jc = imin(vb * 8 + 7, L) - r - k;
+        const int nr = imin(jr, 7) + 1, nc = imin(jc, chi) + 1;
+        const int lr = nr <= 1 ? 0 : nr <= 2 ? 1 : nr <= 4 ? 2 : 3, lc = nc <= 1 ? 0 : nc <= 2 ? 1 : nc <= 4 ? 2 : 3;
+        int R, slot, ue, ve; // items side by side, this lane's item among them, its row and column
+        if (lr <= lc) {      // rows 0..2^lr-1, all columns
+            R = 8 >> lr; slot = lane >> (3 + lr); ue = (lane >> 3) & ((1 << lr) - 1); ve = lane & 7;
+        } else {             // all rows, the last 2^lc columns that exist
+            R = 8 >> lc; slot = lane >> (3 + lc);
+            const int w = lane & ((8 << lc) - 1);
+            ue = w >> lc; ve = imax(0, chi - (1 << lc) + 1) + (w & ((1 << lc) - 1));
+        }
+        // The items of the pass, with (PACK) or without several of them side by side in a wave; the
+        // plain variant keeps the item's block, row offset and key column in scalar registers.
+        auto run_items = [&](auto pack_c, const int R, const int slot, const int ue, const int ve) {
+        constexpr bool PACK = decltype(pack_c)::value;
+        const int yl = y_left ? ue : ve, ql = y_left ? ve : ue; // lane index of a streaming / stationary record
+        const int col = PACK ? ue * 8 + ve : lane;              // this lane's state: its column of the key table
+        const int nsup = cdiv(nmb, R);
+        const int rem = nsup % nw, full = nsup - rem;
+        const int parts = ((halves & 3) && rem) ? imax(1, nw / rem) : 1;
+        const int nitems = full + rem * parts;
         for (int item = wave; item < nitems; item += nw) {
             const int cut = item >= full, jj = item - full;
-            const int mb = cut ? full + jj / parts : item, part = cut ? jj % parts : 0, np = cut ? parts : 1;
-            const int q0 = qM0 + 8 * mb;                        // first stationary unit count of the block
-            int mlo = imax(yM0, a_g0 - (q0 + 7)), mhi = imin(yM1, a_g1 - q0); // streaming range
+            const int sb = cut ? full + jj / parts : item, part = cut ? jj % parts : 0, np = cut ? parts : 1;
+            // stationary blocks sb R .. sb R + R - 1 (those that exist); this lane's is mb
+            const int mb_first = sb * R, mb_last = imin(mb_first + R - 1, nmb - 1);
+            const bool dead = PACK && mb_first + slot > mb_last; // a lane without a block works on the last one, unseen
+            const int mb = PACK ? imin(mb_first + slot, mb_last) : sb;
+            const int q0 = qM0 + 8 * mb;                // first stationary unit count of this lane's block
+            // streaming range: every unit count some block of the item pairs with inside the target
+            // group; a lane's surplus steps fall on targets outside the group and are swallowed
+            int mlo = imax(yM0, a_g0 - (qM0 + 8 * mb_last + 7)), mhi = imin(yM1, a_g1 - (qM0 + 8 * mb_first));
             if (np > 1 && mlo <= mhi) { // piece `part` of `np` of that range
                 const int len = mhi - mlo + 1, lo = mlo + len * part / np;
                 mhi = mlo + len * (part + 1) / np - 1;
@@ -484,7 +513,7 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
             for (int i = 0; i < 8; ++i) {
                 const int o = fillY + (8 * mb + i) * 8 + ql;
                 const double2 p = pair[o];
-                bb2[i] = p.x; bbt[i] = p.y; btm[i] = tmv[o];
+                bb2[i] = dead ? kNone : p.x; bbt[i] = dead ? kNone : p.y; btm[i] = tmv[o];
                 acc[i] = kNone;
             }
             const double kd = (double)k;
@@ -511,7 +540,7 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
             acc[((j) + i) & 7] = fmin(acc[((j) + i) & 7], T);                                         \
         }                                                                                             \
         const int row = imin(imax(m + aoff, -1), na) + 1;                                             \
-        atomicMin(&s_acc[row * 64 + lane], (unsigned long long)__double_as_longlong(fma(acc[(j)], KS, kd))); \
+        atomicMin(&s_acc[row * 64 + col], (unsigned long long)__double_as_longlong(fma(acc[(j)], KS, kd))); \
         acc[(j)] = kNone;                                                                             \
         p = pn; atm = tn;                                                                             \
     }
@@ -530,9 +559,12 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
 #pragma unroll
             for (int i = 0; i < 7; ++i) {
                 const int row = imin(imax(mhi + 1 + i + aoff, -1), na) + 1;
-                atomicMin(&s_acc[row * 64 + lane], (unsigned long long)__double_as_longlong(fma(acc[i], KS, kd)));
+                atomicMin(&s_acc[row * 64 + col], (unsigned long long)__double_as_longlong(fma(acc[i], KS, kd)));
             }
         }
+        };
+        if (R > 1 && nmb > 1 && (halves & 4)) run_items(std::true_type{}, R, slot, ue, ve);
+        else run_items(std::false_type{}, 1, 0, lane >> 3, lane & 7);
         if (NBUF == 1) __syncthreads(); // one buffer: everybody is done reading it before it is refilled
         if (k < kmax) {
 #pragma unroll
@@ -921,6 +953,7 @@ int env_or(const char *name, int dflt) {
 }
 static const int kKeyWaves = env_or("OOB_TUNE_KEY_WAVES", 4);
 static const int kKeyHalves = env_or("OOB_TUNE_KEY_HALVES", 2);
+static const int kKeyPack = env_or("OOB_TUNE_KEY_PACK", 1);
 bool plan_split_key(const Shape &sh, int Sp, int fam, SplitPlan *p) {
     int t_lo, t_hi;
     target_units(fam, Sp, sh.M, sh.n_max, &t_lo, &t_hi);
@@ -943,7 +976,7 @@ bool plan_split_key(const Shape &sh, int Sp, int fam, SplitPlan *p) {
             }
         }
     }
-    p->pc = kKeyHalves;
+    p->pc = (kKeyHalves & 3) | (kKeyPack ? 4 : 0); // bits 0-1: cut left-over items; bit 2: several items per wave near the range ends
     p->ntab = ntab;
     p->na = imin(cnt, kKeyTargets);
     p->lds = 0; // static LDS: see the capacity classes at the launch site
