@@ -26,8 +26,11 @@ OPS_PER_CANDIDATE = 30
 PEAK_LANE_OPS = 256 * 64 * 2.4e9  # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T 32-bit lane-ops/s
 # HBM bytes of the level kernels of one call on configuration 4, from the two rocprofv3 --pmc
 # runs (FETCH_SIZE, WRITE_SIZE) summarised in profiles/k_split_key_config4.md, scaled by what
-# the same counters read for a 256 MiB copy: 21.18 GB read + 5.72 GB written.
-HBM_BYTES_PER_CALL_CONFIG4 = 21.18e9 + 5.72e9
+# the same counters read for a 256 MiB copy: 21.01 GB read + 5.72 GB written.
+# Vector-ALU wave-instructions the level kernels execute per call on configuration 4 (SQ_INSTS_VALU of
+# the same summary): what the hardware actually issues, as opposed to the algorithmic count above.
+VALU_WAVE_INSTS_PER_CALL_CONFIG4 = 4.06e9 + 0.09e9  # k_split_key + k_select
+HBM_BYTES_PER_CALL_CONFIG4 = 21.01e9 + 5.72e9
 
 
 def cpu_baseline(inp):
@@ -170,6 +173,8 @@ def main():
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12,
                      "unit": "T lane-op/s", "frac": achieved / PEAK_LANE_OPS, "traffic": traffic,
                      "measured_peak": measured_peak / 1e12, "frac_of_measured_peak": achieved / measured_peak,
+                     "valu_issue_utilisation": (VALU_WAVE_INSTS_PER_CALL_CONFIG4 * 4 / (1024 * 2.4e9 * lvl_ms * 1e-3)
+                                                if args.config == 4 else None),
                      "traffic_unit": "HBM bytes per level (one launch group), rocprofv3 --pmc",
                      "kernel": "level kernels S'>=2 (divide/combine, Eq. 1-3)",
                      "ops_per_candidate": OPS_PER_CANDIDATE, "launches": launches,
