@@ -67,7 +67,9 @@ SHAPES = [(5, 1, 1, 3, 6), (6, 2, 1, 3, 8), (7, 2, 1, 2, 5), (6, 4, 1, 2, 12), (
           (6, 3, 1, 2, 0), (7, 1, 1, 4, 0), (9, 3, 1, 4, 4), (12, 2, 2, 5, 0), (10, 8, 1, 2, 16),
           (1, 1, 1, 1, 4), (1, 4, 1, 2, 4), (3, 2, 1, 5, 2), (37, 3, 1, 5, 9), (70, 2, 1, 6, 11),
           # more than 64 target device sets (two workgroup groups), 16 GPUs per node, many nodes
-          (72, 1, 1, 70, 0), (20, 16, 1, 2, 8), (40, 2, 1, 40, 64), (30, 3, 2, 30, 0)]
+          (72, 1, 1, 70, 0), (20, 16, 1, 2, 8), (40, 2, 1, 40, 64), (30, 3, 2, 30, 0),
+          # the largest node the library takes: 64 GPUs (OOB_MAX_GPUS), 63 device sets inside it
+          (40, 64, 1, 1, 0), (20, 64, 1, 2, 24)]
 
 
 @pytest.mark.parametrize("shape", SHAPES)
