@@ -324,14 +324,14 @@ __global__ void __launch_bounds__(512) k_split(Tables t, int Sp, int fam, int NT
 // ---------------------------------------------------------------------------------------
 // Levels S' >= 2, first kernel, keyed variant (runs when flags[0] = 1).
 //
-// Same result as k_split, different mapping.  A workgroup owns (block of the plane, s) and a
-// group of up to kKeyTargets target sets; per chunk of k it stages the left records of every
-// m and the right records of every m' (padded to whole 8-blocks of m') in LDS.  Work items
-// are (k, 8-block of m'); the waves take them round robin.  An item keeps its 8 right records
-// in registers and streams m: step m forms the 8 candidates (m, m'0..m'0+7), which belong to
-// the 8 consecutive targets a = m + m'0 + i.  The 8 running minima rotate: after step m the
-// minimum of target m + m'0 is complete for this item and is merged into the workgroup's LDS
-// table acc[a][lane] with an integer atomic min on the bits of key = total * 2^kbits + k
+// Same result as k_split, different mapping.  A workgroup owns (block of the plane, segment of
+// its split points, s) and a group of up to kKeyTargets target sets; per split point it stages
+// the records of both children for every unit count it needs in LDS.  Work items are (k, block
+// of eight unit counts of one child); the waves take them round robin.  An item keeps those
+// eight records in registers and streams the other child: a step forms eight candidates, which
+// belong to eight consecutive targets.  The eight running minima rotate: after a step the
+// minimum of the lowest target is complete for this item and is merged into the workgroup's
+// LDS table acc[a][lane] with an integer atomic min on the bits of key = total * 2^kbits + k
 // (non-negative doubles order like their bit patterns).  The key makes the merge order-free
 // and yields, per (s, state), the smallest total and the first k reaching it at once.
 // ---------------------------------------------------------------------------------------
