@@ -173,6 +173,7 @@ def main():
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12,
                      "unit": "T lane-op/s", "frac": achieved / PEAK_LANE_OPS, "traffic": traffic,
                      "measured_peak": measured_peak / 1e12, "frac_of_measured_peak": achieved / measured_peak,
+                     "frac_at_6_ops_per_candidate": cands * 6 / (lvl_ms * 1e-3) / PEAK_LANE_OPS,
                      "valu_issue_utilisation": (VALU_WAVE_INSTS_PER_CALL_CONFIG4 * 4 / (1024 * 2.4e9 * lvl_ms * 1e-3)
                                                 if args.config == 4 else None),
                      "traffic_unit": "HBM bytes per level (one launch group), rocprofv3 --pmc",
