@@ -183,6 +183,39 @@ def test_config4_repeated_calls_on_one_handle_stay_identical(P):
     planner.close()
 
 
+def test_call_can_be_captured_into_a_graph_and_replayed(P):
+    """The call forks to the handle's second stream and joins it again with events, so a caller
+    may capture it.  The graph is replayed three times with eager work in between; every replay
+    must give the oracle's templates again (the output buffers are cleared before each)."""
+    import torch
+
+    inp = inputs.config(2)
+    o, want = oracle_expected(inp)
+    o.close()
+    planner = P.Planner(inp.L, inp.n_max, inp.gpus_per_node)
+    prof = P.DeviceProfile(inp)
+    out = planner.new_outputs(inp)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        planner.enqueue(prof, out)  # first call: the handle creates its second stream and events
+    torch.cuda.synchronize()
+    PU.compare_templates(out.to_host(), want, inp.n_max - inp.n_min + 1)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        planner.enqueue(prof, out)
+    for i in range(3):
+        say(f"replay {i}")
+        for v in out.t.values():
+            v.zero_()
+        torch.randn(1 << 20, device="cuda").sum().item()  # eager work and a synchronisation between replays
+        graph.replay()
+        torch.cuda.synchronize()
+        PU.compare_templates(out.to_host(), want, inp.n_max - inp.n_min + 1)
+    full = {(S, d): planner.block(S, d) for S in (2, 9, 17) for d in range(2, 8)}
+    assert any(b is not None for b in full.values())
+    planner.close()
+
+
 def test_device_status_reports_bad_profile_values(P):
     import torch
 
