@@ -79,6 +79,15 @@ def test_large_cluster_sizes_take_the_table_from_global_memory(P):
     assert compare(P, sizes, 1000, 1100, 2) > 1000
 
 
+def test_largest_dimensions_the_entry_points_take(P):
+    """OOB_INST_MAX_P template sizes and cluster sizes up to OOB_INST_MAX_N: 1023 sizes
+    3073..4095, N' = 3990..4095: one pipeline of exactly N' nodes is the only way each time."""
+    sizes = list(range(3073, 4096))
+    print("1023 sizes, N' 3990..4095", flush=True)
+    assert compare(P, sizes, 3990, 4095, 0) == 106
+    assert compare(P, sizes, 4000, 4095, 1) == 0          # two pipelines never fit
+
+
 def test_integer_table_path(P, monkeypatch):
     """Counts of 2^53 and more keep the table in int64 (no case the oracle could enumerate gets
     there): the knob forces that path on ordinary cases."""
