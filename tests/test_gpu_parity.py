@@ -87,6 +87,16 @@ def test_small_random_every_state(P, shape):
     planner.close()
 
 
+def test_longest_model_the_library_takes(P):
+    """OOB_MAX_L layers (1023): 129 x 129 blocks of the plane, up to 128 segments per block."""
+    planner = P.Planner(1023, 2, 1)
+    full_check(P, planner, inputs.random_small(5, 1023, 1, 1, 2, 0, f=1))
+    planner.close()
+    planner = P.Planner(300, 2, 2)
+    full_check(P, planner, inputs.random_small(5, 300, 2, 1, 2, 5, f=1))
+    planner.close()
+
+
 def test_handle_reuse_across_shapes(P):
     """One handle sized for the maxima serves smaller jobs back to back."""
     planner = P.Planner(40, 6, 4)
