@@ -130,7 +130,7 @@ __global__ void __launch_bounds__(1024) k_inst_count(Spec s, long long *offsets,
 // the groups, so the kGroup counts of a group are stored by whole waves (128 contiguous bytes
 // per template), and one read of kGroup counts fetches every count a lane must compare with in
 // that group.  C is non-decreasing along a row, so the number of entries <= rho locates i without
-// a search.
+// a search, and a group whose first count exceeds rho holds no pipeline of this vector.
 template <typename CT> // long long, or unsigned when the counting kernel could narrow the table
 __device__ __forceinline__ void unrank_all(const Spec &s, const long long *offsets, unsigned short *x,
                                            long long capacity, long long total) {
@@ -145,16 +145,33 @@ __device__ __forceinline__ void unrank_all(const Spec &s, const long long *offse
         }
         int N = s.N_lo + lo, q = s.Q;
         CT rho = (CT)(idx - offsets[lo]);
+        // A group can hold a pipeline only if its first count is <= rho.  The first counts of up to
+        // eight groups are read in one go (independent reads), so that the many empty groups of the
+        // large sizes cost one round trip together instead of one each.
+        int gcov = (s.p - 1) / kGroup + 1; // groups gcov.. have been probed with the current (N, q, rho)
+        int gnext = -1;                    // highest probed group that can hold a pipeline
         for (int g = (s.p - 1) / kGroup; g >= 0; --g) {
             const int base = g * kGroup;
+            if (g < gcov) {
+                const CT *r0 = tab + ((long long)N * QQ + q) * s.R;
+                CT f[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) f[i] = r0[(g - i > 0 ? g - i : 0) * kGroup];
+                gnext = -1;
+#pragma unroll
+                for (int i = 7; i >= 0; --i)
+                    if (g - i >= 0 && f[i] <= rho) gnext = g - i;
+                gcov = g - 7 > 0 ? g - 7 : 0;
+            }
             int kcap = s.p - 1 - base < kGroup - 1 ? s.p - 1 - base : kGroup - 1; // sizes base..base+kcap may get a pipeline
             unsigned long long xlo = 0, xhi = 0; // kGroup 16-bit counts
-            while (true) {
+            while (g == gnext) {
                 const CT *row = tab + ((long long)N * QQ + q) * s.R + base;
                 CT c[kGroup];
 #pragma unroll
                 for (int k = 0; k < kGroup; ++k) c[k] = row[k];
-                if (c[0] > rho) break; // nothing (more) in this group: the usual case for the large sizes
+                gcov = g;              // whatever follows changes (N, q, rho): the groups below are probed again
+                if (c[0] > rho) break; // nothing (more) in this group
                 int m = 0;             // entries <= rho: a prefix of the row
 #pragma unroll
                 for (int k = 0; k < kGroup; ++k) m += c[k] <= rho ? 1 : 0;
