@@ -97,8 +97,8 @@ def bench_instantiation(P, inp, res, reps=20):
             "roofline": {"bound": "hbm", "achieved": nbytes / t_enum / 1e9, "peak": 8000.0, "unit": "GB/s",
                          "frac": nbytes / t_enum / 8e12,
                          # rocprofv3 --pmc of this kernel on configuration 4's node specification, scaled as
-                         # above: 149 557 KiB written + 907 KiB read per launch (profiles/k_inst_unrank_config4.md)
-                         "traffic": (149557 + 907) * 1024 if (n0, n_hi, inp.f) == (8, 64, 8) else None,
+                         # above: 149 557 KiB written + 694 KiB read per launch (profiles/k_inst_unrank_config4.md)
+                         "traffic": (149557 + 694) * 1024 if (n0, n_hi, inp.f) == (8, 64, 8) else None,
                          "kernel": "k_inst_unrank", "bytes_per_vector": 2 * p}}
 
 
