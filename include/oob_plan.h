@@ -120,6 +120,8 @@ int oob_plan_templates_batch(oob_plan *h, int count, const oob_profile *profiles
                              const int *microbatches, const int64_t *mem_cap, const int *f,
                              oob_templates *outs, void *stream);
 
+/* Releases the handle.  The caller must have waited for every call that used it (the handle's
+ * second stream and events go back to a pool of the library for the next handle). */
 int oob_plan_destroy(oob_plan *h);
 
 /* Measurement hook.  After oob_plan_level_timing(h, 1) every oob_plan_templates call records

@@ -30,6 +30,7 @@
 //            (s, k) whose candidate equals it -- the smallest (T, s, k, m) -- and the record.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <type_traits>
 #include <vector>
 #include <math.h>
@@ -988,6 +989,36 @@ bool plan_split_key(const Shape &sh, int Sp, int fam, SplitPlan *p) {
 
 using namespace oob;
 
+// The second stream and the events of a handle are borrowed from a pool that lives as long as the
+// process and are given back when the handle is destroyed: nothing is created or destroyed per
+// handle once the pool is warm (a harness that created and destroyed hundreds of handles, each
+// with a stream and events of its own, ended in a host segmentation fault inside the runtime).
+struct AuxPool {
+    std::mutex mu;
+    std::vector<hipStream_t> streams;
+    std::vector<hipEvent_t> events;
+};
+static AuxPool &aux_pool() {
+    static AuxPool *p = new AuxPool(); // never destroyed: no order-of-destruction trouble at exit
+    return *p;
+}
+static hipStream_t borrow_stream() {
+    AuxPool &p = aux_pool();
+    std::lock_guard<std::mutex> lk(p.mu);
+    if (!p.streams.empty()) { hipStream_t s = p.streams.back(); p.streams.pop_back(); return s; }
+    hipStream_t s = nullptr;
+    if (hipStreamCreateWithFlags(&s, hipStreamNonBlocking) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+    return s;
+}
+static hipEvent_t borrow_event() {
+    AuxPool &p = aux_pool();
+    std::lock_guard<std::mutex> lk(p.mu);
+    if (!p.events.empty()) { hipEvent_t e = p.events.back(); p.events.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+    return e;
+}
+
 struct oob_plan {
     int max_L, max_nodes, max_M;
     char *ws;
@@ -997,8 +1028,8 @@ struct oob_plan {
     bool have_last;
     hipEvent_t ev_begin, ev_end; // optional: recorded around the level launches
     bool timed;
-    hipStream_t aux;             // second stream for the odd levels (null: everything on the caller's stream)
-    std::vector<hipEvent_t> ev_level; // [S'] "level S' selected"; ev_level[0], [1]: fork and join
+    hipStream_t aux;             // second stream for the odd levels, borrowed (null: everything on the caller's stream)
+    std::vector<hipEvent_t> ev_level; // [S'] "level S' selected", borrowed; ev_level[0]: fork
 };
 
 #define OOB_HIP_CHECK(expr)                                                                   \
@@ -1045,8 +1076,12 @@ extern "C" int oob_plan_create(oob_plan **h, int max_L, int max_nodes, int max_g
 extern "C" int oob_plan_destroy(oob_plan *h) {
     if (!h) return OOB_EINVAL;
     if (h->ev_begin) { (void)hipEventDestroy(h->ev_begin); (void)hipEventDestroy(h->ev_end); }
-    for (hipEvent_t e : h->ev_level) (void)hipEventDestroy(e);
-    if (h->aux) (void)hipStreamDestroy(h->aux);
+    { // the caller has waited for the handle's work: its stream and events go back to the pool
+        AuxPool &p = aux_pool();
+        std::lock_guard<std::mutex> lk(p.mu);
+        for (hipEvent_t e : h->ev_level) p.events.push_back(e);
+        if (h->aux) p.streams.push_back(h->aux);
+    }
     delete h;
     return OOB_OK;
 }
@@ -1173,14 +1208,11 @@ extern "C" int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L
     // tails of each other's launches.  Each stream has its own buffer of per-split minima.
     static const int want_overlap = env_or("OOB_TUNE_OVERLAP", 1);
     bool overlap = want_overlap && !force_plain && sh.Smax >= 4;
-    if (overlap && !h->aux && hipStreamCreateWithFlags(&h->aux, hipStreamNonBlocking) != hipSuccess) {
-        h->aux = nullptr;
-        (void)hipGetLastError();
-    }
+    if (overlap && !h->aux) h->aux = borrow_stream();
     if (overlap && h->aux) {
         while ((int)h->ev_level.size() < sh.Smax + 1) {
-            hipEvent_t e;
-            if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); break; }
+            hipEvent_t e = borrow_event();
+            if (!e) break;
             h->ev_level.push_back(e);
         }
     }
