@@ -97,6 +97,37 @@ def test_longest_model_the_library_takes(P):
     planner.close()
 
 
+def test_many_random_shapes_on_one_handle(P):
+    """Four hundred random shapes (L, GPUs per node, template range, N_b, f, memory and
+    forbidden-GPU-count variants, large times, uniform layers) back to back on one handle, every
+    state of every case against the oracle."""
+    import random
+
+    rng = random.Random(2309)
+    planner = P.Planner(60, 24, 16)
+    states = 0
+    for case in range(400):
+        M = rng.choice([1, 1, 2, 3, 4, 5, 8, 8, 12, 16])
+        L = rng.randint(1, 60 if M <= 4 else 34)
+        n_max = rng.randint(1, max(1, min(24, L)))
+        n_min = rng.randint(1, n_max)
+        nb = rng.choice([0, 0, rng.randint(1, 2 * L + 2), rng.randint(1, 12)])
+        kw = {}
+        if rng.random() < 0.15:
+            kw["t_lo"] = 1 << rng.randint(20, 30)
+            kw["t_hi"] = 2 * kw["t_lo"]
+        if rng.random() < 0.2:
+            kw["uniform_layers"] = True
+        if rng.random() < 0.3:
+            kw["boundary"] = rng.random() < 0.5
+        var = rng.choice(["plain", "tight", "forbid"])
+        inp = inputs.random_small(rng.randint(0, 10**6), L, M, n_min, n_max, nb, f=rng.randint(0, 4),
+                                  tight_mem=(var == "tight"), forbid_some_d=(var == "forbid"), **kw)
+        states += full_check(P, planner, inp)[1]
+    planner.close()
+    assert states > 1_000_000
+
+
 def test_handle_reuse_across_shapes(P):
     """One handle sized for the maxima serves smaller jobs back to back."""
     planner = P.Planner(40, 6, 4)
