@@ -11,3 +11,4 @@ from .synthetic import (  # noqa: F401
     make_profile,
     random_small,
 )
+from .failures import failure_draws, starting_pipelines  # noqa: F401,E402
