@@ -22,6 +22,8 @@ SYMBOLS = ["oob_plan_max_stages", "oob_plan_workspace_size", "oob_plan_create",
            "oob_plan_templates", "oob_plan_templates_batch", "oob_plan_destroy", "oob_plan_export_block",
            "oob_plan_level_timing", "oob_plan_last_level_ms", "oob_plan_export_flags", "oob_plan_valu_peak"]
 INST_SYMBOLS = ["oob_inst_workspace_size", "oob_inst_count", "oob_inst_enumerate"]
+RECONF_SYMBOLS = ["oob_reconf_simulate"]
+RECONF_ROWS = ("survived", "reinstantiated", "borrowed", "merges", "alive", "nodes", "violations", "stop")
 
 
 class oob_profile(C.Structure):
@@ -84,6 +86,10 @@ def load():
         L.oob_inst_count.restype = C.c_int
         L.oob_inst_enumerate.argtypes = spec + [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
         L.oob_inst_enumerate.restype = C.c_int
+        L.oob_reconf_simulate.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int,
+                                          C.c_int, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_void_p]
+        L.oob_reconf_simulate.restype = C.c_int
         _lib = L
     return _lib
 
@@ -153,6 +159,13 @@ def oob_inst_enumerate(sizes_ptr, p, n0, N_lo, N_hi, f, dev_workspace_ptr, works
                                      C.c_void_p(dev_workspace_ptr), workspace_bytes, C.c_void_p(x_ptr),
                                      capacity, C.c_void_p(offsets_ptr), C.c_void_p(status_ptr),
                                      C.c_void_p(stream_ptr))
+
+
+def oob_reconf_simulate(sizes0_ptr, c0, n0, n_hi, f, draws_ptr, steps, burst, T, trace_ptr, final_sizes_ptr,
+                        summary_ptr, status_ptr, stream_ptr) -> int:
+    return load().oob_reconf_simulate(C.c_void_p(sizes0_ptr), c0, n0, n_hi, f, C.c_void_p(draws_ptr), steps, burst,
+                                      T, C.c_void_p(trace_ptr), C.c_void_p(final_sizes_ptr),
+                                      C.c_void_p(summary_ptr), C.c_void_p(status_ptr), C.c_void_p(stream_ptr))
 
 
 # ---- convenience layer over torch device memory ------------------------------------------
@@ -367,6 +380,46 @@ class Instantiator:
         self.enqueue(x, total)
         torch.cuda.synchronize(self.device)
         return off, x.cpu().numpy().view("uint16")[:, :total].T.copy(), int(self.status.item())
+
+
+class FailureSimulator:
+    """Device buffers for oob_reconf_simulate: T trajectories of `steps` steps of `burst` failures."""
+
+    def __init__(self, sizes0, n0: int, n_hi: int, f: int, draws, trace: bool = True, device="cuda:0"):
+        """draws: uint32 host array [steps, burst, T] (inputs.failure_draws)."""
+        import numpy as np
+        import torch
+
+        self.device = torch.device(device)
+        self.steps, self.burst, self.T = (int(v) for v in draws.shape)
+        self.n0, self.n_hi, self.f = n0, n_hi, f
+        self.sizes0 = torch.tensor([int(v) for v in sizes0], dtype=torch.int32, device=self.device)
+        self.c0 = self.sizes0.numel()
+        self.draws = torch.from_numpy(np.ascontiguousarray(draws).view(np.int32)).to(self.device)  # uint32 bits
+        self.trace = torch.zeros((self.steps, self.T), dtype=torch.int32, device=self.device) if trace else None
+        self.final_sizes = torch.zeros((self.c0, self.T), dtype=torch.int32, device=self.device)
+        self.summary = torch.zeros((len(RECONF_ROWS), self.T), dtype=torch.int32, device=self.device)
+        self.status = torch.full((1,), -99, dtype=torch.int32, device=self.device)
+
+    def enqueue(self) -> None:
+        import torch
+
+        s = torch.cuda.current_stream(self.device)
+        check(oob_reconf_simulate(self.sizes0.data_ptr(), self.c0, self.n0, self.n_hi, self.f,
+                                  self.draws.data_ptr(), self.steps, self.burst, self.T,
+                                  self.trace.data_ptr() if self.trace is not None else 0,
+                                  self.final_sizes.data_ptr(), self.summary.data_ptr(), self.status.data_ptr(),
+                                  s.cuda_stream), "oob_reconf_simulate")
+
+    def run(self):
+        """(status, summary rows by name, final sizes [c0, T], trace words [steps, T] as uint32)."""
+        import torch
+
+        self.enqueue()
+        torch.cuda.synchronize(self.device)
+        summary = {k: self.summary[i].cpu().numpy() for i, k in enumerate(RECONF_ROWS)}
+        trace = self.trace.cpu().numpy().view("uint32") if self.trace is not None else None
+        return int(self.status.item()), summary, self.final_sizes.cpu().numpy(), trace
 
 
 def template_stages(r: dict, i: int):

@@ -28,7 +28,21 @@ def test_library_exports_every_declared_symbol():
     for name in inst:
         assert hasattr(lib, name), name
     assert sorted(B.INST_SYMBOLS) == inst
-    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["oob_inst.h", "oob_plan.h"]
+    reconf = declared_symbols("oob_reconf.h", "oob_reconf_")
+    assert reconf == ["oob_reconf_simulate"] and hasattr(lib, reconf[0]) and sorted(B.RECONF_SYMBOLS) == reconf
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["oob_inst.h", "oob_plan.h", "oob_reconf.h"]
+
+
+def test_reconfiguration_entry_point_validates_arguments_without_touching_the_gpu():
+    fake = 0x10000  # never dereferenced: every call below fails its host-side checks
+    call = lambda **kw: P.oob_reconf_simulate(kw.get("sizes0", fake), kw.get("c0", 4), kw.get("n0", 2),
+                                              kw.get("n_hi", 5), kw.get("f", 1), kw.get("draws", fake),
+                                              kw.get("steps", 3), kw.get("burst", 1), kw.get("T", 100), fake, fake,
+                                              kw.get("summary", fake), kw.get("status", fake), 0)
+    for bad in (dict(sizes0=0), dict(summary=0), dict(status=0), dict(c0=0), dict(c0=65), dict(n0=0), dict(n_hi=1),
+                dict(n_hi=65536), dict(f=-1), dict(steps=-1), dict(burst=0), dict(burst=256), dict(T=0),
+                dict(draws=0), dict(f=40000)):
+        assert call(**bad) == P.OOB_EINVAL, bad
 
 
 def test_instantiation_entry_points_validate_arguments_without_touching_the_gpu():

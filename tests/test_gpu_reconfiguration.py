@@ -1,0 +1,117 @@
+"""Reconfiguration simulator (Section 5.1, Appendix B) through the C ABI against the CPU oracle:
+every trace word, every final pipeline size and every summary row, bit for bit (integer work)."""
+import numpy as np
+import pytest
+
+import inputs
+from oracle import reconfiguration as R
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    import paper_2309_08125_amd as pkg
+
+    assert torch.cuda.is_available()
+    pkg.load()
+    return pkg
+
+
+def oracle_columns(sizes0, n0, n_hi, f, draws_t):
+    """What the library must report for one trajectory: (summary column, final sizes, trace words)."""
+    o = R.simulate(sizes0, n0, n_hi, f, draws_t)
+    words = [r.reinstantiated | r.borrowed << 8 | r.merges << 16 | r.alive << 23 | r.stop << 30 for r in o.steps]
+    alive = o.steps[-1].alive if o.steps else len(sizes0)
+    summary = [o.survived, sum(r.reinstantiated for r in o.steps), sum(r.borrowed for r in o.steps),
+               sum(r.merges for r in o.steps), alive, sum(o.sizes), o.violations, o.stop]
+    return summary, o.sizes, words
+
+
+def compare(P, sizes0, n0, n_hi, f, draws, sample=None):
+    st, summary, final, trace = P.FailureSimulator(sizes0, n0, n_hi, f, draws).run()
+    assert st == P.OOB_OK
+    T = draws.shape[2]
+    for t in (range(T) if sample is None else sample):
+        want_summary, want_sizes, want_words = oracle_columns(sizes0, n0, n_hi, f, draws[:, :, t])
+        assert [int(summary[k][t]) for k in P.RECONF_ROWS] == want_summary, (t, sizes0, n0, n_hi, f)
+        assert final[:, t].tolist() == want_sizes, (t, sizes0, n0, n_hi, f)
+        assert trace[:, t].tolist() == want_words, (t, sizes0, n0, n_hi, f)
+    return summary, final, trace
+
+
+def test_the_three_cases_of_the_reinstantiation_figure(P):
+    for sizes0, which, want in [([4, 2], 0, [3, 2]), ([2, 3, 2], 0, [2, 2, 2]), ([2, 2, 2], 1, [0, 3, 2])]:
+        draws = np.full((1, 1, 1), sum(sizes0[:which]), dtype=np.uint32)
+        _, final, _ = compare(P, sizes0, 2, 4, 1, draws)
+        assert final[:, 0].tolist() == want
+
+
+def test_random_specifications_every_trajectory(P):
+    """Several workgroups and a ragged last one, single failures and bursts, node specifications
+    with and without the full range of sizes (violations must then match too)."""
+    rng = np.random.Generator(np.random.PCG64(3))
+    cases = 0
+    while cases < 40:
+        seed = int(rng.integers(0, 1 << 30))
+        n0, f = int(rng.integers(1, 6)), int(rng.integers(0, 4))
+        N = (f + 1) * n0 + int(rng.integers(n0, 5 * n0 + 3))
+        n_hi = max(n0, N - f * n0 - int(rng.integers(0, 3)))
+        burst = int(rng.integers(1, 5))
+        T = int(rng.choice([1, 63, 257, 700]))
+        try:
+            sizes0 = inputs.starting_pipelines(seed, n0, n_hi, N, f).tolist()
+        except AssertionError:
+            continue
+        print("case", cases, sizes0, n0, n_hi, f, burst, T, flush=True)
+        draws = inputs.failure_draws(seed, N // burst + 2, burst, T)
+        compare(P, sizes0, n0, n_hi, f, draws)
+        cases += 1
+
+
+def test_edge_cases(P):
+    # no steps at all: the starting state comes back
+    st, summary, final, trace = P.FailureSimulator([3, 4], 3, 5, 0, np.zeros((0, 1, 5), dtype=np.uint32)).run()
+    assert st == P.OOB_OK and final.tolist() == [[3] * 5, [4] * 5] and summary["nodes"].tolist() == [7] * 5
+    assert summary["alive"].tolist() == [2] * 5 and summary["survived"].tolist() == [0] * 5
+    # the largest starting list and the largest burst
+    sizes0 = [2] * 64
+    compare(P, sizes0, 2, 3, 5, inputs.failure_draws(1, 3, 255, 70))
+    compare(P, [3] * 64, 2, 3, 0, inputs.failure_draws(2, 200, 1, 130))
+    # a single pipeline, f = 0: shrinks to n0, then training stops
+    summary, final, _ = compare(P, [9], 4, 9, 0, inputs.failure_draws(3, 8, 1, 3))
+    assert final.tolist() == [[3] * 3] and summary["survived"].tolist() == [5] * 3
+    # starting sizes that are no template sizes: reported on the device, nothing else written
+    sim = P.FailureSimulator([1, 2, 3], 2, 3, 0, inputs.failure_draws(0, 2, 1, 5))
+    st, summary, final, trace = sim.run()
+    assert st == P.OOB_EINVAL and not summary["nodes"].any() and not final.any() and not trace.any()
+    # without trace and final sizes
+    sim = P.FailureSimulator([2, 3, 4], 2, 4, 1, inputs.failure_draws(5, 6, 1, 300), trace=False)
+    st, summary, final, trace = sim.run()
+    want = [oracle_columns([2, 3, 4], 2, 4, 1, sim.draws.cpu().numpy().view("uint32")[:, :, t])[0] for t in range(300)]
+    assert st == P.OOB_OK and trace is None
+    assert [[int(summary[k][t]) for k in P.RECONF_ROWS] for t in range(300)] == want
+
+
+def test_headline_node_specification_at_full_size(P):
+    """The node specification of the headline workload (templates for 8..64 nodes, f = 8, so
+    N = 64 + 8 * 8 = 128 nodes), a million failure sequences down to the end of training, as
+    bench.py runs it.  Sampled trajectories against the oracle; all of them against what Section 5
+    and Appendix B promise for single failures: exactly N - (f+1) n0 failures are repaired,
+    every pipeline stays on a template size, f+1 pipelines remain."""
+    n0, n_hi, f, N = 8, 64, 8, 128
+    T = 1 << 20
+    sizes0 = inputs.starting_pipelines(4, n0, n_hi, N, f).tolist()
+    steps = N - (f + 1) * n0 + 1
+    draws = inputs.failure_draws(4, steps, 1, T)
+    sample = np.random.Generator(np.random.PCG64(9)).integers(0, T, size=200).tolist() + [0, T - 1]
+    summary, final, trace = compare(P, sizes0, n0, n_hi, f, draws, sample=sample)
+    assert (summary["survived"] == N - (f + 1) * n0).all()
+    assert (summary["nodes"] == (f + 1) * n0 - 1).all()
+    assert not summary["violations"].any()
+    assert (summary["stop"] == R.STOP_TOO_FEW_NODES).all()
+    assert (summary["alive"] >= f + 1).all()
+    assert (final.sum(axis=0) == (f + 1) * n0 - 1).all()
+    assert ((trace >> 30) == 0)[:-1].all() and ((trace >> 30) == 1)[-1].all()
+    assert (((trace >> 23) & 0x7F)[:-1] >= f + 1).all()
