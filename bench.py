@@ -102,6 +102,51 @@ def bench_instantiation(P, inp, res, reps=20):
                          "kernel": "k_inst_unrank", "bytes_per_vector": 2 * p}}
 
 
+def bench_reconfiguration(P, inp, res, trajectories=1 << 20, reps=5, oracle_sample=64):
+    """Section 5.1 on the node specification the planner just produced: `trajectories` failure
+    sequences, one node lost per step, from N nodes down to the end of training.  Timed with events
+    on the stream the kernel is launched on; the oracle is timed on a sample of the trajectories."""
+    import torch
+    import inputs
+    from oracle import reconfiguration
+
+    n0, n_hi, p, N = (int(v) for v in res["cover_hdr"][:4])
+    if p < 1 or N // n0 > 64:
+        return None
+    sizes0 = inputs.starting_pipelines(4, n0, n_hi, N, inp.f).tolist()
+    steps = N - (inp.f + 1) * n0 + 1
+    draws = inputs.failure_draws(4, steps, 1, trajectories)
+    sim = P.FailureSimulator(sizes0, n0, n_hi, inp.f, draws)
+    stream = torch.cuda.current_stream()
+    sim.enqueue()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev[0].record(stream)
+    for _ in range(reps):
+        sim.enqueue()
+    ev[1].record(stream)
+    torch.cuda.synchronize()
+    dt = ev[0].elapsed_time(ev[1]) / reps * 1e-3
+    st, summary, final, trace = sim.run()
+    assert st == P.OOB_OK and not summary["violations"].any(), "reconfiguration"
+    t0 = time.time()
+    for t in range(oracle_sample):
+        reconfiguration.simulate(sizes0, n0, n_hi, inp.f, draws[:, :, t])
+    cpu = oracle_sample * steps / (time.time() - t0)
+    # algorithmic HBM bytes: one draw read and one trace word written per step, summary and final sizes once
+    nbytes = trajectories * (8.0 * steps + 4 * (len(sizes0) + 8))
+    return {"workload": f"template sizes {n0}..{n_hi}, f={inp.f}, {N} nodes in {len(sizes0)} pipelines, "
+                        f"{trajectories} failure sequences of {steps} single-node failures",
+            "value": trajectories * steps / dt, "unit": "repaired failures/s", "ms": dt * 1e3,
+            "merges_per_sequence": float(summary["merges"].mean()),
+            "borrowed_per_sequence": float(summary["borrowed"].mean()),
+            "roofline": {"bound": "hbm", "achieved": nbytes / dt / 1e9, "peak": 8000.0, "unit": "GB/s",
+                         "frac": nbytes / dt / 8e12, "traffic": None, "kernel": "k_reconf",
+                         "bytes_per_step": 8},
+            "cpu_baseline": {"value": cpu, "unit": "repaired failures/s", "cores": 1, "kind": "oracle",
+                             "sample": f"{oracle_sample} of the sequences"}}
+
+
 def bench_batch(P, insts, args):
     """Configuration 5: 256 independent instances through oob_plan_templates_batch, profiles
     resident in HBM; a step is the whole batch."""
@@ -239,6 +284,7 @@ def main():
                      "candidates_per_s": cands / (lvl_ms * 1e-3)},
     }
     line["instantiation"] = bench_instantiation(P, inp, res)
+    line["reconfiguration"] = bench_reconfiguration(P, inp, res)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(inp)
     print(json.dumps(line))

@@ -8,7 +8,8 @@
  * n0, n0+1, ..., n_hi of the node specification (Section 4.1.1).
  *
  * One step loses `burst` nodes and then repairs every affected pipeline, in list order:
- *   - draw r selects node r mod (nodes left), nodes counted pipeline after pipeline in list order;
+ *   - draw r selects node floor(r * (nodes left) / 2^32), nodes counted pipeline after pipeline in
+ *     list order;
  *   - if fewer than (f+1) n0 nodes are left after the losses, training stops for good (Section 5)
  *     and the step repairs nothing;
  *   - a pipeline that still has at least n0 nodes is reinstantiated from the template of its new

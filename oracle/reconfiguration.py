@@ -7,8 +7,8 @@ n0, n0+1, ..., n_hi (Section 4.1.1).  One *step* loses `burst` nodes, then repai
 affected pipeline.  Plain Python, one trajectory at a time, in the paper's order of steps.
 
 Where the paper leaves a choice open, this build reads it as follows:
-  * which node fails: the caller's draw r (a 32-bit number) selects node r mod (nodes left),
-    nodes counted pipeline after pipeline in list order;
+  * which node fails: the caller's draw r (a 32-bit number) selects node
+    floor(r * (nodes left) / 2^32), nodes counted pipeline after pipeline in list order;
   * training stops for good once fewer than (f+1) n0 nodes are left (Section 5, last sentence
     of its introduction); the step that gets there repairs nothing;
   * affected pipelines are repaired in list order;
@@ -51,9 +51,10 @@ class Trajectory:
 
 
 def fail_node(sizes: List[Optional[int]], r: int) -> int:
-    """Removes node r mod (nodes left) and returns the list position of its pipeline."""
+    """Removes node floor(r * nodes left / 2^32) and returns the list position of its pipeline."""
     total = sum(s for s in sizes if s is not None)
-    r %= total
+    assert 0 <= r < 1 << 32
+    r = (r * total) >> 32
     for i, s in enumerate(sizes):
         if s is None:
             continue

@@ -43,7 +43,7 @@ def compare(P, sizes0, n0, n_hi, f, draws, sample=None):
 
 def test_the_three_cases_of_the_reinstantiation_figure(P):
     for sizes0, which, want in [([4, 2], 0, [3, 2]), ([2, 3, 2], 0, [2, 2, 2]), ([2, 2, 2], 1, [0, 3, 2])]:
-        draws = np.full((1, 1, 1), sum(sizes0[:which]), dtype=np.uint32)
+        draws = np.full((1, 1, 1), -(-(sum(sizes0[:which]) << 32) // sum(sizes0)), dtype=np.uint32)
         _, final, _ = compare(P, sizes0, 2, 4, 1, draws)
         assert final[:, 0].tolist() == want
 

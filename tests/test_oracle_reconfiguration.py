@@ -8,9 +8,14 @@ import inputs
 from oracle import reconfiguration as R
 
 
+def draw_for(node, total):
+    """The smallest draw that selects `node` out of `total` nodes."""
+    return -(-(node << 32) // total)
+
+
 def one_failure_in(sizes, which):
-    """The draw that makes the first node of pipeline `which` fail."""
-    return sum(sizes[:which])
+    """A draw that makes the first node of pipeline `which` fail."""
+    return draw_for(sum(sizes[:which]), sum(sizes))
 
 
 def test_the_three_cases_of_the_reinstantiation_figure():
@@ -29,15 +34,16 @@ def test_the_three_cases_of_the_reinstantiation_figure():
 
 
 def test_node_selection_counts_nodes_pipeline_after_pipeline():
-    for r, want in [(0, [2, 3, 4]), (2, [2, 3, 4]), (3, [3, 2, 4]), (5, [3, 2, 4]), (6, [3, 3, 3]), (9, [3, 3, 3]),
-                    (10, [2, 3, 4]), (2**32 - 1, None)]:
+    """Ten nodes in pipelines of 3, 3 and 4: node = floor(draw * 10 / 2^32); draws worked by hand
+    (1288490189 = ceil(3 * 2^32 / 10), 2576980378 = ceil(6 * 2^32 / 10))."""
+    for r, want in [(0, [2, 3, 4]), (1288490188, [2, 3, 4]), (1288490189, [3, 2, 4]), (1 << 31, [3, 2, 4]),
+                    (2576980377, [3, 2, 4]), (2576980378, [3, 3, 3]), (2**32 - 1, [3, 3, 3])]:
         sizes = [3, 3, 4]
         i = R.fail_node(sizes, r)
-        if want is not None:
-            assert sizes == want, (r, sizes)
-        assert sum(sizes) == 9 and sizes[i] in (2, 3)
+        assert sizes == want and sizes[i] == want[i], (r, sizes)
     sizes = [3, None, 4]
-    assert R.fail_node(sizes, 3) == 2 and sizes == [3, None, 3]
+    assert R.fail_node(sizes, draw_for(3, 7)) == 2 and sizes == [3, None, 3]
+    assert R.fail_node(sizes, draw_for(3, 6) - 1) == 0 and sizes == [2, None, 3]
 
 
 def test_training_survives_exactly_down_to_f_plus_one_smallest_pipelines():
@@ -81,7 +87,7 @@ def test_merging_happens_only_when_nobody_can_lend_and_lands_below_twice_n0():
         sizes0 = [n0] * c                      # nobody can lend
         k = int(rng.integers(1, n0))           # lose k nodes of one pipeline in one burst
         which = int(rng.integers(0, c))
-        draws = [[one_failure_in(sizes0, which)] * k]
+        draws = [[draw_for(which * n0, c * n0 - b) for b in range(k)]]
         tr = R.simulate(sizes0, n0, 2 * n0 - 1, f, draws)
         assert tr.steps[0].merges == 1 and tr.steps[0].borrowed == 0
         assert tr.sizes[which] == 2 * n0 - k and sorted(tr.sizes)[0] == 0 and tr.violations == 0
@@ -121,11 +127,11 @@ def test_the_choices_the_paper_leaves_open_follow_the_stated_reading():
     tr = R.simulate([3, 3, 4], 3, 5, 0, [[0, 0]])
     assert tr.sizes == [5, 0, 3] and (tr.steps[0].borrowed, tr.steps[0].merges) == (1, 1)
     # [1, 3, 2] after the burst: the merge partner is the smallest other pipeline, not the first
-    tr = R.simulate([3, 3, 3], 3, 5, 0, [[0, 0, 6]])
+    tr = R.simulate([3, 3, 3], 3, 5, 0, [[0, 0, draw_for(6, 7)]])
     assert tr.sizes == [3, 3, 0] and (tr.steps[0].borrowed, tr.steps[0].merges) == (0, 1)
     # [2, 2, 2, 3] after the burst, f = 2: the first pipeline absorbs the second (4 nodes) and then
     # lends a node to the third: three pipelines of three nodes are left
-    tr = R.simulate([3, 3, 3, 3], 3, 5, 2, [[0, 3, 6]])
+    tr = R.simulate([3, 3, 3, 3], 3, 5, 2, [[0, draw_for(3, 11), draw_for(6, 10)]])
     assert tr.sizes == [3, 0, 3, 3] and (tr.steps[0].borrowed, tr.steps[0].merges, tr.steps[0].alive) == (1, 1, 3)
     assert tr.violations == 0
     # fewer than (f+1) n0 nodes: training stops, nothing is repaired, later steps change nothing
