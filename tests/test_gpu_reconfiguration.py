@@ -86,6 +86,11 @@ def test_edge_cases(P):
     sim = P.FailureSimulator([1, 2, 3], 2, 3, 0, inputs.failure_draws(0, 2, 1, 5))
     st, summary, final, trace = sim.run()
     assert st == P.OOB_EINVAL and not summary["nodes"].any() and not final.any() and not trace.any()
+    # both violation flags: no template for a merged pipeline; fewer than f+1 pipelines
+    summary, final, _ = compare(P, [3, 3], 3, 4, 0, np.zeros((1, 1, 2), dtype=np.uint32))
+    assert summary["violations"].tolist() == [1, 1] and final.tolist() == [[5, 5], [0, 0]]
+    summary, _, _ = compare(P, [4, 4], 2, 4, 2, np.zeros((1, 1, 2), dtype=np.uint32))
+    assert summary["violations"].tolist() == [2, 2]
     # without trace and final sizes
     sim = P.FailureSimulator([2, 3, 4], 2, 4, 1, inputs.failure_draws(5, 6, 1, 300), trace=False)
     st, summary, final, trace = sim.run()

@@ -137,3 +137,18 @@ def test_the_choices_the_paper_leaves_open_follow_the_stated_reading():
     # fewer than (f+1) n0 nodes: training stops, nothing is repaired, later steps change nothing
     tr = R.simulate([2, 2], 2, 3, 1, [[0], [0]])
     assert tr.sizes == [1, 2] and tr.survived == 0 and [r.stop for r in tr.steps] == [1, 1]
+
+
+def test_counts_and_violation_flags_on_hand_cases():
+    # a pipeline that lands exactly on n0 is a plain reinstantiation
+    tr = R.simulate([3, 2], 2, 4, 0, [[0]])
+    assert tr.sizes == [2, 2] and (tr.steps[0].reinstantiated, tr.steps[0].borrowed, tr.steps[0].merges) == (1, 0, 0)
+    # two sizes only (3 and 4) although n0 - 1 = 2 would need more than two (Section 4.1.1): the merge
+    # of a 2-node rest with a 3-node pipeline has 5 nodes and no template; with a 5-node template it has
+    assert R.simulate([3, 3], 3, 4, 0, [[0]]).violations == 1
+    assert R.simulate([3, 3], 3, 4, 0, [[0]]).sizes == [5, 0]
+    assert R.simulate([3, 3], 3, 5, 0, [[0]]).violations == 0
+    # a start with fewer than f+1 pipelines is reported once a step has been repaired
+    tr = R.simulate([4, 4], 2, 4, 2, [[0]])
+    assert tr.sizes == [3, 4] and tr.violations == 2 and tr.survived == 1
+    assert R.simulate([4, 4], 2, 4, 1, [[0]]).violations == 0
