@@ -70,6 +70,30 @@ def test_random_specifications_every_trajectory(P):
         cases += 1
 
 
+def test_larger_specifications_every_trajectory(P):
+    """Node specifications of the size of the planner's workloads (n0 up to 16, f up to 8, dozens
+    of pipelines), a few hundred sequences each, to the end of training."""
+    rng = np.random.Generator(np.random.PCG64(11))
+    cases = 0
+    while cases < 12:
+        seed = int(rng.integers(0, 1 << 30))
+        n0, f = int(rng.integers(6, 17)), int(rng.integers(0, 9))
+        N = (f + 1) * n0 + int(rng.integers(n0, 12 * n0))
+        n_hi = N - f * n0
+        burst = int(rng.choice([1, 1, 3, 17]))
+        try:
+            sizes0 = inputs.starting_pipelines(seed, n0, n_hi, N, f).tolist()
+        except AssertionError:
+            continue
+        if len(sizes0) > 64:
+            continue
+        print("case", cases, len(sizes0), "pipelines", n0, n_hi, f, burst, flush=True)
+        draws = inputs.failure_draws(seed, (N - (f + 1) * n0) // burst + 2, burst, 200)
+        summary, _, _ = compare(P, sizes0, n0, n_hi, f, draws)
+        assert not summary["violations"].any() and (summary["stop"] == R.STOP_TOO_FEW_NODES).all()
+        cases += 1
+
+
 def test_edge_cases(P):
     # no steps at all: the starting state comes back
     st, summary, final, trace = P.FailureSimulator([3, 4], 3, 5, 0, np.zeros((0, 1, 5), dtype=np.uint32)).run()
