@@ -307,6 +307,20 @@ def test_plain_split_kernel(P, monkeypatch):
         planner.close()
 
 
+def test_xcd_chunked_task_order(P, monkeypatch):
+    """The other order of the workgroup tasks (block row by block row, each XCD walking one
+    contiguous stretch of the list) computes the same tables."""
+    monkeypatch.setenv("OOB_TUNE_XCD", "1")
+    for inp in (inputs.config(2), inputs.config(3),
+                inputs.random_small(3, 37, 3, 1, 5, 9, f=1, tight_mem=True),
+                inputs.random_small(5, 60, 2, 1, 6, 11, f=2),
+                inputs.random_small(4, 30, 3, 2, 30, 0, f=2)):
+        print("xcd", inp.name, inp.L, flush=True)
+        planner = P.Planner(inp.L, inp.n_max, inp.gpus_per_node)
+        full_check(P, planner, inp)
+        planner.close()
+
+
 def test_two_calls_same_answer(P):
     """Determinism: the same job twice on one handle gives identical tables."""
     inp = inputs.config(2)
