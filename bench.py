@@ -217,6 +217,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    from paper_2309_08125_amd import build as hip_build
+
+    hip_build.ensure_built()  # loads what is built; compiles only if there is no library
     if args.config == 5:
         return bench_batch(P, inputs.config(5), args)
     inp = inputs.config(args.config)

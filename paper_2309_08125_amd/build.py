@@ -35,5 +35,11 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """Builds only if no library is there (tests, smoke and bench call this; a changed source
+    needs an explicit build)."""
+    return LIB if os.path.exists(LIB) else build()
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

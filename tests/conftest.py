@@ -11,6 +11,10 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests load the library that is built; they compile it only if there is none
+    from paper_2309_08125_amd import build as hip_build
+
+    hip_build.ensure_built()
 
 
 def simple_input(fb, M=1, n_min=1, n_max=1, nb=4, cap=None, f=0, mem=None, bnd=None,
