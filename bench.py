@@ -152,7 +152,8 @@ def bench_batch(P, insts, args):
     resident in HBM; a step is the whole batch."""
     import torch
 
-    planner = P.Planner(max(i.L for i in insts), max(i.n_max for i in insts), max(i.gpus_per_node for i in insts))
+    planner = P.Planner(max(i.L for i in insts), max(i.n_max for i in insts), max(i.gpus_per_node for i in insts),
+                        lanes=args.lanes)
     profs = [P.DeviceProfile(i) for i in insts]
     outs = [planner.new_outputs(i) for i in insts]
     stream = torch.cuda.current_stream()
@@ -184,6 +185,7 @@ def bench_batch(P, insts, args):
         "scaling": "weak", "vs_baseline": None, "dtype": "f64 (exact integers < 2^52; int64 in and out)",
         "data": "synthetic",
         "config": {"workload": "config 5: 256 instances, L=24..128, templates n=1..32 x 8 GPUs, N_b=64",
+                   "lanes": args.lanes,
                    "states": states, "candidates": cands},
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12,
                      "unit": "T lane-op/s", "frac": achieved / PEAK_LANE_OPS, "traffic": None,
@@ -198,6 +200,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=4,
                     help="workload 1-4 (default: headline 4); 5 = the batch of 256 instances (one batched call per step)")
+    ap.add_argument("--lanes", type=int, default=4,
+                    help="--config 5 only: jobs of the batch in flight side by side (workspace for that many)")
     ap.add_argument("--paper-nb", action="store_true",
                     help="N_b = 4 S' per state (the paper's planning-time choice) instead of the configuration's N_b")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -96,7 +96,9 @@ int oob_plan_max_stages(int L, int n_max, int gpus_per_node, int microbatches);
 size_t oob_plan_workspace_size(int max_L, int max_nodes, int max_gpus_per_node);
 
 /* Creates a handle over caller-owned device memory (256-byte aligned, at least
- * oob_plan_workspace_size bytes, alive until destroy).  No device memory is allocated. */
+ * oob_plan_workspace_size bytes, alive until destroy).  No device memory is allocated.
+ * A workspace of k times that size (each share rounded up to 256 bytes; k <= 8) gives the handle
+ * k lanes: oob_plan_templates_batch then keeps up to k jobs in flight side by side. */
 int oob_plan_create(oob_plan **h, int max_L, int max_nodes, int max_gpus_per_node,
                     void *dev_workspace, size_t workspace_bytes);
 
@@ -113,8 +115,13 @@ int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L, int n_min
                        int gpus_per_node, int microbatches, int64_t mem_cap, int f,
                        oob_templates *out, void *stream);
 
-/* Independent planning jobs, one after the other on `stream`, sharing the handle's workspace.
- * All arrays are HOST arrays of length count (of structs / ints holding the per-job values). */
+/* Independent planning jobs.  With one lane (see oob_plan_create) they run one after the other
+ * on `stream`; with k lanes job i runs in lane i mod k, the lanes side by side on streams of the
+ * library that start after the work already enqueued on `stream` and that `stream` waits for
+ * before the call returns, so that the call still looks like work on `stream` to the caller.
+ * Every job needs output arrays of its own.
+ * All arrays are HOST arrays of length count (of structs / ints holding the per-job values).
+ * Returns the first error; jobs before it stay enqueued. */
 int oob_plan_templates_batch(oob_plan *h, int count, const oob_profile *profiles, const int *L,
                              const int *n_min, const int *n_max, const int *gpus_per_node,
                              const int *microbatches, const int64_t *mem_cap, const int *f,

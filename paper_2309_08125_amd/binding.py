@@ -213,15 +213,17 @@ class DeviceTemplates:
 
 
 class Planner:
-    """Owns a workspace tensor and a handle sized for the given maxima."""
+    """Owns a workspace tensor and a handle sized for the given maxima; `lanes` > 1 sizes the
+    workspace for that many jobs side by side in plan_batch."""
 
-    def __init__(self, max_L: int, max_nodes: int, max_gpus_per_node: int, device="cuda:0"):
+    def __init__(self, max_L: int, max_nodes: int, max_gpus_per_node: int, device="cuda:0", lanes: int = 1):
         import torch
 
         self.device = torch.device(device)
         nbytes = oob_plan_workspace_size(max_L, max_nodes, max_gpus_per_node)
         if nbytes == 0:
             raise ValueError("oob_plan_workspace_size: dimensions out of range")
+        nbytes = (nbytes + 255) // 256 * 256 * max(1, lanes)
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         rc, self.h = oob_plan_create(max_L, max_nodes, max_gpus_per_node,
                                      self.workspace.data_ptr(), nbytes)

@@ -32,6 +32,7 @@
 
 #include <mutex>
 #include <type_traits>
+#include <algorithm>
 #include <vector>
 #include <math.h>
 #include <new>
@@ -1050,17 +1051,31 @@ static hipEvent_t borrow_event() {
     return e;
 }
 
+// A lane is one job's worth of workspace plus the streams and events to run a job in it.  Lane 0
+// serves oob_plan_templates; oob_plan_templates_batch spreads its jobs over all lanes the caller's
+// workspace has room for, so that several (small) jobs fill the GPU side by side.
+constexpr int kMaxLanes = 8;
+struct Lane {
+    hipStream_t main = nullptr;       // lanes >= 1: borrowed; lane 0 runs on the caller's stream
+    hipStream_t aux = nullptr;        // second stream for the odd levels, borrowed (null: one stream)
+    std::vector<hipEvent_t> ev_level; // [S'] "level S' selected", borrowed; ev_level[0]: fork
+    hipEvent_t ev_join = nullptr;     // lanes >= 1: end of the lane's work in a batch, borrowed
+};
+
 struct oob_plan {
     int max_L, max_nodes, max_M;
     char *ws;
     size_t ws_bytes;
     Carve cv;
+    int lanes;        // workspace_bytes / bytes of one job, at most kMaxLanes
+    size_t lane_bytes;
+    Lane lane[kMaxLanes];
+    hipEvent_t ev_fork; // start of a batch, borrowed at the first batch
     Shape last;       // shape of the last call (for oob_plan_export_block)
+    int last_lane;    // and the lane it ran in
     bool have_last;
     hipEvent_t ev_begin, ev_end; // optional: recorded around the level launches
     bool timed;
-    hipStream_t aux;             // second stream for the odd levels, borrowed (null: everything on the caller's stream)
-    std::vector<hipEvent_t> ev_level; // [S'] "level S' selected", borrowed; ev_level[0]: fork
 };
 
 #define OOB_HIP_CHECK(expr)                                                                   \
@@ -1099,7 +1114,9 @@ extern "C" int oob_plan_create(oob_plan **h, int max_L, int max_nodes, int max_g
     p->max_L = max_L; p->max_nodes = max_nodes; p->max_M = max_gpus_per_node;
     p->ws = (char *)dev_workspace; p->ws_bytes = workspace_bytes; p->cv = cv; p->have_last = false;
     p->ev_begin = nullptr; p->ev_end = nullptr; p->timed = false;
-    p->aux = nullptr;
+    p->lane_bytes = align_up(cv.total);
+    p->lanes = (int)std::min<size_t>(kMaxLanes, std::max<size_t>(1, workspace_bytes / p->lane_bytes));
+    p->ev_fork = nullptr; p->last_lane = 0;
     *h = p;
     return OOB_OK;
 }
@@ -1110,31 +1127,37 @@ extern "C" int oob_plan_destroy(oob_plan *h) {
     { // the caller has waited for the handle's work: its stream and events go back to the pool
         AuxPool &p = aux_pool();
         std::lock_guard<std::mutex> lk(p.mu);
-        for (hipEvent_t e : h->ev_level) p.events.push_back(e);
-        if (h->aux) p.streams.push_back(h->aux);
+        for (Lane &ln : h->lane) {
+            for (hipEvent_t e : ln.ev_level) p.events.push_back(e);
+            if (ln.ev_join) p.events.push_back(ln.ev_join);
+            if (ln.aux) p.streams.push_back(ln.aux);
+            if (ln.main) p.streams.push_back(ln.main);
+        }
+        if (h->ev_fork) p.events.push_back(h->ev_fork);
     }
     delete h;
     return OOB_OK;
 }
 
-static Tables make_tables(const oob_plan *h, const Shape &sh, int *status) {
+static Tables make_tables(const oob_plan *h, int lane, const Shape &sh, int *status) {
     Tables t;
+    char *ws = h->ws + (size_t)lane * h->lane_bytes;
     t.sh = sh;
     t.NB = nblocks_of(sh.L);
     t.tab_recs = tri_blocks(t.NB) * 64;
-    t.lvl_tab = (long long *)(h->ws + h->cv.lvl_tab);
-    t.PT = (long long *)(h->ws + h->cv.PT);
-    t.PF = (int *)(h->ws + h->cv.PF);
-    t.PM = (long long *)(h->ws + h->cv.PM);
-    t.rec = (Rec *)(h->ws + h->cv.rec);
-    t.kstar = (int *)(h->ws + h->cv.kstar);
-    t.choice = (int *)(h->ws + h->cv.choice);
-    t.partT = (double *)(h->ws + h->cv.partT);
-    t.partKey = (unsigned long long *)(h->ws + h->cv.partT);
-    t.partK = (int *)(h->ws + h->cv.partK);
-    t.stack = (int *)(h->ws + h->cv.stack);
-    t.flags = (int *)(h->ws + h->cv.flags);
-    t.seg_tab = (int2 *)(h->ws + h->cv.seg_tab);
+    t.lvl_tab = (long long *)(ws + h->cv.lvl_tab);
+    t.PT = (long long *)(ws + h->cv.PT);
+    t.PF = (int *)(ws + h->cv.PF);
+    t.PM = (long long *)(ws + h->cv.PM);
+    t.rec = (Rec *)(ws + h->cv.rec);
+    t.kstar = (int *)(ws + h->cv.kstar);
+    t.choice = (int *)(ws + h->cv.choice);
+    t.partT = (double *)(ws + h->cv.partT);
+    t.partKey = (unsigned long long *)(ws + h->cv.partT);
+    t.partK = (int *)(ws + h->cv.partK);
+    t.stack = (int *)(ws + h->cv.stack);
+    t.flags = (int *)(ws + h->cv.flags);
+    t.seg_tab = (int2 *)(ws + h->cv.seg_tab);
     t.seg_stride = seg_count(sh.L, 2);
     t.status = status;
     return t;
@@ -1189,10 +1212,13 @@ static void launch_split(const Tables &t, int S, int fam, const SplitPlan &sp, i
                        NT, NAall);
 }
 
-extern "C" int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L, int n_min, int n_max,
-                                  int gpus_per_node, int microbatches, int64_t mem_cap, int f,
-                                  oob_templates *out, void *stream) {
+// One job in lane `ln` of the handle, enqueued on `st` (and on the lane's second stream when the
+// levels overlap).
+static int enqueue_job(oob_plan *h, int ln, bool want_overlap, const oob_profile *profile, int L, int n_min,
+                       int n_max, int gpus_per_node, int microbatches, int64_t mem_cap, int f,
+                       oob_templates *out, hipStream_t st) {
     if (!h || !profile || !out_ok(out)) return OOB_EINVAL;
+    Lane &lane = h->lane[ln];
     if (!profile->fwd_ns || !profile->bwd_ns || !profile->mem_bytes || !profile->boundary_ns) return OOB_EINVAL;
     if (L < 1 || n_min < 1 || n_min > n_max || gpus_per_node < 1 || microbatches < 0 || f < 0 || mem_cap <= 0)
         return OOB_EINVAL;
@@ -1221,8 +1247,7 @@ extern "C" int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L
                 SplitPlan sp;
                 if (plan_split(sh, S, fam, &sp) && sp.lds > kLdsLimit) return OOB_ECAPACITY;
             }
-    const Tables t = make_tables(h, sh, (int *)out->status);
-    hipStream_t st = (hipStream_t)stream;
+    const Tables t = make_tables(h, ln, sh, (int *)out->status);
     work_counts(sh, (long long *)&out->states, (long long *)&out->candidates);
 
     hipLaunchKernelGGL(k_setup, dim3(1), dim3(OOB_MAX_GPUS + 1), 0, st, t, *profile, force_plain);
@@ -1237,27 +1262,27 @@ extern "C" int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L
     // ones on the handle's second stream, each level waiting for the other stream's last select
     // only before its two outer splits (s = 1 and S'-1).  Two levels side by side fill the idle
     // tails of each other's launches.  Each stream has its own buffer of per-split minima.
-    static const int want_overlap = env_or("OOB_TUNE_OVERLAP", 1);
     bool overlap = want_overlap && !force_plain && sh.Smax >= 4;
-    if (overlap && !h->aux) h->aux = borrow_stream();
-    if (overlap && h->aux) {
-        while ((int)h->ev_level.size() < sh.Smax + 1) {
+    if (overlap && !lane.aux) lane.aux = borrow_stream();
+    if (overlap && lane.aux) {
+        while ((int)lane.ev_level.size() < sh.Smax + 1) {
             hipEvent_t e = borrow_event();
             if (!e) break;
-            h->ev_level.push_back(e);
+            lane.ev_level.push_back(e);
         }
     }
-    overlap = overlap && h->aux && (int)h->ev_level.size() >= sh.Smax + 1;
-    if (h->ev_begin) OOB_HIP_CHECK(hipEventRecord(h->ev_begin, st));
+    overlap = overlap && lane.aux && (int)lane.ev_level.size() >= sh.Smax + 1;
+    const bool timed = ln == 0 && h->ev_begin;
+    if (timed) OOB_HIP_CHECK(hipEventRecord(h->ev_begin, st));
     if (overlap) { // the second stream starts after everything enqueued so far
-        OOB_HIP_CHECK(hipEventRecord(h->ev_level[0], st));
-        OOB_HIP_CHECK(hipStreamWaitEvent(h->aux, h->ev_level[0], 0));
+        OOB_HIP_CHECK(hipEventRecord(lane.ev_level[0], st));
+        OOB_HIP_CHECK(hipStreamWaitEvent(lane.aux, lane.ev_level[0], 0));
     }
     for (int S = 2; S <= sh.Smax; ++S) {
         const int NAall = dhi_of(S, M, n_max) - dlo_of(S, M) + 1;
         if (NAall <= 0) continue;
         const int NT = tile_count(L, S);
-        hipStream_t sx = overlap && (S & 1) ? h->aux : st;
+        hipStream_t sx = overlap && (S & 1) ? lane.aux : st;
         Tables tl = t; // this level's buffer of per-split minima
         tl.partT = t.partT + (S & 1) * slot_stride;
         tl.partKey = t.partKey + (S & 1) * slot_stride;
@@ -1270,7 +1295,7 @@ extern "C" int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L
         if (overlap) {
             for (int fam = 0; fam < 2; ++fam) // inner splits: in order behind this stream's level S'-2
                 if (have[fam]) launch_split_key(tl, S, fam, kp[fam], NT, NAall, SplitRange{2, 1, S - 3}, sx);
-            if (S >= 3) OOB_HIP_CHECK(hipStreamWaitEvent(sx, h->ev_level[S - 1], 0));
+            if (S >= 3) OOB_HIP_CHECK(hipStreamWaitEvent(sx, lane.ev_level[S - 1], 0));
         }
         for (int fam = 0; fam < 2; ++fam) {
             if (!have[fam]) continue;
@@ -1281,19 +1306,28 @@ extern "C" int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L
             else launch_split<1>(tl, S, fam, sp[fam], NT, NAall, sx);
         }
         hipLaunchKernelGGL(k_select, dim3(NT, NAall), dim3(64), 0, sx, tl, S, NT, NAall);
-        if (overlap) OOB_HIP_CHECK(hipEventRecord(h->ev_level[S], sx));
+        if (overlap) OOB_HIP_CHECK(hipEventRecord(lane.ev_level[S], sx));
     }
     if (overlap) // whatever the second stream did last is awaited on the caller's stream
-        OOB_HIP_CHECK(hipStreamWaitEvent(st, h->ev_level[sh.Smax & 1 ? sh.Smax : sh.Smax - 1], 0));
-    if (h->ev_end) { OOB_HIP_CHECK(hipEventRecord(h->ev_end, st)); h->timed = true; }
+        OOB_HIP_CHECK(hipStreamWaitEvent(st, lane.ev_level[sh.Smax & 1 ? sh.Smax : sh.Smax - 1], 0));
+    if (timed) { OOB_HIP_CHECK(hipEventRecord(h->ev_end, st)); h->timed = true; }
     hipLaunchKernelGGL(k_pick, dim3((sh.count + 63) / 64), dim3(64), 0, st, t, *out);
     hipLaunchKernelGGL(k_backtrack, dim3((sh.count + 1 + 63) / 64), dim3(64), 0, st, t, *out);
     const int len = sh.count > f + 1 ? sh.count : f + 1;
     hipLaunchKernelGGL(k_coverage, dim3(1), dim3(64), 0, st, t, *out, len);
     OOB_HIP_CHECK(hipGetLastError());
     h->last = sh;
+    h->last_lane = ln;
     h->have_last = true;
     return OOB_OK;
+}
+
+extern "C" int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L, int n_min, int n_max,
+                                  int gpus_per_node, int microbatches, int64_t mem_cap, int f,
+                                  oob_templates *out, void *stream) {
+    static const int want_overlap = env_or("OOB_TUNE_OVERLAP", 1);
+    return enqueue_job(h, 0, want_overlap != 0, profile, L, n_min, n_max, gpus_per_node, microbatches, mem_cap, f,
+                       out, (hipStream_t)stream);
 }
 
 extern "C" int oob_plan_templates_batch(oob_plan *h, int count, const oob_profile *profiles, const int *L,
@@ -1303,12 +1337,37 @@ extern "C" int oob_plan_templates_batch(oob_plan *h, int count, const oob_profil
     if (!h || count < 0 || (count > 0 && (!profiles || !L || !n_min || !n_max || !gpus_per_node ||
                                            !microbatches || !mem_cap || !f || !outs)))
         return OOB_EINVAL;
-    for (int i = 0; i < count; ++i) {
-        const int rc = oob_plan_templates(h, &profiles[i], L[i], n_min[i], n_max[i], gpus_per_node[i],
-                                          microbatches[i], mem_cap[i], f[i], &outs[i], stream);
-        if (rc != OOB_OK) return rc;
+    static const int want_overlap = env_or("OOB_TUNE_OVERLAP", 1);
+    static const int lane_overlap = env_or("OOB_TUNE_BATCH_OVERLAP", 0);
+    static const int max_lanes = env_or("OOB_TUNE_BATCH_LANES", kMaxLanes);
+    hipStream_t st = (hipStream_t)stream;
+    // Lanes: job i runs in lane i mod K, the jobs of a lane one after the other on the lane's own
+    // stream, the lanes side by side.  Lane 0 is the caller's stream; the others start after what
+    // the caller has enqueued so far (fork event) and the caller's stream waits for them at the end.
+    int K = std::max(1, std::min(std::min(h->lanes, max_lanes), count));
+    if (K > 1 && !h->ev_fork) h->ev_fork = borrow_event();
+    if (K > 1 && !h->ev_fork) K = 1;
+    for (int ln = 1; ln < K; ++ln) {
+        Lane &lane = h->lane[ln];
+        if (!lane.main) lane.main = borrow_stream();
+        if (!lane.ev_join) lane.ev_join = borrow_event();
+        if (!lane.main || !lane.ev_join) { K = ln; break; }
     }
-    return OOB_OK;
+    if (K > 1) {
+        OOB_HIP_CHECK(hipEventRecord(h->ev_fork, st));
+        for (int ln = 1; ln < K; ++ln) OOB_HIP_CHECK(hipStreamWaitEvent(h->lane[ln].main, h->ev_fork, 0));
+    }
+    int rc = OOB_OK;
+    for (int i = 0; i < count && rc == OOB_OK; ++i) {
+        const int ln = i % K;
+        rc = enqueue_job(h, ln, K > 1 ? lane_overlap != 0 : want_overlap != 0, &profiles[i], L[i], n_min[i], n_max[i],
+                         gpus_per_node[i], microbatches[i], mem_cap[i], f[i], &outs[i], ln ? h->lane[ln].main : st);
+    }
+    for (int ln = 1; ln < K; ++ln) { // also after an error: the caller's stream covers all that was enqueued
+        OOB_HIP_CHECK(hipEventRecord(h->lane[ln].ev_join, h->lane[ln].main));
+        OOB_HIP_CHECK(hipStreamWaitEvent(st, h->lane[ln].ev_join, 0));
+    }
+    return rc;
 }
 
 extern "C" int oob_plan_level_timing(oob_plan *h, int enable) {
@@ -1357,7 +1416,7 @@ __global__ void k_export_flags(const int *flags, int *dst) {
 
 extern "C" int oob_plan_export_flags(oob_plan *h, int32_t *flags, void *stream) {
     if (!h || !h->have_last || !flags) return OOB_EINVAL;
-    hipLaunchKernelGGL(k_export_flags, dim3(1), dim3(64), 0, (hipStream_t)stream, (const int *)(h->ws + h->cv.flags),
+    hipLaunchKernelGGL(k_export_flags, dim3(1), dim3(64), 0, (hipStream_t)stream, (const int *)(h->ws + (size_t)h->last_lane * h->lane_bytes + h->cv.flags),
                        (int *)flags);
     OOB_HIP_CHECK(hipGetLastError());
     return OOB_OK;
@@ -1369,7 +1428,7 @@ extern "C" int oob_plan_export_block(oob_plan *h, int S, int delta, double *T, d
     const Shape &sh = h->last;
     if (S < 1 || S > sh.Smax) return OOB_EINVAL;
     if (delta < dlo_of(S, sh.M) || delta > dhi_of(S, sh.M, sh.n_max)) return OOB_EINVAL;
-    const Tables t = make_tables(h, sh, nullptr);
+    const Tables t = make_tables(h, h->last_lane, sh, nullptr);
     const int n = sh.L - S + 1;
     hipLaunchKernelGGL(k_export, dim3((n * n + 255) / 256), dim3(256), 0, (hipStream_t)stream, t, S, delta, T,
                        T1, tmax, T3, (int *)kstar, (int *)choice);

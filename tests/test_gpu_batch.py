@@ -91,6 +91,33 @@ def test_batch_small_and_middle_instances_against_oracle(P, instances):
     planner.close()
 
 
+def test_batch_on_several_lanes_against_oracle(P, instances):
+    """A workspace for three jobs: the jobs of a batch run three at a time side by side (job i in
+    lane i mod 3).  Ragged batch of eight, every template against the oracle, and every state of
+    the last job, whose tables are in lane 1."""
+    order = sorted(range(len(instances)), key=lambda i: instances[i].L)
+    batch = [instances[i] for i in order[:4] + order[60:62] + order[5:7]]
+    planner = P.Planner(max(b.L for b in batch), 32, 8, lanes=3)
+    for rep in range(2):  # the second batch reuses the lanes' streams and events
+        results = planner.plan_batch(batch)
+        for inp, got in zip(batch, results):
+            print(f"lanes: instance {inp.name} L={inp.L} f={inp.f}", flush=True)
+            o, want = oracle_expected(inp)
+            o.close()
+            PU.compare_templates(got, want, inp.n_max - inp.n_min + 1)
+    for S in (1, 2, 7):  # the last job ran in lane 7 mod 3 = 1: its tables are read from there
+        o, _ = oracle_expected(batch[-1])
+        for delta in range(o.D):
+            gb = planner.block(S, delta)
+            assert (gb is not None) == o.valid(S, delta)
+            if gb is not None:
+                PU.compare_block(gb, o.block(S, delta), S, batch[-1].L)
+        o.close()
+    # a single call after a batch runs in lane 0 again
+    full_check(P, planner, batch[0])
+    planner.close()
+
+
 @pytest.mark.timeout(900)
 def test_largest_instance_against_stored_oracle_results(P, instances):
     """L = 128, 32 nodes x 8 GPUs, N_b = 64: 3.5e10 candidates; oracle results stored by
@@ -107,11 +134,16 @@ def test_all_256_instances_properties(P, instances):
     import torch
 
     planner = P.Planner(128, 32, 8)
+    lanes4 = P.Planner(128, 32, 8, lanes=4)  # the same jobs four at a time: identical results
     t0 = time.time()
     states = cands = 0
     for lo in range(0, len(instances), 32):  # 8 calls of 32 jobs keep the result buffers small
         chunk = instances[lo: lo + 32]
         results = planner.plan_batch(chunk)
+        for r, r4 in zip(results, lanes4.plan_batch(chunk)):
+            assert r.keys() == r4.keys()
+            for k in r:
+                assert np.array_equal(r[k], r4[k]), k
         for inp, r in zip(chunk, results):
             check_properties(P, inp, r)
             states += r["states"]
@@ -122,3 +154,4 @@ def test_all_256_instances_properties(P, instances):
     print(f"256 instances: {states} states, {cands} candidates in {time.time() - t0:.1f} s "
           f"(GPU planning + host-side property checks)", flush=True)
     planner.close()
+    lanes4.close()
