@@ -93,15 +93,10 @@ def sweep(T: Sequence[int], Q: int) -> Tuple[Optional[int], Optional[List[int]],
             if N[i] < 2:
                 continue
             for j in range(x):       # ... for pipeline j: gain(mu) = c - 2 mu (T_j - T_i)
-                if j == i or T[i] > T[j]:
-                    continue
+                if T[i] >= T[j]:     # the gain of such an exchange does not grow with mu: N is optimal at
+                    continue         # mu, so it does not pay now and never will
                 c = T[i] * T[i] + T[j] * T[j] - 2 * T[i] * T[i] * N[i] + 2 * T[j] * T[j] * N[j]
-                if T[i] < T[j]:
-                    level = max(mu, Fraction(c, 2 * (T[j] - T[i])))
-                elif c < 0:          # equal T: pays at any level
-                    level = mu
-                else:
-                    continue
+                level = max(mu, Fraction(c, 2 * (T[j] - T[i])))
                 if nxt is None or level < nxt[0]:
                     nxt = (level, i, j)
         if nxt is None or nxt[0] > mu_end:
