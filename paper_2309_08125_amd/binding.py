@@ -23,6 +23,8 @@ SYMBOLS = ["oob_plan_max_stages", "oob_plan_workspace_size", "oob_plan_create",
            "oob_plan_level_timing", "oob_plan_last_level_ms", "oob_plan_export_flags", "oob_plan_valu_peak"]
 INST_SYMBOLS = ["oob_inst_workspace_size", "oob_inst_count", "oob_inst_enumerate"]
 RECONF_SYMBOLS = ["oob_reconf_simulate"]
+DIST_SYMBOLS = ["oob_dist_solve", "oob_dist_choose"]
+OOB_DIST_OK, OOB_DIST_TOO_FEW_MICROBATCHES, OOB_DIST_TOO_MANY_TEMPLATES, OOB_DIST_BAD_TIME, OOB_DIST_NO_PIPELINE = range(5)
 RECONF_ROWS = ("survived", "reinstantiated", "borrowed", "merges", "alive", "nodes", "violations", "stop")
 
 
@@ -90,6 +92,11 @@ def load():
                                           C.c_int, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_void_p]
         L.oob_reconf_simulate.restype = C.c_int
+        L.oob_dist_solve.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_int, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oob_dist_solve.restype = C.c_int
+        L.oob_dist_choose.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oob_dist_choose.restype = C.c_int
         _lib = L
     return _lib
 
@@ -166,6 +173,18 @@ def oob_reconf_simulate(sizes0_ptr, c0, n0, n_hi, f, draws_ptr, steps, burst, T,
     return load().oob_reconf_simulate(C.c_void_p(sizes0_ptr), c0, n0, n_hi, f, C.c_void_p(draws_ptr), steps, burst,
                                       T, C.c_void_p(trace_ptr), C.c_void_p(final_sizes_ptr),
                                       C.c_void_p(summary_ptr), C.c_void_p(status_ptr), C.c_void_p(stream_ptr))
+
+
+def oob_dist_solve(x_ptr, count, capacity, p, template_T_ptr, Q, vx_ptr, slowest_ptr, base_ptr, extra_ptr,
+                   status_ptr, stream_ptr) -> int:
+    return load().oob_dist_solve(C.c_void_p(x_ptr), count, capacity, p, C.c_void_p(template_T_ptr), Q,
+                                 C.c_void_p(vx_ptr), C.c_void_p(slowest_ptr), C.c_void_p(base_ptr),
+                                 C.c_void_p(extra_ptr), C.c_void_p(status_ptr), C.c_void_p(stream_ptr))
+
+
+def oob_dist_choose(offsets_ptr, segments, slowest_ptr, status_ptr, best_ptr, stream_ptr) -> int:
+    return load().oob_dist_choose(C.c_void_p(offsets_ptr), segments, C.c_void_p(slowest_ptr),
+                                  C.c_void_p(status_ptr), C.c_void_p(best_ptr), C.c_void_p(stream_ptr))
 
 
 # ---- convenience layer over torch device memory ------------------------------------------
@@ -422,6 +441,64 @@ class FailureSimulator:
         summary = {k: self.summary[i].cpu().numpy() for i, k in enumerate(RECONF_ROWS)}
         trace = self.trace.cpu().numpy().view("uint32") if self.trace is not None else None
         return int(self.status.item()), summary, self.final_sizes.cpu().numpy(), trace
+
+
+class Distributor:
+    """Device buffers for oob_dist_solve / oob_dist_choose over `count` plans of p templates."""
+
+    def __init__(self, x, count: int, template_T, Q: int, distribution: bool = True, device="cuda:0"):
+        """x: int16 device tensor [p, capacity] (uint16 bits, as Instantiator.enqueue fills it) or a host
+        array [count, p] of counts; template_T: p times per microbatch."""
+        import numpy as np
+        import torch
+
+        self.device = torch.device(device)
+        if not torch.is_tensor(x):
+            x = torch.from_numpy(np.ascontiguousarray(np.asarray(x, dtype=np.uint16).T).view(np.int16)).to(self.device)
+        self.x, self.count, self.Q = x, count, Q
+        self.p, self.capacity = int(x.shape[0]), int(x.shape[1])
+        self.template_T = torch.tensor([int(v) for v in template_T], dtype=torch.int64, device=self.device)
+        n = max(count, 1)
+        self.vx = torch.zeros((n, 2), dtype=torch.int64, device=self.device)
+        self.slowest = torch.zeros(n, dtype=torch.int64, device=self.device)
+        self.status = torch.full((n,), -99, dtype=torch.int32, device=self.device)
+        self.base = torch.zeros_like(x) if distribution else None
+        self.extra = torch.zeros_like(x) if distribution else None
+
+    def enqueue(self) -> None:
+        import torch
+
+        s = torch.cuda.current_stream(self.device)
+        check(oob_dist_solve(self.x.data_ptr(), self.count, self.capacity, self.p, self.template_T.data_ptr(), self.Q,
+                             self.vx.data_ptr(), self.slowest.data_ptr(),
+                             self.base.data_ptr() if self.base is not None else 0,
+                             self.extra.data_ptr() if self.extra is not None else 0,
+                             self.status.data_ptr(), s.cuda_stream), "oob_dist_solve")
+
+    def solve(self):
+        """(status [count], vx [count] as Python ints, slowest [count], base [count, p], extra [count, p])."""
+        import torch
+
+        self.enqueue()
+        torch.cuda.synchronize(self.device)
+        w = self.vx.cpu().numpy().view("uint64")[: self.count]
+        vx = [(int(hi) << 64) | int(lo) for lo, hi in w]
+        cut = lambda t: None if t is None else t.cpu().numpy().view("uint16")[:, : self.count].T.copy()
+        return (self.status.cpu().numpy()[: self.count], vx, self.slowest.cpu().numpy()[: self.count],
+                cut(self.base), cut(self.extra))
+
+    def choose(self, offsets):
+        """Index of the best plan of every group offsets[g] .. offsets[g+1]-1 (host array in, host array out)."""
+        import numpy as np
+        import torch
+
+        off = torch.from_numpy(np.asarray(offsets, dtype=np.int64)).to(self.device)
+        best = torch.full((len(offsets) - 1,), -99, dtype=torch.int64, device=self.device)
+        s = torch.cuda.current_stream(self.device)
+        check(oob_dist_choose(off.data_ptr(), len(offsets) - 1, self.slowest.data_ptr(), self.status.data_ptr(),
+                              best.data_ptr(), s.cuda_stream), "oob_dist_choose")
+        torch.cuda.synchronize(self.device)
+        return best.cpu().numpy()
 
 
 def template_stages(r: dict, i: int):

@@ -1,0 +1,246 @@
+// Batch distribution (Section 4.2.2, Eq. 6 of the Oobleck paper) and the choice of the plan by
+// throughput, for gfx950.  One lane solves one plan, exactly.
+//
+// Method.  For a fixed level mu,  min sum_i (N_i T_i - mu)^2  over sum N_i = Q, N_i >= 1  is a
+// separable convex allocation: rounding mu / T_i and then adding or removing microbatches one at
+// a time where that is cheapest gives its optimum, and as mu grows the optimum changes by single
+// exchanges of one microbatch from a faster to a slower pipeline, each at a level that is a ratio
+// of integers.  Every allocation on that path is feasible for Eq. 6, and at mu = the mean of an
+// optimum of Eq. 6 the path holds such an optimum (the sum of squares around the mean IS the
+// variance, and no allocation has a smaller one), so the smallest variance met on the path is
+// the minimum.  Any feasible allocation bounds the part of the path that matters: with V its
+// sum of squared deviations, no pipeline of an optimum is further than sqrt(V) from the
+// optimum's mean, hence that mean is within sqrt(V) of Q / sum_i (1 / T_i).
+//
+// Pipelines of one template have the same T and stay within one microbatch of each other, so the
+// state of a plan is one total per template in use (at most 16), kept in LDS with one column
+// per lane; a template's donor is one of its fullest pipelines, its receiver one of its
+// emptiest.  Products reach 2^124: all exact arithmetic is in 128-bit integers.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "oob_dist.h"
+#include "oob_plan.h"
+
+namespace oob_dist {
+
+typedef __int128 i128;
+constexpr int kLanes = 64; // plans per workgroup
+constexpr int kT = OOB_DIST_MAX_TEMPLATES_IN_PLAN;
+constexpr long long kMaxExchanges = 1ll << 24; // never reached (at most Q exchanges per template): every lane's loop ends
+
+struct Args {
+    const unsigned short *x;
+    long long count, capacity;
+    int p;
+    const long long *tT;
+    int Q;
+    unsigned long long *vx;
+    long long *slowest;
+    unsigned short *base, *extra;
+    int *status;
+};
+
+// One plan's state: column `lane` of arrays [kT][kLanes].
+struct Plan {
+    long long *T; // time per microbatch of template k of the plan
+    int *x, *M;   // pipelines of it; microbatches all of them hold together
+    int t, xs;    // templates in use; pipelines in all
+    __device__ long long Tk(int k) const { return T[k * kLanes]; }
+    __device__ int xk(int k) const { return x[k * kLanes]; }
+    __device__ int Mk(int k) const { return M[k * kLanes]; }
+    __device__ int fullest(int k) const { return (Mk(k) + xk(k) - 1) / xk(k); } // microbatches of a fullest pipeline
+    __device__ int emptiest(int k) const { return Mk(k) / xk(k); }
+};
+
+// The optimum of the fixed-level problem at the integer level mu >= 0.
+__device__ void allocate_at(const Plan &pl, long long mu, int Q) {
+    long long tot = 0;
+    for (int k = 0; k < pl.t; ++k) {
+        const long long T = pl.Tk(k);
+        long long n = (2 * mu + T) / (2 * T); // nearest integer to mu / T
+        if (n < 1) n = 1;
+        if (n > Q) n = Q;
+        pl.M[k * kLanes] = (int)(n * pl.xk(k));
+        tot += n * pl.xk(k);
+    }
+    while (tot > Q) { // remove where it costs least: f(n-1) - f(n) = T^2 (1 - 2n) + 2 T mu, n = a fullest pipeline's
+        int arg = -1;
+        i128 best = 0;
+        for (int k = 0; k < pl.t; ++k) {
+            const int n = pl.fullest(k);
+            if (n < 2) continue;
+            const i128 T = pl.Tk(k), c = T * T * (1 - 2 * n) + 2 * T * mu;
+            if (arg < 0 || c < best) { best = c; arg = k; }
+        }
+        if (arg < 0) break; // cannot happen: tot > Q >= pipelines, so some pipeline holds two
+        pl.M[arg * kLanes] -= 1;
+        --tot;
+    }
+    while (tot < Q) { // add where it costs least: f(n+1) - f(n) = T^2 (2n + 1) - 2 T mu, n = an emptiest pipeline's
+        int arg = 0;
+        i128 best = 0;
+        for (int k = 0; k < pl.t; ++k) {
+            const i128 T = pl.Tk(k), c = T * T * (2 * pl.emptiest(k) + 1) - 2 * T * mu;
+            if (k == 0 || c < best) { best = c; arg = k; }
+        }
+        pl.M[arg * kLanes] += 1;
+        ++tot;
+    }
+}
+
+// S1 = sum a_i, S2 = sum a_i^2 over the pipelines (a_i = N_i T_i).
+__device__ void sums(const Plan &pl, i128 *S1, i128 *S2) {
+    i128 s1 = 0, s2 = 0;
+    for (int k = 0; k < pl.t; ++k) {
+        const i128 T = pl.Tk(k);
+        const int n = pl.emptiest(k), e = pl.Mk(k) - n * pl.xk(k); // e pipelines hold n + 1, the others n
+        const i128 lo = T * n, hi = T * (n + 1);
+        s1 += lo * (pl.xk(k) - e) + hi * e;
+        s2 += lo * lo * (pl.xk(k) - e) + hi * hi * e;
+    }
+    *S1 = s1; *S2 = s2;
+}
+
+__global__ void __launch_bounds__(kLanes) k_dist_solve(Args a) {
+    __shared__ long long s_T[kT * kLanes];
+    __shared__ int s_x[kT * kLanes], s_M[kT * kLanes], s_best[kT * kLanes];
+    __shared__ unsigned short s_j[kT * kLanes];
+    const int lane = threadIdx.x;
+    const long long i = (long long)blockIdx.x * kLanes + lane;
+    if (i >= a.count) return;
+    Plan pl;
+    pl.T = s_T + lane; pl.x = s_x + lane; pl.M = s_M + lane;
+    int *bestM = s_best + lane;
+    unsigned short *tj = s_j + lane;
+
+    // the templates in use
+    int t = 0, xs = 0, st = OOB_DIST_OK;
+    for (int j = 0; j < a.p; ++j) {
+        const int c = a.x[(long long)j * a.capacity + i];
+        if (a.base) { a.base[(long long)j * a.capacity + i] = 0; a.extra[(long long)j * a.capacity + i] = 0; }
+        if (!c || st != OOB_DIST_OK) continue;
+        const long long T = a.tT[j];
+        if (t == kT) { st = OOB_DIST_TOO_MANY_TEMPLATES; continue; }
+        if (T < 1 || T > OOB_DIST_MAX_T) { st = OOB_DIST_BAD_TIME; continue; }
+        pl.T[t * kLanes] = T; pl.x[t * kLanes] = c; tj[t * kLanes] = (unsigned short)j;
+        xs += c;
+        ++t;
+    }
+    if (st == OOB_DIST_OK && t == 0) st = OOB_DIST_NO_PIPELINE;
+    if (st == OOB_DIST_OK && xs > a.Q) st = OOB_DIST_TOO_FEW_MICROBATCHES;
+    a.status[i] = st;
+    if (st != OOB_DIST_OK) {
+        a.vx[2 * i] = 0; a.vx[2 * i + 1] = 0; a.slowest[i] = 0;
+        return;
+    }
+    pl.t = t; pl.xs = xs;
+
+    // the stretch of levels that can hold the optimum's mean
+    double H = 0;
+    for (int k = 0; k < t; ++k) H += (double)pl.xk(k) / (double)pl.Tk(k);
+    const double L0 = (double)a.Q / H;
+    allocate_at(pl, (long long)(L0 + 0.5), a.Q);
+    i128 S1, S2;
+    sums(pl, &S1, &S2);
+    const double V = (double)((i128)xs * S2 - S1 * S1) / (double)xs; // sum of squared deviations of a feasible allocation
+    const double R = sqrt(V) * (1.0 + 1e-9) + L0 * 1e-9 + 2.0;       // widened for the rounding of these few operations
+    const long long mu_lo = L0 - R > 0 ? (long long)(L0 - R) : 0;
+    const i128 mu_hi = (i128)(long long)(L0 + R) + 1;
+
+    allocate_at(pl, mu_lo, a.Q);
+    sums(pl, &S1, &S2);
+    i128 best = (i128)xs * S2 - S1 * S1;
+    for (int k = 0; k < t; ++k) bestM[k * kLanes] = pl.Mk(k);
+    for (long long step = 0; step < kMaxExchanges; ++step) {
+        // the next exchange: a microbatch of a fullest pipeline of template d (n_d of them) goes to an emptiest
+        // pipeline of a slower template r (n_r): it pays from the level c / w on,
+        // c = T_d^2 + T_r^2 - 2 T_d^2 n_d + 2 T_r^2 n_r,  w = 2 (T_r - T_d) > 0
+        int bd = -1, br = -1;
+        i128 bc = 0, bw = 1;
+        for (int d = 0; d < t; ++d) {
+            const int nd = pl.fullest(d);
+            if (nd < 2) continue;
+            const i128 Td = pl.Tk(d), cd = Td * Td * (1 - 2 * nd);
+            for (int r = 0; r < t; ++r) {
+                const i128 Tr = pl.Tk(r);
+                if (Tr <= Td) continue;
+                const i128 c = cd + Tr * Tr * (1 + 2 * pl.emptiest(r)), w = 2 * (Tr - Td);
+                if (bd < 0 || c * bw < bc * w) { bc = c; bw = w; bd = d; br = r; }
+            }
+        }
+        if (bd < 0 || bc > bw * mu_hi) break; // past the stretch
+        const i128 Td = pl.Tk(bd), Tr = pl.Tk(br);
+        const int nd = pl.fullest(bd), nr = pl.emptiest(br);
+        S1 += Tr - Td;
+        S2 += Tr * Tr * (2 * nr + 1) - Td * Td * (2 * nd - 1);
+        pl.M[bd * kLanes] -= 1;
+        pl.M[br * kLanes] += 1;
+        const i128 v = (i128)xs * S2 - S1 * S1;
+        if (v < best) {
+            best = v;
+            for (int k = 0; k < t; ++k) bestM[k * kLanes] = pl.Mk(k);
+        }
+    }
+
+    long long slow = 0;
+    for (int k = 0; k < t; ++k) {
+        const int xk = pl.xk(k), m = bestM[k * kLanes], n = m / xk, e = m - n * xk;
+        const long long time = (long long)(n + (e > 0)) * pl.Tk(k);
+        slow = time > slow ? time : slow;
+        if (a.base) {
+            a.base[(long long)tj[k * kLanes] * a.capacity + i] = (unsigned short)n;
+            a.extra[(long long)tj[k * kLanes] * a.capacity + i] = (unsigned short)e;
+        }
+    }
+    a.vx[2 * i] = (unsigned long long)best;
+    a.vx[2 * i + 1] = (unsigned long long)(best >> 64);
+    a.slowest[i] = slow;
+}
+
+// One workgroup (one wave) per group of plans: the smallest `slowest` among the solved plans, the
+// first of equals.
+__global__ void __launch_bounds__(kLanes) k_dist_choose(const long long *offsets, const long long *slowest,
+                                                        const int *status, long long *best) {
+    __shared__ long long s_v[kLanes], s_i[kLanes];
+    const int lane = threadIdx.x;
+    const long long lo = offsets[blockIdx.x], hi = offsets[blockIdx.x + 1];
+    long long bv = 0, bi = -1;
+    for (long long i = lo + lane; i < hi; i += kLanes) // ascending: a lane keeps its first minimum
+        if (status[i] == OOB_DIST_OK && (bi < 0 || slowest[i] < bv)) { bv = slowest[i]; bi = i; }
+    s_v[lane] = bv; s_i[lane] = bi;
+    __syncthreads();
+    if (lane == 0) {
+        for (int l = 1; l < kLanes; ++l)
+            if (s_i[l] >= 0 && (bi < 0 || s_v[l] < bv || (s_v[l] == bv && s_i[l] < bi))) { bv = s_v[l]; bi = s_i[l]; }
+        best[blockIdx.x] = bi;
+    }
+}
+
+} // namespace oob_dist
+
+extern "C" int oob_dist_solve(const uint16_t *x, int64_t count, int64_t capacity, int p, const int64_t *template_T,
+                              int Q, uint64_t *vx, int64_t *slowest, uint16_t *base, uint16_t *extra,
+                              int32_t *status, void *stream) {
+    using namespace oob_dist;
+    if (!x || !template_T || !vx || !slowest || !status || (base == nullptr) != (extra == nullptr)) return OOB_EINVAL;
+    if (count < 0 || capacity < count || p < 1 || p > 65535 || Q < 1 || Q > OOB_DIST_MAX_Q) return OOB_EINVAL;
+    if (count == 0) return OOB_OK;
+    const long long blocks = (count + kLanes - 1) / kLanes;
+    if (blocks > 0x7fffffffll) return OOB_EINVAL;
+    Args a;
+    a.x = x; a.count = count; a.capacity = capacity; a.p = p; a.tT = (const long long *)template_T; a.Q = Q;
+    a.vx = (unsigned long long *)vx; a.slowest = (long long *)slowest; a.base = base; a.extra = extra; a.status = status;
+    hipLaunchKernelGGL(k_dist_solve, dim3((unsigned)blocks), dim3(kLanes), 0, (hipStream_t)stream, a);
+    return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
+}
+
+extern "C" int oob_dist_choose(const int64_t *offsets, int segments, const int64_t *slowest, const int32_t *status,
+                               int64_t *best, void *stream) {
+    using namespace oob_dist;
+    if (!offsets || !slowest || !status || !best || segments < 0) return OOB_EINVAL;
+    if (segments == 0) return OOB_OK;
+    hipLaunchKernelGGL(k_dist_choose, dim3((unsigned)segments), dim3(kLanes), 0, (hipStream_t)stream,
+                       (const long long *)offsets, (const long long *)slowest, status, (long long *)best);
+    return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
+}

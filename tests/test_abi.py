@@ -30,7 +30,10 @@ def test_library_exports_every_declared_symbol():
     assert sorted(B.INST_SYMBOLS) == inst
     reconf = declared_symbols("oob_reconf.h", "oob_reconf_")
     assert reconf == ["oob_reconf_simulate"] and hasattr(lib, reconf[0]) and sorted(B.RECONF_SYMBOLS) == reconf
-    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["oob_inst.h", "oob_plan.h", "oob_reconf.h"]
+    dist = declared_symbols("oob_dist.h", "oob_dist_")
+    assert dist == ["oob_dist_choose", "oob_dist_solve"] and all(hasattr(lib, n) for n in dist)
+    assert sorted(B.DIST_SYMBOLS) == dist
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["oob_dist.h", "oob_inst.h", "oob_plan.h", "oob_reconf.h"]
 
 
 def test_reconfiguration_entry_point_validates_arguments_without_touching_the_gpu():
