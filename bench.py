@@ -102,6 +102,63 @@ def bench_instantiation(P, inp, res, reps=20):
                          "kernel": "k_inst_unrank", "bytes_per_vector": 2 * p}}
 
 
+def bench_distribution(P, inp, res, Q=512, reps=3, oracle_sample=40):
+    """Section 4.2.2 on every plan the enumeration of this node specification lists: Eq. 6 solved
+    exactly per plan (time per microbatch of a template = its T1), then the best plan per cluster
+    size.  Timed with events on the stream the kernels are launched on; the oracle on a sample."""
+    import numpy as np
+    import torch
+    from oracle import batch_distribution
+
+    n0, n_hi, p, N = (int(v) for v in res["cover_hdr"][:4])
+    if p < 1:
+        return None
+    tT = [int(v) for v in res["T1"][n0 - inp.n_min: n0 - inp.n_min + p]]
+    if max(tT) > (1 << 35) or min(tT) < 1:
+        return None
+    inst = P.Instantiator(None, (inp.f + 1) * n0, N, inp.f, n0=n0, p=p)
+    off, st = inst.count()
+    total = int(off[-1])
+    if st != P.OOB_OK or total == 0:
+        return None
+    x = torch.empty((p, total), dtype=torch.int16, device="cuda")
+    inst.enqueue(x, total)
+    d = P.Distributor(x, total, tT, Q, distribution=True)
+    stream = torch.cuda.current_stream()
+    d.enqueue()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev[0].record(stream)
+    for _ in range(reps):
+        d.enqueue()
+    ev[1].record(stream)
+    torch.cuda.synchronize()
+    dt = ev[0].elapsed_time(ev[1]) / reps * 1e-3
+    status, vx, slow, base, extra = d.solve()
+    t0 = time.perf_counter()
+    best = d.choose(off)
+    t_choose = time.perf_counter() - t0
+    assert (status == P.OOB_DIST_OK).all(), "distribution"
+    X = x.cpu().numpy().view("uint16").T
+    rng = np.random.Generator(np.random.PCG64(1))
+    sample = rng.integers(0, total, size=oracle_sample).tolist()
+    t0 = time.time()
+    for i in sample:
+        assert batch_distribution.sweep(batch_distribution.pipelines_of(X[i].tolist(), tT), Q)[0] == vx[i], i
+    cpu = oracle_sample / (time.time() - t0)
+    # algorithmic HBM bytes per plan: its counts in, base and extra out (2 bytes each per template), 28 bytes of results
+    nbytes = total * (6.0 * p + 28)
+    return {"workload": f"all {total} plans of template sizes {n0}..{n_hi}, f={inp.f}, N'={(inp.f + 1) * n0}..{N}; "
+                        f"{Q} microbatches; time per microbatch = T1 of the template",
+            "value": total / dt, "unit": "plans/s", "ms": dt * 1e3, "choose_ms_with_sync": t_choose * 1e3,
+            "best_plan_for_all_nodes": X[int(best[-1])].nonzero()[0].tolist() if best[-1] >= 0 else None,
+            "roofline": {"bound": "hbm", "achieved": nbytes / dt / 1e9, "peak": 8000.0, "unit": "GB/s",
+                         "frac": nbytes / dt / 8e12, "traffic": None, "kernel": "k_dist_solve",
+                         "bytes_per_plan": 6 * p + 28},
+            "cpu_baseline": {"value": cpu, "unit": "plans/s", "cores": 1, "kind": "oracle",
+                             "sample": f"{oracle_sample} of the plans"}}
+
+
 def bench_reconfiguration(P, inp, res, trajectories=1 << 20, reps=5, oracle_sample=64):
     """Section 5.1 on the node specification the planner just produced: `trajectories` failure
     sequences, one node lost per step, from N nodes down to the end of training.  Timed with events
@@ -292,6 +349,7 @@ def main():
     }
     line["instantiation"] = bench_instantiation(P, inp, res)
     line["reconfiguration"] = bench_reconfiguration(P, inp, res)
+    line["distribution"] = bench_distribution(P, inp, res)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(inp)
     print(json.dumps(line))

@@ -31,6 +31,7 @@
 extern "C" {
 #endif
 
+#define OOB_DIST_MAX_TEMPLATES 1023       /* templates p                                   */
 #define OOB_DIST_MAX_TEMPLATES_IN_PLAN 16 /* templates with x_j > 0 in one plan            */
 #define OOB_DIST_MAX_Q 65535             /* microbatches per iteration                     */
 #define OOB_DIST_MAX_T ((int64_t)1 << 35) /* time per microbatch (about 34 s in ns): keeps every product below 2^127 */
@@ -45,7 +46,7 @@ extern "C" {
 /* Solves Eq. 6 for `count` plans.
  *   x           [p][capacity] uint16: x[j * capacity + i] = pipelines of template j in plan i
  *               (the layout oob_inst_enumerate writes), capacity >= count
- *   template_T  [p] time per microbatch of a pipeline of template j
+ *   template_T  [p] time per microbatch of a pipeline of template j, p <= OOB_DIST_MAX_TEMPLATES
  *   Q           microbatches per iteration, 1..OOB_DIST_MAX_Q
  *   vx          [count][2] out: x * sum_i (N_i T_i - mean)^2 = x sum a_i^2 - (sum a_i)^2 at the
  *               optimum (x = pipelines of the plan, a_i = N_i T_i), a 128-bit integer as

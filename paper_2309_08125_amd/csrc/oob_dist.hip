@@ -14,8 +14,9 @@
 //
 // Pipelines of one template have the same T and stay within one microbatch of each other, so the
 // state of a plan is one total per template in use (at most 16), kept in LDS with one column
-// per lane; a template's donor is one of its fullest pipelines, its receiver one of its
-// emptiest.  Products reach 2^124: all exact arithmetic is in 128-bit integers.
+// per lane (192 bytes a lane; the templates' times are one table per workgroup); a template's
+// donor is one of its fullest pipelines, its receiver one of its emptiest.  Products reach
+// 2^124: all exact arithmetic is in 128-bit integers.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -25,7 +26,7 @@
 namespace oob_dist {
 
 typedef __int128 i128;
-constexpr int kLanes = 64; // plans per workgroup
+constexpr int kLanes = 256; // plans per workgroup
 constexpr int kT = OOB_DIST_MAX_TEMPLATES_IN_PLAN;
 constexpr long long kMaxExchanges = 1ll << 24; // never reached (at most Q exchanges per template): every lane's loop ends
 
@@ -41,16 +42,24 @@ struct Args {
     int *status;
 };
 
-// One plan's state: column `lane` of arrays [kT][kLanes].
+// One plan's state: column `lane` of arrays [kT][kLanes].  Template k of the plan has x pipelines;
+// e of them hold n + 1 microbatches, the others n (0 <= e < x): no division in the loops.
 struct Plan {
-    long long *T; // time per microbatch of template k of the plan
-    int *x, *M;   // pipelines of it; microbatches all of them hold together
-    int t, xs;    // templates in use; pipelines in all
-    __device__ long long Tk(int k) const { return T[k * kLanes]; }
+    const long long *tT;           // the workgroup's copy of the templates' times per microbatch
+    unsigned short *j, *x, *n, *e; // template index; pipelines; see above
+    int t, xs;                     // templates in use; pipelines in all
+    __device__ long long Tk(int k) const { return tT[j[k * kLanes]]; }
     __device__ int xk(int k) const { return x[k * kLanes]; }
-    __device__ int Mk(int k) const { return M[k * kLanes]; }
-    __device__ int fullest(int k) const { return (Mk(k) + xk(k) - 1) / xk(k); } // microbatches of a fullest pipeline
-    __device__ int emptiest(int k) const { return Mk(k) / xk(k); }
+    __device__ int fullest(int k) const { return n[k * kLanes] + (e[k * kLanes] > 0); } // microbatches of a fullest pipeline
+    __device__ int emptiest(int k) const { return n[k * kLanes]; }
+    __device__ void take(int k) const { // one microbatch less for a fullest pipeline
+        if (e[k * kLanes] > 0) e[k * kLanes] -= 1;
+        else { n[k * kLanes] -= 1; e[k * kLanes] = (unsigned short)(xk(k) - 1); }
+    }
+    __device__ void give(int k) const { // one more for an emptiest pipeline
+        if (e[k * kLanes] + 1 == xk(k)) { n[k * kLanes] += 1; e[k * kLanes] = 0; }
+        else e[k * kLanes] += 1;
+    }
 };
 
 // The optimum of the fixed-level problem at the integer level mu >= 0.
@@ -61,7 +70,8 @@ __device__ void allocate_at(const Plan &pl, long long mu, int Q) {
         long long n = (2 * mu + T) / (2 * T); // nearest integer to mu / T
         if (n < 1) n = 1;
         if (n > Q) n = Q;
-        pl.M[k * kLanes] = (int)(n * pl.xk(k));
+        pl.n[k * kLanes] = (unsigned short)n;
+        pl.e[k * kLanes] = 0;
         tot += n * pl.xk(k);
     }
     while (tot > Q) { // remove where it costs least: f(n-1) - f(n) = T^2 (1 - 2n) + 2 T mu, n = a fullest pipeline's
@@ -70,21 +80,23 @@ __device__ void allocate_at(const Plan &pl, long long mu, int Q) {
         for (int k = 0; k < pl.t; ++k) {
             const int n = pl.fullest(k);
             if (n < 2) continue;
-            const i128 T = pl.Tk(k), c = T * T * (1 - 2 * n) + 2 * T * mu;
+            const long long T = pl.Tk(k);
+            const i128 c = (i128)T * T * (1 - 2 * n) + (i128)(2 * T) * mu;
             if (arg < 0 || c < best) { best = c; arg = k; }
         }
         if (arg < 0) break; // cannot happen: tot > Q >= pipelines, so some pipeline holds two
-        pl.M[arg * kLanes] -= 1;
+        pl.take(arg);
         --tot;
     }
     while (tot < Q) { // add where it costs least: f(n+1) - f(n) = T^2 (2n + 1) - 2 T mu, n = an emptiest pipeline's
         int arg = 0;
         i128 best = 0;
         for (int k = 0; k < pl.t; ++k) {
-            const i128 T = pl.Tk(k), c = T * T * (2 * pl.emptiest(k) + 1) - 2 * T * mu;
+            const long long T = pl.Tk(k);
+            const i128 c = (i128)T * T * (2 * pl.emptiest(k) + 1) - (i128)(2 * T) * mu;
             if (k == 0 || c < best) { best = c; arg = k; }
         }
-        pl.M[arg * kLanes] += 1;
+        pl.give(arg);
         ++tot;
     }
 }
@@ -94,7 +106,7 @@ __device__ void sums(const Plan &pl, i128 *S1, i128 *S2) {
     i128 s1 = 0, s2 = 0;
     for (int k = 0; k < pl.t; ++k) {
         const i128 T = pl.Tk(k);
-        const int n = pl.emptiest(k), e = pl.Mk(k) - n * pl.xk(k); // e pipelines hold n + 1, the others n
+        const int n = pl.n[k * kLanes], e = pl.e[k * kLanes]; // e pipelines hold n + 1, the others n
         const i128 lo = T * n, hi = T * (n + 1);
         s1 += lo * (pl.xk(k) - e) + hi * e;
         s2 += lo * lo * (pl.xk(k) - e) + hi * hi * e;
@@ -103,16 +115,17 @@ __device__ void sums(const Plan &pl, i128 *S1, i128 *S2) {
 }
 
 __global__ void __launch_bounds__(kLanes) k_dist_solve(Args a) {
-    __shared__ long long s_T[kT * kLanes];
-    __shared__ int s_x[kT * kLanes], s_M[kT * kLanes], s_best[kT * kLanes];
-    __shared__ unsigned short s_j[kT * kLanes];
+    HIP_DYNAMIC_SHARED(long long, s_tT) // [p]
+    __shared__ unsigned short s_x[kT * kLanes], s_j[kT * kLanes], s_n[kT * kLanes], s_e[kT * kLanes];
+    __shared__ unsigned short s_bn[kT * kLanes], s_be[kT * kLanes]; // the best allocation met so far
     const int lane = threadIdx.x;
+    for (int j = lane; j < a.p; j += kLanes) s_tT[j] = a.tT[j];
+    __syncthreads();
     const long long i = (long long)blockIdx.x * kLanes + lane;
     if (i >= a.count) return;
     Plan pl;
-    pl.T = s_T + lane; pl.x = s_x + lane; pl.M = s_M + lane;
-    int *bestM = s_best + lane;
-    unsigned short *tj = s_j + lane;
+    pl.tT = s_tT; pl.j = s_j + lane; pl.x = s_x + lane; pl.n = s_n + lane; pl.e = s_e + lane;
+    unsigned short *bn = s_bn + lane, *be = s_be + lane, *tj = s_j + lane;
 
     // the templates in use
     int t = 0, xs = 0, st = OOB_DIST_OK;
@@ -123,7 +136,7 @@ __global__ void __launch_bounds__(kLanes) k_dist_solve(Args a) {
         const long long T = a.tT[j];
         if (t == kT) { st = OOB_DIST_TOO_MANY_TEMPLATES; continue; }
         if (T < 1 || T > OOB_DIST_MAX_T) { st = OOB_DIST_BAD_TIME; continue; }
-        pl.T[t * kLanes] = T; pl.x[t * kLanes] = c; tj[t * kLanes] = (unsigned short)j;
+        pl.x[t * kLanes] = (unsigned short)c; tj[t * kLanes] = (unsigned short)j;
         xs += c;
         ++t;
     }
@@ -151,41 +164,44 @@ __global__ void __launch_bounds__(kLanes) k_dist_solve(Args a) {
     allocate_at(pl, mu_lo, a.Q);
     sums(pl, &S1, &S2);
     i128 best = (i128)xs * S2 - S1 * S1;
-    for (int k = 0; k < t; ++k) bestM[k * kLanes] = pl.Mk(k);
+    for (int k = 0; k < t; ++k) { bn[k * kLanes] = pl.n[k * kLanes]; be[k * kLanes] = pl.e[k * kLanes]; }
     for (long long step = 0; step < kMaxExchanges; ++step) {
         // the next exchange: a microbatch of a fullest pipeline of template d (n_d of them) goes to an emptiest
         // pipeline of a slower template r (n_r): it pays from the level c / w on,
         // c = T_d^2 + T_r^2 - 2 T_d^2 n_d + 2 T_r^2 n_r,  w = 2 (T_r - T_d) > 0
         int bd = -1, br = -1;
-        i128 bc = 0, bw = 1;
+        i128 bc = 0;
+        long long bw = 1; // w < 2^37: a 64-bit factor keeps the two products of a comparison cheap
         for (int d = 0; d < t; ++d) {
             const int nd = pl.fullest(d);
             if (nd < 2) continue;
-            const i128 Td = pl.Tk(d), cd = Td * Td * (1 - 2 * nd);
+            const long long Td = pl.Tk(d);
+            const i128 cd = (i128)Td * Td * (1 - 2 * nd);
             for (int r = 0; r < t; ++r) {
-                const i128 Tr = pl.Tk(r);
+                const long long Tr = pl.Tk(r);
                 if (Tr <= Td) continue;
-                const i128 c = cd + Tr * Tr * (1 + 2 * pl.emptiest(r)), w = 2 * (Tr - Td);
+                const i128 c = cd + (i128)Tr * Tr * (1 + 2 * pl.emptiest(r));
+                const long long w = 2 * (Tr - Td);
                 if (bd < 0 || c * bw < bc * w) { bc = c; bw = w; bd = d; br = r; }
             }
         }
         if (bd < 0 || bc > bw * mu_hi) break; // past the stretch
-        const i128 Td = pl.Tk(bd), Tr = pl.Tk(br);
+        const long long Td = pl.Tk(bd), Tr = pl.Tk(br);
         const int nd = pl.fullest(bd), nr = pl.emptiest(br);
         S1 += Tr - Td;
-        S2 += Tr * Tr * (2 * nr + 1) - Td * Td * (2 * nd - 1);
-        pl.M[bd * kLanes] -= 1;
-        pl.M[br * kLanes] += 1;
+        S2 += (i128)Tr * Tr * (2 * nr + 1) - (i128)Td * Td * (2 * nd - 1);
+        pl.take(bd);
+        pl.give(br);
         const i128 v = (i128)xs * S2 - S1 * S1;
         if (v < best) {
             best = v;
-            for (int k = 0; k < t; ++k) bestM[k * kLanes] = pl.Mk(k);
+            for (int k = 0; k < t; ++k) { bn[k * kLanes] = pl.n[k * kLanes]; be[k * kLanes] = pl.e[k * kLanes]; }
         }
     }
 
     long long slow = 0;
     for (int k = 0; k < t; ++k) {
-        const int xk = pl.xk(k), m = bestM[k * kLanes], n = m / xk, e = m - n * xk;
+        const int n = bn[k * kLanes], e = be[k * kLanes];
         const long long time = (long long)(n + (e > 0)) * pl.Tk(k);
         slow = time > slow ? time : slow;
         if (a.base) {
@@ -200,18 +216,19 @@ __global__ void __launch_bounds__(kLanes) k_dist_solve(Args a) {
 
 // One workgroup (one wave) per group of plans: the smallest `slowest` among the solved plans, the
 // first of equals.
-__global__ void __launch_bounds__(kLanes) k_dist_choose(const long long *offsets, const long long *slowest,
+constexpr int kChooseLanes = 64;
+__global__ void __launch_bounds__(kChooseLanes) k_dist_choose(const long long *offsets, const long long *slowest,
                                                         const int *status, long long *best) {
-    __shared__ long long s_v[kLanes], s_i[kLanes];
+    __shared__ long long s_v[kChooseLanes], s_i[kChooseLanes];
     const int lane = threadIdx.x;
     const long long lo = offsets[blockIdx.x], hi = offsets[blockIdx.x + 1];
     long long bv = 0, bi = -1;
-    for (long long i = lo + lane; i < hi; i += kLanes) // ascending: a lane keeps its first minimum
+    for (long long i = lo + lane; i < hi; i += kChooseLanes) // ascending: a lane keeps its first minimum
         if (status[i] == OOB_DIST_OK && (bi < 0 || slowest[i] < bv)) { bv = slowest[i]; bi = i; }
     s_v[lane] = bv; s_i[lane] = bi;
     __syncthreads();
     if (lane == 0) {
-        for (int l = 1; l < kLanes; ++l)
+        for (int l = 1; l < kChooseLanes; ++l)
             if (s_i[l] >= 0 && (bi < 0 || s_v[l] < bv || (s_v[l] == bv && s_i[l] < bi))) { bv = s_v[l]; bi = s_i[l]; }
         best[blockIdx.x] = bi;
     }
@@ -224,14 +241,14 @@ extern "C" int oob_dist_solve(const uint16_t *x, int64_t count, int64_t capacity
                               int32_t *status, void *stream) {
     using namespace oob_dist;
     if (!x || !template_T || !vx || !slowest || !status || (base == nullptr) != (extra == nullptr)) return OOB_EINVAL;
-    if (count < 0 || capacity < count || p < 1 || p > 65535 || Q < 1 || Q > OOB_DIST_MAX_Q) return OOB_EINVAL;
+    if (count < 0 || capacity < count || p < 1 || p > OOB_DIST_MAX_TEMPLATES || Q < 1 || Q > OOB_DIST_MAX_Q) return OOB_EINVAL;
     if (count == 0) return OOB_OK;
     const long long blocks = (count + kLanes - 1) / kLanes;
     if (blocks > 0x7fffffffll) return OOB_EINVAL;
     Args a;
     a.x = x; a.count = count; a.capacity = capacity; a.p = p; a.tT = (const long long *)template_T; a.Q = Q;
     a.vx = (unsigned long long *)vx; a.slowest = (long long *)slowest; a.base = base; a.extra = extra; a.status = status;
-    hipLaunchKernelGGL(k_dist_solve, dim3((unsigned)blocks), dim3(kLanes), 0, (hipStream_t)stream, a);
+    hipLaunchKernelGGL(k_dist_solve, dim3((unsigned)blocks), dim3(kLanes), (size_t)p * sizeof(long long), (hipStream_t)stream, a);
     return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
 }
 
@@ -240,7 +257,7 @@ extern "C" int oob_dist_choose(const int64_t *offsets, int segments, const int64
     using namespace oob_dist;
     if (!offsets || !slowest || !status || !best || segments < 0) return OOB_EINVAL;
     if (segments == 0) return OOB_OK;
-    hipLaunchKernelGGL(k_dist_choose, dim3((unsigned)segments), dim3(kLanes), 0, (hipStream_t)stream,
+    hipLaunchKernelGGL(k_dist_choose, dim3((unsigned)segments), dim3(kChooseLanes), 0, (hipStream_t)stream,
                        (const long long *)offsets, (const long long *)slowest, status, (long long *)best);
     return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
 }
