@@ -73,6 +73,22 @@ def test_instantiation_entry_points_validate_arguments_without_touching_the_gpu(
     assert rc == P.OOB_EINVAL                        # capacity > 0 without an output array
 
 
+def test_distribution_entry_points_validate_arguments_without_touching_the_gpu():
+    fake = 0x10000  # never dereferenced: every call below fails its host-side checks or has nothing to do
+    solve = lambda **kw: P.oob_dist_solve(kw.get("x", fake), kw.get("count", 1), kw.get("capacity", 1), kw.get("p", 1),
+                                          kw.get("tT", fake), kw.get("Q", 1), kw.get("vx", fake), kw.get("slowest", fake),
+                                          kw.get("base", 0), kw.get("extra", 0), kw.get("status", fake), 0)
+    for bad in (dict(x=0), dict(tT=0), dict(vx=0), dict(slowest=0), dict(status=0), dict(count=-1),
+                dict(count=2, capacity=1), dict(p=0), dict(p=1024), dict(Q=0), dict(Q=65536),
+                dict(base=fake), dict(extra=fake)):
+        assert solve(**bad) == P.OOB_EINVAL, bad
+    assert solve(count=0, capacity=0) == P.OOB_OK
+    assert P.oob_dist_choose(0, 1, fake, fake, fake, 0) == P.OOB_EINVAL
+    assert P.oob_dist_choose(fake, -1, fake, fake, fake, 0) == P.OOB_EINVAL
+    assert P.oob_dist_choose(fake, 1, fake, fake, 0, 0) == P.OOB_EINVAL
+    assert P.oob_dist_choose(fake, 0, fake, fake, fake, 0) == P.OOB_OK
+
+
 def test_max_stages_and_workspace_size():
     assert P.oob_plan_max_stages(98, 64, 8, 128) == 98
     assert P.oob_plan_max_stages(12, 4, 1, 8) == 4
