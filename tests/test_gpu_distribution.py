@@ -99,6 +99,19 @@ def test_realistic_plans_against_the_parametric_oracle(P):
         compare(P, vecs, tT, Q, exhaustive=False)
 
 
+def test_templates_of_nearly_equal_time(P):
+    """Times that differ by a few ns in 10^10: the levels of the exchanges then cancel to a small
+    part of their terms: only exact integer comparisons order them correctly."""
+    rng = random.Random(9)
+    for case in range(30):
+        base = rng.randint(10**9, 3 * 10**10)
+        tT = sorted(set(base + rng.randint(0, 6) for _ in range(rng.randint(2, 8))))
+        Q = rng.choice([20, 64, 200])
+        vecs = [[rng.choice([0, 1, 1, 2]) for _ in range(len(tT))] for _ in range(40)]
+        vecs = [v for v in vecs if 0 < sum(v) <= Q]
+        compare(P, vecs, tT, Q, exhaustive=False)
+
+
 def test_status_codes_and_limits(P):
     tT = list(range(100, 120))
     x17 = [1] * 17 + [0] * 3          # seventeen templates in one plan
