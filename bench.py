@@ -6,6 +6,10 @@ extraction, coverage) on the GPT-175B-shaped workload (98 profile entries, templ
 8..64 nodes x 8 GPUs, 128 microbatches) with the profile already resident in HBM.
 Prints ONE JSON line.  Metric: dynamic-program states per second (structural count of valid
 states, 3 724 666 per step for the headline workload) and wall-ms per full template set.
+The same line carries, as objects of their own and outside the timed steps, the later stages
+on the node specification the planner produced: `instantiation` (Section 4.2.1), `distribution`
+(Section 4.2.2) and `reconfiguration` (Section 5.1), each with its own roofline.
+`--config 5` times the batch of 256 independent jobs instead.
 """
 import argparse
 import dataclasses
