@@ -6,7 +6,7 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "oob_oracle.c")
-SRCS = [SRC, os.path.join(HERE, "oob_inst_oracle.c")]
+SRCS = [SRC, os.path.join(HERE, "oob_inst_oracle.c"), os.path.join(HERE, "oob_exact_oracle.c")]
 LIB = os.path.join(HERE, "liboob_oracle.so")
 
 
