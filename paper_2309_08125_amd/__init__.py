@@ -4,6 +4,7 @@ from .binding import (  # noqa: F401
     DeviceProfile, DeviceTemplates, Planner, load, oob_plan_create, oob_plan_destroy,
     oob_plan_max_stages, oob_plan_templates, oob_plan_templates_batch, oob_plan_workspace_size,
     template_stages,
+    EXACT_SYMBOLS, ExactMinimum, oob_exact_minimum, oob_exact_workspace_size,
     DIST_SYMBOLS, Distributor, oob_dist_choose, oob_dist_solve,
     OOB_DIST_OK, OOB_DIST_TOO_FEW_MICROBATCHES, OOB_DIST_TOO_MANY_TEMPLATES, OOB_DIST_BAD_TIME, OOB_DIST_NO_PIPELINE,
     RECONF_ROWS, RECONF_SYMBOLS, FailureSimulator, oob_reconf_simulate,

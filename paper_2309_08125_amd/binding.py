@@ -24,6 +24,7 @@ SYMBOLS = ["oob_plan_max_stages", "oob_plan_workspace_size", "oob_plan_create",
 INST_SYMBOLS = ["oob_inst_workspace_size", "oob_inst_count", "oob_inst_enumerate"]
 RECONF_SYMBOLS = ["oob_reconf_simulate"]
 DIST_SYMBOLS = ["oob_dist_solve", "oob_dist_choose"]
+EXACT_SYMBOLS = ["oob_exact_workspace_size", "oob_exact_minimum"]
 OOB_DIST_OK, OOB_DIST_TOO_FEW_MICROBATCHES, OOB_DIST_TOO_MANY_TEMPLATES, OOB_DIST_BAD_TIME, OOB_DIST_NO_PIPELINE = range(5)
 RECONF_ROWS = ("survived", "reinstantiated", "borrowed", "merges", "alive", "nodes", "violations", "stop")
 
@@ -97,6 +98,11 @@ def load():
         L.oob_dist_solve.restype = C.c_int
         L.oob_dist_choose.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.oob_dist_choose.restype = C.c_int
+        L.oob_exact_workspace_size.argtypes = [C.c_int] * 3
+        L.oob_exact_workspace_size.restype = C.c_size_t
+        L.oob_exact_minimum.argtypes = [C.POINTER(oob_profile), C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64,
+                                        C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oob_exact_minimum.restype = C.c_int
         _lib = L
     return _lib
 
@@ -185,6 +191,18 @@ def oob_dist_solve(x_ptr, count, capacity, p, template_T_ptr, Q, vx_ptr, slowest
 def oob_dist_choose(offsets_ptr, segments, slowest_ptr, status_ptr, best_ptr, stream_ptr) -> int:
     return load().oob_dist_choose(C.c_void_p(offsets_ptr), segments, C.c_void_p(slowest_ptr),
                                   C.c_void_p(status_ptr), C.c_void_p(best_ptr), C.c_void_p(stream_ptr))
+
+
+def oob_exact_workspace_size(L, n_max, gpus_per_node) -> int:
+    return load().oob_exact_workspace_size(L, n_max, gpus_per_node)
+
+
+def oob_exact_minimum(profile, L, n_min, n_max, gpus_per_node, microbatches, mem_cap, dev_workspace_ptr,
+                      workspace_bytes, best_ptr, status_ptr, stream_ptr) -> int:
+    return load().oob_exact_minimum(C.byref(profile) if profile is not None else None, L, n_min, n_max,
+                                    gpus_per_node, microbatches, mem_cap, C.c_void_p(dev_workspace_ptr),
+                                    workspace_bytes, C.c_void_p(best_ptr), C.c_void_p(status_ptr),
+                                    C.c_void_p(stream_ptr))
 
 
 # ---- convenience layer over torch device memory ------------------------------------------
@@ -441,6 +459,40 @@ class FailureSimulator:
         summary = {k: self.summary[i].cpu().numpy() for i, k in enumerate(RECONF_ROWS)}
         trace = self.trace.cpu().numpy().view("uint32") if self.trace is not None else None
         return int(self.status.item()), summary, self.final_sizes.cpu().numpy(), trace
+
+
+class ExactMinimum:
+    """Device buffers for oob_exact_minimum of one planning job."""
+
+    def __init__(self, inp, device="cuda:0"):
+        import torch
+
+        self.device = torch.device(device)
+        self.inp = inp
+        self.prof = DeviceProfile(inp, self.device)
+        nbytes = oob_exact_workspace_size(inp.L, inp.n_max, inp.gpus_per_node)
+        if nbytes == 0:
+            raise ValueError("oob_exact_workspace_size: dimensions out of range")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.best = torch.full((inp.n_max - inp.n_min + 1,), -99, dtype=torch.int64, device=self.device)
+        self.status = torch.full((1,), -99, dtype=torch.int32, device=self.device)
+
+    def enqueue(self) -> int:
+        import torch
+
+        i = self.inp
+        s = torch.cuda.current_stream(self.device)
+        return oob_exact_minimum(self.prof.c, i.L, i.n_min, i.n_max, i.gpus_per_node, i.microbatches, i.mem_cap,
+                                 self.workspace.data_ptr(), self.workspace.numel(), self.best.data_ptr(),
+                                 self.status.data_ptr(), s.cuda_stream)
+
+    def run(self):
+        """(status, exact minimum per template as a list, None where no pipeline exists)."""
+        import torch
+
+        check(self.enqueue(), "oob_exact_minimum")
+        torch.cuda.synchronize(self.device)
+        return int(self.status.item()), [None if v < 0 else int(v) for v in self.best.cpu().numpy()]
 
 
 class Distributor:

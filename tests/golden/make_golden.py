@@ -8,6 +8,7 @@ stage-count level over the canonical form of every state record of that level
     python tests/golden/make_golden.py cfg4
     python tests/golden/make_golden.py cfg4_paper_nb     (configuration 4 with N_b = 4 S' per state)
     python tests/golden/make_golden.py cfg5 <instance> [<instance> ...]
+    python tests/golden/make_golden.py cfg4_exact        (exact minimum of the cost per template, about a minute)
 """
 import hashlib
 import json
@@ -64,6 +65,13 @@ def main():
         for idx in map(int, sys.argv[2:]):
             json.dump(expected(insts[idx]),
                       open(os.path.join(HERE, f"cfg5_{idx}_expected.json"), "w"))
+    elif which == "cfg4_exact":
+        from oracle import exact_minimum
+
+        inp = inputs.config(4)
+        json.dump({"source": "oracle/exact_minimum.py on inputs.config(4)", "n_min": inp.n_min,
+                   "exact_minimum": exact_minimum.exact_minimum(inp)},
+                  open(os.path.join(HERE, "cfg4_exact_minimum.json"), "w"))
     else:
         raise SystemExit(__doc__)
 

@@ -33,7 +33,25 @@ def test_library_exports_every_declared_symbol():
     dist = declared_symbols("oob_dist.h", "oob_dist_")
     assert dist == ["oob_dist_choose", "oob_dist_solve"] and all(hasattr(lib, n) for n in dist)
     assert sorted(B.DIST_SYMBOLS) == dist
-    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["oob_dist.h", "oob_inst.h", "oob_plan.h", "oob_reconf.h"]
+    exact = declared_symbols("oob_exact.h", "oob_exact_")
+    assert exact == ["oob_exact_minimum", "oob_exact_workspace_size"] and all(hasattr(lib, n) for n in exact)
+    assert sorted(B.EXACT_SYMBOLS) == exact
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["oob_dist.h", "oob_exact.h", "oob_inst.h", "oob_plan.h",
+                                                                  "oob_reconf.h"]
+
+
+def test_exact_minimum_entry_point_validates_arguments_without_touching_the_gpu():
+    assert P.oob_exact_workspace_size(98, 64, 8) > 0 and P.oob_exact_workspace_size(98, 64, 8) % 256 == 0
+    assert P.oob_exact_workspace_size(256, 1, 1) == 0 and P.oob_exact_workspace_size(10, 600, 8) == 0
+    prof = B.oob_profile(1, 1, 1, 1)
+    fake = 0x10000
+    call = lambda **kw: P.oob_exact_minimum(kw.get("prof", prof), kw.get("L", 12), kw.get("n_min", 1), kw.get("n_max", 4),
+                                            kw.get("M", 2), kw.get("nb", 8), kw.get("cap", 1 << 30), kw.get("ws", fake),
+                                            kw.get("nbytes", 1 << 40), kw.get("best", fake), kw.get("st", fake), 0)
+    for bad in (dict(prof=None), dict(L=0), dict(L=256), dict(n_min=0), dict(n_min=5), dict(M=0), dict(cap=0),
+                dict(ws=0), dict(ws=0x10001), dict(best=0), dict(st=0), dict(nb=7)):   # nb = 7 < min(L, n_max M) = 8
+        assert call(**bad) == P.OOB_EINVAL, bad
+    assert call(nbytes=1024) == P.OOB_ECAPACITY
 
 
 def test_reconfiguration_entry_point_validates_arguments_without_touching_the_gpu():
