@@ -106,6 +106,50 @@ def bench_instantiation(P, inp, res, reps=20):
                          "kernel": "k_inst_unrank", "bytes_per_vector": 2 * p}}
 
 
+def bench_exact(P, inp, res, reps=3):
+    """The exact minimum of the template cost for every template of the workload, and the gap of the
+    recursion's result to it.  Timed with events on the stream the kernels are launched on; the
+    oracle (all host cores) is timed on the same job when that takes seconds, else on a part of it."""
+    import torch
+    from oracle import capi, exact_minimum
+
+    if inp.microbatches < min(inp.L, inp.n_max * inp.gpus_per_node):
+        return None
+    ex = P.ExactMinimum(inp)
+    stream = torch.cuda.current_stream()
+    st, got = ex.run()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev[0].record(stream)
+    for _ in range(reps):
+        ex.enqueue()
+    ev[1].record(stream)
+    torch.cuda.synchronize()
+    dt = ev[0].elapsed_time(ev[1]) / reps * 1e-3
+    assert st == P.OOB_OK, "exact minimum"
+    gaps = [int(res["T"][i]) / e - 1 for i, e in enumerate(got) if e is not None]
+    small = dataclasses.replace(inp, n_max=min(inp.n_max, inp.n_min + 7)) if capi.lib().oob_oracle_threads() < 16 else inp
+    t0 = time.time()
+    want = exact_minimum.exact_minimum(small)
+    t_cpu = time.time() - t0
+    assert want == got[: len(want)], "exact minimum against the oracle"
+    L, M, Dmax = inp.L, inp.gpus_per_node, inp.n_max * inp.gpus_per_node
+    cand = L * (L + 1) // 2 * M
+    # relaxations the two tables of a candidate take: (earlier layer, GPU count, position) triples per layer
+    per_layer_pair = sum(sum(1 for D0 in range(0, Dmax - dd + 1) if D0 % M + dd <= M) for dd in range(1, M + 1))
+    relax = sum(M * per_layer_pair * (u * (u + 1) // 2 + (L - v) * (L - v + 1) // 2)
+                for u in range(L) for v in range(u + 1, L + 1))
+    ops = 8  # per relaxation: 64-bit add, compare and select (2 lane-ops each) and the test of the stage time
+    return {"workload": f"{len(got)} templates, {cand} candidate slowest stages, tables of {L + 1} x "
+                        f"{Dmax + 1} positions, {relax} relaxations",
+            "ms": dt * 1e3, "value": len(got) / dt, "unit": "templates/s",
+            "roofline": {"bound": "alu", "achieved": relax * ops / dt / 1e12, "peak": PEAK_LANE_OPS / 1e12,
+                         "unit": "T lane-op/s", "frac": relax * ops / dt / PEAK_LANE_OPS, "traffic": None,
+                         "kernel": "k_exact", "ops_per_relaxation": ops, "relaxations_per_s": relax / dt},
+            "recursion_gap_max": max(gaps) if gaps else None, "recursion_exact_for": sum(g == 0 for g in gaps),
+            "cpu_baseline": {"seconds": t_cpu, "cores": capi.lib().oob_oracle_threads(), "kind": "oracle",
+                             "sample": f"templates for {small.n_min}..{small.n_max} nodes"}}
+
+
 def bench_distribution(P, inp, res, Q=512, reps=3, oracle_sample=40):
     """Section 4.2.2 on every plan the enumeration of this node specification lists: Eq. 6 solved
     exactly per plan (time per microbatch of a template = its T1), then the best plan per cluster
@@ -354,6 +398,7 @@ def main():
     line["instantiation"] = bench_instantiation(P, inp, res)
     line["reconfiguration"] = bench_reconfiguration(P, inp, res)
     line["distribution"] = bench_distribution(P, inp, res)
+    line["exact_minimum"] = bench_exact(P, inp, res)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(inp)
     print(json.dumps(line))

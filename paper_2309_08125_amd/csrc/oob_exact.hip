@@ -15,13 +15,14 @@
 // template into LDS and, at the end, into the result with 64-bit atomic minima.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "oob_exact.h"
 
 namespace oob_exact {
 
 constexpr int kThreads = 256;
-constexpr int kSlots = 1024;                    // workgroups in flight, each with tables of its own
+constexpr int kSlots = 2048;                    // workgroups in flight (8 waves per SIMD), each with tables of its own
 constexpr long long kInf = 1ll << 61;
 constexpr long long kForbidden = 1ll << 62;
 
@@ -185,7 +186,9 @@ extern "C" int oob_exact_minimum(const oob_profile *profile, int L, int n_min, i
     const int setup_threads = L * M > count ? L * M : count;
     hipLaunchKernelGGL(k_exact_stages, dim3((setup_threads + 63) / 64), dim3(64), 0, st, a);
     const long long ncand = (long long)L * (L + 1) / 2 * M;
-    const unsigned grid = (unsigned)(ncand < kSlots ? ncand : kSlots);
+    const char *env = getenv("OOB_TUNE_EXACT_SLOTS"); // debug knob: fewer workgroups in flight (at most kSlots)
+    const long long want = env && atoi(env) > 0 && atoi(env) < kSlots ? atoi(env) : kSlots;
+    const unsigned grid = (unsigned)(ncand < want ? ncand : want);
     const size_t lds = sizeof(long long) * ((size_t)L * M + count);
     hipLaunchKernelGGL(k_exact, dim3(grid), dim3(kThreads), lds, st, a);
     hipLaunchKernelGGL(k_exact_finish, dim3((count + 63) / 64), dim3(64), 0, st, (long long *)best, count);
