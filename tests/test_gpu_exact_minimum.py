@@ -23,7 +23,9 @@ def P():
 
 
 SHAPES = [(1, 1, 1, 1, 4), (5, 1, 1, 3, 6), (6, 2, 1, 3, 8), (7, 2, 1, 2, 9), (6, 4, 1, 2, 12), (8, 4, 2, 2, 12),
-          (9, 2, 2, 3, 9), (12, 3, 1, 4, 12), (15, 2, 1, 5, 15), (23, 8, 1, 3, 30), (37, 3, 1, 5, 40), (20, 16, 1, 2, 33)]
+          (9, 2, 2, 3, 9), (12, 3, 1, 4, 12), (15, 2, 1, 5, 15), (23, 8, 1, 3, 30), (37, 3, 1, 5, 40), (20, 16, 1, 2, 33),
+          # more GPU positions than one tile of the kernel holds: several blocks of whole nodes
+          (12, 8, 1, 10, 12), (10, 4, 2, 20, 10), (14, 3, 1, 30, 14), (9, 16, 1, 6, 9), (30, 5, 1, 27, 30)]
 
 
 @pytest.mark.parametrize("shape", SHAPES)
