@@ -93,9 +93,11 @@ __global__ void __launch_bounds__(kThreads) k_exact(Args a) {
                 for (int dd = 1; dd <= M && dd <= D; ++dd) {
                     const int D0 = D - dd;
                     if (D0 % M + dd > M) continue; // would cross a node boundary
-                    for (int q = 0; q < p; ++q) {
+                    // a stage [q, p) only gets longer and heavier as q goes down: once it is too slow (or
+                    // impossible) it stays so, and the loop ends
+                    for (int q = p - 1; q >= 0; --q) {
                         const long long tt = s_col[q * M + dd - 1];
-                        if (tt < 0 || tt >= tau) continue;
+                        if (tt < 0 || tt >= tau) break;
                         const long long x = Pre[(size_t)q * W + D0] + tt;
                         m = x < m ? x : m;
                     }
@@ -116,9 +118,9 @@ __global__ void __launch_bounds__(kThreads) k_exact(Args a) {
                 for (int dd = 1; dd <= M && dd <= E; ++dd) {
                     const int E0 = E - dd;
                     if (E0 % M + dd > M) continue;
-                    for (int w = p + 1; w <= L; ++w) {
+                    for (int w = p + 1; w <= L; ++w) { // likewise for [p, w) as w goes up
                         const long long tt = s_col[(w - p - 1) * M + dd - 1];
-                        if (tt < 0 || tt > tau) continue;
+                        if (tt < 0 || tt > tau) break;
                         const long long x = Suf[(size_t)w * W + E0] + 2 * tt - tau;
                         m = x < m ? x : m;
                     }
