@@ -40,7 +40,10 @@ size_t oob_exact_workspace_size(int L, int n_max, int gpus_per_node);
 
 /*   profile       as for oob_plan_templates (device arrays)
  *   best          [n_max - n_min + 1] out: the exact minimum for n nodes, -1 if no pipeline exists
- *   status        [1] out: OOB_OK, or OOB_EINVAL for a negative profile entry
+ *   status        [1] out: OOB_OK; OOB_EINVAL for a negative profile entry; OOB_EOVERFLOW when
+ *                 (N_b + 2) w >= 2^61, w = sum over the layers of (largest allowed F + B of the
+ *                 layer over the GPU counts) + boundary_ns: every cost stays below (N_b + 2) w, so
+ *                 below that bound all int64 arithmetic is exact.  `best` is meaningless unless OOB_OK.
  * Returns OOB_OK once enqueued; OOB_EINVAL for arguments the host can reject, among them
  * microbatches < min(L, n_max * gpus_per_node); OOB_ECAPACITY for a workspace that is too small. */
 int oob_exact_minimum(const oob_profile *profile, int L, int n_min, int n_max, int gpus_per_node,

@@ -66,6 +66,11 @@ int oob_inst_enumerate(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, 
                        uint16_t *x, int64_t capacity, const int64_t *offsets, int32_t *status,
                        void *stream);
 
+/* Test hook (process-wide): on != 0 makes oob_inst_count keep the table in 64 bits even when every
+ * count is below 2^32, so that the path for longer lists can be exercised on cases small enough
+ * to enumerate.  Results are identical either way.  Returns the previous setting. */
+int oob_inst_keep_wide_table(int on);
+
 #ifdef __cplusplus
 }
 #endif

@@ -131,6 +131,22 @@ int oob_plan_templates_batch(oob_plan *h, int count, const oob_profile *profiles
  * second stream and events go back to a pool of the library for the next handle). */
 int oob_plan_destroy(oob_plan *h);
 
+/* Launch options of a handle (tests and measurements; every setting gives bit-identical results).
+ * Takes effect from the next oob_plan_templates / oob_plan_templates_batch call on.
+ *   OOB_OPT_PLAIN_SPLIT  1: the levels S' >= 2 run the tiled split kernel without (total, k) keys,
+ *                        which otherwise only serves shapes beyond the keyed kernel's LDS classes
+ *                        (hundreds of nodes); default 0
+ *   OOB_OPT_XCD_ORDER    1: the workgroup tasks of a level are ordered block row by block row and
+ *                        every XCD walks one contiguous stretch of that list (fewer bytes from
+ *                        HBM, slightly more time on the headline workload); default 0
+ *   OOB_OPT_ONE_STREAM   1: all levels on the caller's stream (no second stream, no events);
+ *                        default 0: consecutive levels overlap on a second stream of the library
+ * Returns OOB_EINVAL for an unknown option. */
+#define OOB_OPT_PLAIN_SPLIT 1
+#define OOB_OPT_XCD_ORDER 2
+#define OOB_OPT_ONE_STREAM 3
+int oob_plan_set_option(oob_plan *h, int option, int value);
+
 /* Measurement hook.  After oob_plan_level_timing(h, 1) every oob_plan_templates call records
  * two HIP events of the handle on its stream, one before the first and one after the last
  * launch of the levels S' >= 2 (the divide/combine step, Eq. 1-3).  oob_plan_last_level_ms

@@ -20,8 +20,10 @@ _ERR = {OOB_EINVAL: "OOB_EINVAL", OOB_ECAPACITY: "OOB_ECAPACITY", OOB_EOVERFLOW:
 
 SYMBOLS = ["oob_plan_max_stages", "oob_plan_workspace_size", "oob_plan_create",
            "oob_plan_templates", "oob_plan_templates_batch", "oob_plan_destroy", "oob_plan_export_block",
-           "oob_plan_level_timing", "oob_plan_last_level_ms", "oob_plan_export_flags", "oob_plan_valu_peak"]
-INST_SYMBOLS = ["oob_inst_workspace_size", "oob_inst_count", "oob_inst_enumerate"]
+           "oob_plan_level_timing", "oob_plan_last_level_ms", "oob_plan_export_flags", "oob_plan_valu_peak",
+           "oob_plan_set_option"]
+OOB_OPT_PLAIN_SPLIT, OOB_OPT_XCD_ORDER, OOB_OPT_ONE_STREAM = 1, 2, 3
+INST_SYMBOLS = ["oob_inst_workspace_size", "oob_inst_count", "oob_inst_enumerate", "oob_inst_keep_wide_table"]
 RECONF_SYMBOLS = ["oob_reconf_simulate"]
 DIST_SYMBOLS = ["oob_dist_solve", "oob_dist_choose"]
 EXACT_SYMBOLS = ["oob_exact_workspace_size", "oob_exact_minimum"]
@@ -82,6 +84,10 @@ def load():
         L.oob_plan_export_block.restype = C.c_int
         L.oob_plan_valu_peak.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
         L.oob_plan_valu_peak.restype = C.c_int
+        L.oob_plan_set_option.argtypes = [C.c_void_p, C.c_int, C.c_int]
+        L.oob_plan_set_option.restype = C.c_int
+        L.oob_inst_keep_wide_table.argtypes = [C.c_int]
+        L.oob_inst_keep_wide_table.restype = C.c_int
         L.oob_inst_workspace_size.argtypes = [C.c_int] * 3
         L.oob_inst_workspace_size.restype = C.c_size_t
         spec = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t]
@@ -334,6 +340,9 @@ class Planner:
         self.enqueue(prof, out)
         torch.cuda.synchronize(self.device)
         return out.to_host()
+
+    def set_option(self, option: int, value: int):
+        check(load().oob_plan_set_option(self.h, option, value), "oob_plan_set_option")
 
     def flags(self):
         """[keyed split kernel used, reserved x3] of the last call."""

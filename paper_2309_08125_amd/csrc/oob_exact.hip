@@ -40,20 +40,51 @@ inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 inline size_t table_bytes(int L, int M) { return align_up(sizeof(long long) * (size_t)(L + 1) * (L + 1) * M); }
 inline size_t slot_bytes(int L, int Dmax) { return align_up(sizeof(long long) * 2 * (size_t)(L + 1) * (Dmax + 1)); }
 
-// Stage times of all (u, v, d): one thread per (u, d) walks v.  Also clears the result.
+// Clears the result and validates the magnitudes: every cost is at most (N_b + 2) w, w = the sum
+// over the layers of the slowest allowed F + B of the layer plus its boundary term (a bound on the
+// sum of all stage times of any pipeline).  status = OOB_EOVERFLOW unless that stays below 2^61.
+// One workgroup; runs before k_exact_stages, which only ever lowers the status.
+__global__ void __launch_bounds__(kThreads) k_exact_init(Args a) {
+    __shared__ long long s_sum[kThreads];
+    const int count = a.n_max - a.n_min + 1;
+    for (int i = threadIdx.x; i < count; i += kThreads) a.best[i] = kInf;
+    const long long *fwd = (const long long *)a.prof.fwd_ns, *bwd = (const long long *)a.prof.bwd_ns;
+    const long long *bnd = (const long long *)a.prof.boundary_ns;
+    long long acc = 0;
+    for (int l = threadIdx.x; l < a.L; l += kThreads) {
+        long long worst = 0;
+        for (int d = 1; d <= a.M; ++d) {
+            const long long f = fwd[(size_t)l * a.M + d - 1], b = bwd[(size_t)l * a.M + d - 1];
+            if (f < 0 || b < 0 || f >= kForbidden || b >= kForbidden) continue;
+            const long long fb = (f >= kInf || b >= kInf) ? kInf : f + b;
+            worst = fb > worst ? fb : worst;
+        }
+        const long long x = bnd[l];
+        if (x > 0) worst = (x >= kInf || worst >= kInf) ? kInf : worst + x;
+        acc = (acc + worst >= kInf || worst >= kInf) ? kInf : acc + worst;
+    }
+    s_sum[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long w = 0;
+        for (int i = 0; i < kThreads; ++i) w = (w + s_sum[i] >= kInf) ? kInf : w + s_sum[i];
+        *a.status = w >= kInf / ((long long)a.Nb + 2) ? OOB_EOVERFLOW : OOB_OK;
+    }
+}
+
+// Stage times of all (u, v, d): one thread per (u, d) walks v.  A negative profile entry sets the
+// status to OOB_EINVAL (every writer stores the same value, so the order does not matter).
 __global__ void k_exact_stages(Args a) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i == 0) *a.status = OOB_OK;
-    if (i <= a.n_max - a.n_min) a.best[i] = kInf;
     if (i >= a.L * a.M) return;
     const int u = i / a.M, d = i % a.M + 1;
     const long long *fwd = (const long long *)a.prof.fwd_ns, *bwd = (const long long *)a.prof.bwd_ns;
     const long long *mem = (const long long *)a.prof.mem_bytes, *bnd = (const long long *)a.prof.boundary_ns;
     long long time = 0, bytes = 0;
-    bool ok = true;
+    bool ok = true, bad = false;
     for (int v = u + 1; v <= a.L; ++v) {
         const long long f = fwd[(size_t)(v - 1) * a.M + d - 1], b = bwd[(size_t)(v - 1) * a.M + d - 1];
-        if (f < 0 || b < 0 || mem[v - 1] < 0 || bnd[v - 1] < 0) *a.status = OOB_EINVAL;
+        if (f < 0 || b < 0 || mem[v - 1] < 0 || bnd[v - 1] < 0) bad = true;
         if (f >= kForbidden || b >= kForbidden) ok = false;
         time += ok ? f + b : 0;
         bytes += mem[v - 1];
@@ -61,6 +92,7 @@ __global__ void k_exact_stages(Args a) {
         if (ok && (bytes + d - 1) / d <= a.cap) val = time + (v < a.L ? bnd[v - 1] : 0);
         a.t[((size_t)u * (a.L + 1) + v) * a.M + d - 1] = val;
     }
+    if (bad) atomicExch(a.status, OOB_EINVAL);
 }
 
 __global__ void __launch_bounds__(kThreads) k_exact(Args a) {
@@ -68,6 +100,8 @@ __global__ void __launch_bounds__(kThreads) k_exact(Args a) {
     const int L = a.L, M = a.M, W = a.Dmax + 1, count = a.n_max - a.n_min + 1;
     long long *s_col = s_dyn, *s_best = s_dyn + (size_t)L * M;
     long long *Pre = a.slots + (size_t)blockIdx.x * 2 * (L + 1) * W, *Suf = Pre + (size_t)(L + 1) * W;
+    const long long *bnd = (const long long *)a.prof.boundary_ns;
+    if (*a.status != OOB_OK) return; // the same for every thread: nothing is computed from a bad profile
     for (int i = threadIdx.x; i < count; i += kThreads) s_best[i] = kInf;
     const long long ncand = (long long)L * (L + 1) / 2 * M;
     for (long long c = blockIdx.x; c < ncand; c += gridDim.x) {
@@ -118,9 +152,17 @@ __global__ void __launch_bounds__(kThreads) k_exact(Args a) {
                 for (int dd = 1; dd <= M && dd <= E; ++dd) {
                     const int E0 = E - dd;
                     if (E0 % M + dd > M) continue;
-                    for (int w = p + 1; w <= L; ++w) { // likewise for [p, w) as w goes up
+                    // [p, w) as w goes up: impossible stays impossible and the time without the boundary
+                    // term only grows, so those end the loop.  The time WITH the boundary term does not
+                    // grow (the term belongs to the last layer and the model's last stage pays none):
+                    // a stage that is only too slow because of it is skipped, not the rest of the run.
+                    for (int w = p + 1; w <= L; ++w) {
                         const long long tt = s_col[(w - p - 1) * M + dd - 1];
-                        if (tt < 0 || tt > tau) break;
+                        if (tt < 0) break;
+                        if (tt > tau) {
+                            if (w == L || tt - bnd[w - 1] > tau) break;
+                            continue;
+                        }
                         const long long x = Suf[(size_t)w * W + E0] + 2 * tt - tau;
                         m = x < m ? x : m;
                     }
@@ -185,12 +227,10 @@ extern "C" int oob_exact_minimum(const oob_profile *profile, int L, int n_min, i
     a.best = (long long *)best; a.status = status;
     hipStream_t st = (hipStream_t)stream;
     const int count = n_max - n_min + 1;
-    const int setup_threads = L * M > count ? L * M : count;
-    hipLaunchKernelGGL(k_exact_stages, dim3((setup_threads + 63) / 64), dim3(64), 0, st, a);
+    hipLaunchKernelGGL(k_exact_init, dim3(1), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL(k_exact_stages, dim3((L * M + 63) / 64), dim3(64), 0, st, a);
     const long long ncand = (long long)L * (L + 1) / 2 * M;
-    const char *env = getenv("OOB_TUNE_EXACT_SLOTS"); // debug knob: fewer workgroups in flight (at most kSlots)
-    const long long want = env && atoi(env) > 0 && atoi(env) < kSlots ? atoi(env) : kSlots;
-    const unsigned grid = (unsigned)(ncand < want ? ncand : want);
+    const unsigned grid = (unsigned)(ncand < kSlots ? ncand : kSlots);
     const size_t lds = sizeof(long long) * ((size_t)L * M + count);
     hipLaunchKernelGGL(k_exact, dim3(grid), dim3(kThreads), lds, st, a);
     hipLaunchKernelGGL(k_exact_finish, dim3((count + 63) / 64), dim3(64), 0, st, (long long *)best, count);

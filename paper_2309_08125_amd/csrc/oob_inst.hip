@@ -15,6 +15,7 @@
 #include <stdint.h>
 #include <stdlib.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "oob_inst.h"
@@ -243,9 +244,42 @@ static int check_spec(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, i
     return OOB_OK;
 }
 
+static std::atomic<int> g_keep_wide{0}; // test hook: never use the 32-bit copy of the table
+
+static int launch_count(const Spec &s, int64_t *offsets, int32_t *status, hipStream_t stream) {
+    const int keep_wide = g_keep_wide.load();
+    const size_t plane = (size_t)(s.N_hi + 1) * (s.Q + 1) * sizeof(long long);
+    const size_t scan = (size_t)(s.N_hi - s.N_lo + 2) * sizeof(long long);
+    if (2 * plane <= 128 * 1024) {
+        const size_t lds = 2 * plane > scan ? 2 * plane : scan;
+        if (lds > 64 * 1024 &&
+            hipFuncSetAttribute((const void *)k_inst_count<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return OOB_EHIP;
+        hipLaunchKernelGGL(k_inst_count<true>, dim3(1), dim3(1024), lds, stream, s, (long long *)offsets, status,
+                           keep_wide);
+    } else {
+        hipLaunchKernelGGL(k_inst_count<false>, dim3(1), dim3(1024), scan, stream, s, (long long *)offsets, status,
+                           keep_wide);
+    }
+    return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
+}
+
+static int launch_unrank(const Spec &s, const int64_t *offsets, int32_t *status, uint16_t *x, int64_t capacity,
+                         hipStream_t stream) {
+    // one lane per vector of the capacity; the kernel strides if the grid limit cuts that short
+    const long long want = (capacity + 255) / 256;
+    const int grid = (int)(want < 1 ? 1 : (want > (1 << 22) ? (1 << 22) : want));
+    hipLaunchKernelGGL(k_inst_unrank, dim3(grid), dim3(256), 0, stream, s, (const long long *)offsets, status,
+                       (unsigned short *)x, (long long)capacity);
+    return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
+}
+
 } // namespace oob_inst
 
 extern "C" {
+
+int oob_inst_keep_wide_table(int on) { return oob_inst::g_keep_wide.exchange(on != 0); }
 
 size_t oob_inst_workspace_size(int p, int N_hi, int f) {
     if (!oob_inst::args_ok(p, 0, N_hi, f)) return 0;
@@ -258,24 +292,7 @@ int oob_inst_count(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, int 
     Spec s;
     const int rc = check_spec(sizes, p, n0, N_lo, N_hi, f, dev_workspace, workspace_bytes, offsets, status, &s);
     if (rc != OOB_OK) return rc;
-    // debug knob: never use the 32-bit copy of the table (tests of the 64-bit path)
-    const char *ev = getenv("OOB_TUNE_INST_INT64");
-    const int keep_wide = ev && atoi(ev) != 0;
-    const size_t plane = (size_t)(N_hi + 1) * (f + 2) * sizeof(long long);
-    const size_t scan = (size_t)(N_hi - N_lo + 2) * sizeof(long long);
-    if (2 * plane <= 128 * 1024) {
-        const size_t lds = 2 * plane > scan ? 2 * plane : scan;
-        if (lds > 64 * 1024 &&
-            hipFuncSetAttribute((const void *)k_inst_count<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds) != hipSuccess)
-            return OOB_EHIP;
-        hipLaunchKernelGGL(k_inst_count<true>, dim3(1), dim3(1024), lds, (hipStream_t)stream, s,
-                           (long long *)offsets, status, keep_wide);
-    } else {
-        hipLaunchKernelGGL(k_inst_count<false>, dim3(1), dim3(1024), scan, (hipStream_t)stream, s,
-                           (long long *)offsets, status, keep_wide);
-    }
-    return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
+    return launch_count(s, offsets, status, (hipStream_t)stream);
 }
 
 int oob_inst_enumerate(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, int f, void *dev_workspace,
@@ -287,12 +304,7 @@ int oob_inst_enumerate(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, 
                               status, &s);
     if (rc != OOB_OK) return rc;
     if (capacity < 0 || (capacity > 0 && !x)) return OOB_EINVAL;
-    // one lane per vector of the capacity; the kernel strides if the grid limit cuts that short
-    const long long want = (capacity + 255) / 256;
-    const int grid = (int)(want < 1 ? 1 : (want > (1 << 22) ? (1 << 22) : want));
-    hipLaunchKernelGGL(k_inst_unrank, dim3(grid), dim3(256), 0, (hipStream_t)stream, s,
-                       (const long long *)offsets, status, (unsigned short *)x, (long long)capacity);
-    return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
+    return launch_unrank(s, offsets, status, x, capacity, (hipStream_t)stream);
 }
 
 } // extern "C"

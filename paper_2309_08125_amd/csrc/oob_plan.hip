@@ -722,9 +722,6 @@ __global__ void __launch_bounds__(64) k_select(Tables t, int Sp, int NT, int NAa
     }
     if (best < kNone) {
         if (bm == 0) {
-#ifdef OOB_EMU_DEBUG
-            fprintf(stderr, "select fail Sp=%d delta=%d u=%d v=%d best=%g bs=%d bk=%d\n", Sp, delta, u, v, best, bs, bk);
-#endif
             *t.status = kInternalError;
         } else {
             const int r = Sp - bs;
@@ -983,10 +980,14 @@ int env_or(const char *name, int dflt) {
     const char *v = getenv(name);
     return v && *v ? atoi(v) : dflt;
 }
+// Debug knobs, read once when the library is loaded (the defaults are the measured optimum).
 static const int kKeyWaves = env_or("OOB_TUNE_KEY_WAVES", 4);
 static const int kKeyHalves = env_or("OOB_TUNE_KEY_HALVES", 2);
 static const int kKeyPack = env_or("OOB_TUNE_KEY_PACK", 1);
-bool plan_split_key(const Shape &sh, int Sp, int fam, SplitPlan *p) {
+static const int kKeyNbuf = env_or("OOB_TUNE_KEY_NBUF", 1);
+static const int kBatchOverlap = env_or("OOB_TUNE_BATCH_OVERLAP", 0);
+static const int kBatchLanes = env_or("OOB_TUNE_BATCH_LANES", 8);
+bool plan_split_key(const Shape &sh, int Sp, int fam, int xcd_order, SplitPlan *p) {
     int t_lo, t_hi;
     target_units(fam, Sp, sh.M, sh.n_max, &t_lo, &t_hi);
     if (fam == 0 && Sp > sh.M) return false;
@@ -1008,8 +1009,7 @@ bool plan_split_key(const Shape &sh, int Sp, int fam, SplitPlan *p) {
             }
         }
     }
-    const int kXcd = env_or("OOB_TUNE_XCD", 0); // read at every call
-    p->pc = (kKeyHalves & 3) | (kKeyPack ? 4 : 0) | (kXcd ? 8 : 0); // bits 0-1: cut left-over items; bit 2: several items per wave near the range ends; bit 3: XCD-chunked task order
+    p->pc = (kKeyHalves & 3) | (kKeyPack ? 4 : 0) | (xcd_order ? 8 : 0); // bits 0-1: cut left-over items; bit 2: several items per wave near the range ends; bit 3: XCD-chunked task order
     p->ntab = ntab;
     p->na = imin(cnt, kKeyTargets);
     p->lds = 0; // static LDS: see the capacity classes at the launch site
@@ -1076,6 +1076,7 @@ struct oob_plan {
     bool have_last;
     hipEvent_t ev_begin, ev_end; // optional: recorded around the level launches
     bool timed;
+    int opt_plain, opt_xcd, opt_one_stream; // oob_plan_set_option
 };
 
 #define OOB_HIP_CHECK(expr)                                                                   \
@@ -1117,6 +1118,7 @@ extern "C" int oob_plan_create(oob_plan **h, int max_L, int max_nodes, int max_g
     p->lane_bytes = align_up(cv.total);
     p->lanes = (int)std::min<size_t>(kMaxLanes, std::max<size_t>(1, workspace_bytes / p->lane_bytes));
     p->ev_fork = nullptr; p->last_lane = 0;
+    p->opt_plain = p->opt_xcd = p->opt_one_stream = 0;
     *h = p;
     return OOB_OK;
 }
@@ -1174,8 +1176,7 @@ struct SplitRange { int s0, sstep, scount; };
 template <int NTAB, int NA>
 static void launch_split_key_c(const Tables &t, int S, int fam, const SplitPlan &sp, int NT, int NAall,
                                SplitRange sr, hipStream_t st) {
-    static const int nbuf = env_or("OOB_TUNE_KEY_NBUF", 1);
-    if (nbuf == 2)
+    if (kKeyNbuf == 2)
         hipLaunchKernelGGL((k_split_key<NTAB, NA, 2>), dim3(seg_count(t.sh.L, S), sr.scount, sp.groups),
                            dim3(sp.waves * 64), 0, st, t, S, fam, NT, NAall, sp.pc, sr.s0, sr.sstep);
     else
@@ -1234,12 +1235,11 @@ static int enqueue_job(oob_plan *h, int ln, bool want_overlap, const oob_profile
     sh.Smax = smax_of(L, n_max, M, microbatches);
     // launch shapes first, so that nothing is enqueued when a level cannot be staged in LDS
     // a level's tables exceed the keyed kernel's LDS classes (or the debug knob says so): plain kernel everywhere
-    const char *fp_env = getenv("OOB_TUNE_FORCE_PLAIN");
-    int force_plain = fp_env && atoi(fp_env) != 0;
+    int force_plain = h->opt_plain != 0;
     for (int S = 2; S <= sh.Smax; ++S)
         for (int fam = 0; fam < 2; ++fam) {
             SplitPlan sp;
-            if (plan_split_key(sh, S, fam, &sp) && key_class(sp.ntab, sp.na) < 0) force_plain = 1;
+            if (plan_split_key(sh, S, fam, h->opt_xcd, &sp) && key_class(sp.ntab, sp.na) < 0) force_plain = 1;
         }
     if (force_plain)
         for (int S = 2; S <= sh.Smax; ++S)
@@ -1253,7 +1253,7 @@ static int enqueue_job(oob_plan *h, int ln, bool want_overlap, const oob_profile
     hipLaunchKernelGGL(k_setup, dim3(1), dim3(OOB_MAX_GPUS + 1), 0, st, t, *profile, force_plain);
     hipLaunchKernelGGL(k_level1, dim3(tile_count(L, 1), M), dim3(64), 0, st, t,
                        (const long long *)profile->boundary_ns);
-    if (sh.Smax >= 2) hipLaunchKernelGGL(k_seg_tab, dim3(sh.Smax - 1), dim3(64), 0, st, t, env_or("OOB_TUNE_XCD", 0));
+    if (sh.Smax >= 2) hipLaunchKernelGGL(k_seg_tab, dim3(sh.Smax - 1), dim3(64), 0, st, t, h->opt_xcd);
     const long long slot_stride = h->cv.slots * 64; // distance between the two buffers of per-split minima
     hipLaunchKernelGGL(k_fill_keys, dim3((unsigned)((2 * slot_stride + 255) / 256)), dim3(256), 0, st, t.partKey,
                        2 * slot_stride);
@@ -1289,7 +1289,7 @@ static int enqueue_job(oob_plan *h, int ln, bool want_overlap, const oob_profile
         SplitPlan sp[2], kp[2];
         bool have[2];
         for (int fam = 0; fam < 2; ++fam) {
-            have[fam] = plan_split(sh, S, fam, &sp[fam]) && plan_split_key(sh, S, fam, &kp[fam]);
+            have[fam] = plan_split(sh, S, fam, &sp[fam]) && plan_split_key(sh, S, fam, h->opt_xcd, &kp[fam]);
             if (have[fam]) kp[fam].cls = key_class(kp[fam].ntab, kp[fam].na);
         }
         if (overlap) {
@@ -1325,8 +1325,7 @@ static int enqueue_job(oob_plan *h, int ln, bool want_overlap, const oob_profile
 extern "C" int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L, int n_min, int n_max,
                                   int gpus_per_node, int microbatches, int64_t mem_cap, int f,
                                   oob_templates *out, void *stream) {
-    static const int want_overlap = env_or("OOB_TUNE_OVERLAP", 1);
-    return enqueue_job(h, 0, want_overlap != 0, profile, L, n_min, n_max, gpus_per_node, microbatches, mem_cap, f,
+    return enqueue_job(h, 0, h && !h->opt_one_stream, profile, L, n_min, n_max, gpus_per_node, microbatches, mem_cap, f,
                        out, (hipStream_t)stream);
 }
 
@@ -1337,9 +1336,7 @@ extern "C" int oob_plan_templates_batch(oob_plan *h, int count, const oob_profil
     if (!h || count < 0 || (count > 0 && (!profiles || !L || !n_min || !n_max || !gpus_per_node ||
                                            !microbatches || !mem_cap || !f || !outs)))
         return OOB_EINVAL;
-    static const int want_overlap = env_or("OOB_TUNE_OVERLAP", 1);
-    static const int lane_overlap = env_or("OOB_TUNE_BATCH_OVERLAP", 0);
-    static const int max_lanes = env_or("OOB_TUNE_BATCH_LANES", kMaxLanes);
+    const int want_overlap = !h->opt_one_stream, lane_overlap = kBatchOverlap, max_lanes = kBatchLanes;
     hipStream_t st = (hipStream_t)stream;
     // Lanes: job i runs in lane i mod K, the jobs of a lane one after the other on the lane's own
     // stream, the lanes side by side.  Lane 0 is the caller's stream; the others start after what
@@ -1368,6 +1365,17 @@ extern "C" int oob_plan_templates_batch(oob_plan *h, int count, const oob_profil
         OOB_HIP_CHECK(hipStreamWaitEvent(st, h->lane[ln].ev_join, 0));
     }
     return rc;
+}
+
+extern "C" int oob_plan_set_option(oob_plan *h, int option, int value) {
+    if (!h) return OOB_EINVAL;
+    switch (option) {
+    case OOB_OPT_PLAIN_SPLIT: h->opt_plain = value != 0; break;
+    case OOB_OPT_XCD_ORDER: h->opt_xcd = value != 0; break;
+    case OOB_OPT_ONE_STREAM: h->opt_one_stream = value != 0; break;
+    default: return OOB_EINVAL;
+    }
+    return OOB_OK;
 }
 
 extern "C" int oob_plan_level_timing(oob_plan *h, int enable) {

@@ -9,6 +9,9 @@ stage-count level over the canonical form of every state record of that level
     python tests/golden/make_golden.py cfg4_paper_nb     (configuration 4 with N_b = 4 S' per state)
     python tests/golden/make_golden.py cfg5 <instance> [<instance> ...]
     python tests/golden/make_golden.py cfg4_exact        (exact minimum of the cost per template, about a minute)
+    python tests/golden/make_golden.py cfg5_all [threads] (all 256 instances of the batched configuration: per
+                                                          instance T, S, feasibility and one SHA-256 over everything
+                                                          parity_util.compare_templates compares; about an hour)
 """
 import hashlib
 import json
@@ -65,6 +68,26 @@ def main():
         for idx in map(int, sys.argv[2:]):
             json.dump(expected(insts[idx]),
                       open(os.path.join(HERE, f"cfg5_{idx}_expected.json"), "w"))
+    elif which == "cfg5_all":
+        threads = int(sys.argv[2]) if len(sys.argv) > 2 else 0
+        insts = inputs.config(5)
+        path = os.path.join(HERE, "cfg5_all_templates.json")
+        done = json.load(open(path))["instances"] if os.path.exists(path) else {}
+        t0 = time.time()
+        for idx, inp in enumerate(insts):
+            if str(idx) in done:
+                continue
+            t = capi.plan(inp, threads)
+            cnt = inp.n_max - inp.n_min + 1
+            done[str(idx)] = {"name": inp.name, "L": inp.L, "f": inp.f,
+                              "feasible": [int(x) for x in t["feasible"]], "S": [int(x) for x in t["S"]],
+                              "T": [int(x) for x in t["T"]],
+                              "sha256": hashlib.sha256(PU.canonical_templates(t, cnt, inp.f)).hexdigest()}
+            print(f"instance {idx} L={inp.L} f={inp.f}: {time.time() - t0:.0f} s", flush=True)
+            json.dump({"source": "oracle/capi.plan on inputs.config(5); sha256 over "
+                                 "tests/parity_util.canonical_templates", "instances": done},
+                      open(path + ".tmp", "w"))
+            os.replace(path + ".tmp", path)
     elif which == "cfg4_exact":
         from oracle import exact_minimum
 

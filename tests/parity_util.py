@@ -4,6 +4,22 @@ import numpy as np
 TEMPLATE_KEYS = ("feasible", "S", "kstar", "T", "T1", "T2", "T3", "tmax")
 
 
+def canonical_templates(res: dict, count: int, f: int) -> bytes:
+    """Canonical byte form of everything compare_templates compares, for stored digests: the
+    per-template scalars, the stage lists of every template, the coverage header and array, and
+    the work counters."""
+    parts = [np.asarray(res[k])[:count].astype("<i8").tobytes() for k in TEMPLATE_KEYS]
+    off = np.asarray(res["stage_off"])[:count + 1].astype("<i8")
+    total = int(off[count])
+    parts.append(off.tobytes())
+    parts.append(np.asarray(res["stage_gpus"])[:total].astype("<i8").tobytes())
+    parts.append(np.asarray(res["stage_begin"])[:total + count].astype("<i8").tobytes())
+    parts.append(np.asarray(res["cover_hdr"]).astype("<i8").tobytes())
+    parts.append(np.asarray(res["cover_maxpipes"])[:max(count, f + 1)].astype("<i8").tobytes())
+    parts.append(np.array([res["states"], res["candidates"]], dtype="<i8").tobytes())
+    return b"".join(parts)
+
+
 def compare_templates(got: dict, want: dict, count: int):
     """Bit-exact: per-template scalars, stage lists, coverage, work counters."""
     assert int(got["status"][0]) == 0, f"device status {int(got['status'][0])}"

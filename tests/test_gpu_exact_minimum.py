@@ -40,6 +40,25 @@ def test_small_random_against_the_oracle(P, shape):
             assert st == P.OOB_OK and got == E.exact_minimum(inp), (shape, seed, var)
 
 
+def test_stage_times_that_are_not_monotone_in_the_last_layer(P):
+    """A stage that ends at the model's last layer pays no boundary term, so it can be faster than
+    the stage ending one layer earlier: the hand case of the oracle's pins (32, 20, 20), and small
+    times against boundary terms up to 5 on two hundred seeds."""
+    from test_oracle_exact_minimum import boundary_heavy_case
+
+    inp = boundary_heavy_case()
+    st, got = P.ExactMinimum(inp).run()
+    assert st == P.OOB_OK and got == [32, 20, 20] == E.exact_minimum(inp)
+    for seed in range(1000, 1200):
+        inp = inputs.random_small(seed, 6, 2, 1, 3, 8, t_lo=1, t_hi=4)
+        st, got = P.ExactMinimum(inp).run()
+        assert st == P.OOB_OK and got == E.exact_minimum(inp), seed
+    for seed in range(40):  # longer models, more GPUs per node
+        inp = inputs.random_small(2000 + seed, 14, 4, 1, 4, 16, t_lo=1, t_hi=3)
+        st, got = P.ExactMinimum(inp).run()
+        assert st == P.OOB_OK and got == E.exact_minimum(inp), seed
+
+
 @pytest.mark.parametrize("cfg", [1, 2, 3])
 def test_configurations_1_to_3(P, cfg):
     inp = inputs.config(cfg)
@@ -79,3 +98,21 @@ def test_status_for_negative_profile_entries(P):
     fwd[2, 0] = -5
     st, _ = P.ExactMinimum(dataclasses.replace(inp, fwd_ns=fwd)).run()
     assert st == P.OOB_EINVAL
+    # several workgroups' worth of (layer, GPU count) pairs, the bad entry in the last one
+    inp = inputs.random_small(3, 40, 4, 1, 3, 40)
+    fwd = inp.fwd_ns.copy()
+    fwd[39, 3] = -1
+    st, _ = P.ExactMinimum(dataclasses.replace(inp, fwd_ns=fwd)).run()
+    assert st == P.OOB_EINVAL
+
+
+def test_status_for_times_too_large_to_be_exact(P):
+    import dataclasses
+
+    inp = inputs.random_small(4, 8, 2, 1, 3, 8)
+    big = dataclasses.replace(inp, fwd_ns=inp.fwd_ns + (1 << 57))  # (N_b + 2) * 8 * 2^57 >= 2^61
+    st, _ = P.ExactMinimum(big).run()
+    assert st == P.OOB_EOVERFLOW
+    ok = dataclasses.replace(inp, fwd_ns=inp.fwd_ns + (1 << 50))
+    st, got = P.ExactMinimum(ok).run()
+    assert st == P.OOB_OK and got == E.exact_minimum(ok)

@@ -88,13 +88,17 @@ def test_largest_dimensions_the_entry_points_take(P):
     assert compare(P, sizes, 4000, 4095, 1) == 0          # two pipelines never fit
 
 
-def test_integer_table_path(P, monkeypatch):
+def test_integer_table_path(P):
     """Counts of 2^53 and more keep the table in int64 (no case the oracle could enumerate gets
-    there): the knob forces that path on ordinary cases."""
-    monkeypatch.setenv("OOB_TUNE_INST_INT64", "1")
-    assert compare(P, [2, 3, 4], 0, 13, 0) > 0
-    assert compare(P, None, 20, 48, 4, consecutive=(4, 29)) == 10251
-    assert compare(P, list(range(90, 130, 3)), 1000, 1100, 2) > 1000
+    there): the test hook forces that path on ordinary cases."""
+    lib = P.load()
+    assert lib.oob_inst_keep_wide_table(1) == 0
+    try:
+        assert compare(P, [2, 3, 4], 0, 13, 0) > 0
+        assert compare(P, None, 20, 48, 4, consecutive=(4, 29)) == 10251
+        assert compare(P, list(range(90, 130, 3)), 1000, 1100, 2) > 1000
+    finally:
+        assert lib.oob_inst_keep_wide_table(0) == 1
 
 
 def test_status_codes_and_capacity(P):

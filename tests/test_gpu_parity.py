@@ -292,31 +292,31 @@ def test_large_times_stay_exact_on_both_paths(P):
     planner.close()
 
 
-def test_plain_split_kernel(P, monkeypatch):
+def test_plain_split_kernel(P):
     """The tiled split kernel without keys serves shapes whose tables exceed the keyed kernel's
-    LDS classes (hundreds of nodes); the knob routes ordinary shapes through it."""
-    monkeypatch.setenv("OOB_TUNE_FORCE_PLAIN", "1")
+    LDS classes (hundreds of nodes); the handle option routes ordinary shapes through it."""
     for inp in (inputs.config(1), inputs.config(2),
                 inputs.random_small(3, 37, 3, 1, 5, 9, f=1, tight_mem=True),
                 inputs.random_small(4, 30, 3, 2, 30, 0, f=2),
                 inputs.random_small(21, 9, 2, 1, 3, 7, t_lo=(1 << 38), t_hi=(1 << 39))):
         print("plain", inp.name, inp.L, flush=True)
         planner = P.Planner(inp.L, inp.n_max, inp.gpus_per_node)
+        planner.set_option(P.OOB_OPT_PLAIN_SPLIT, 1)
         full_check(P, planner, inp)
         assert planner.flags()[:2] == [0, 1]
         planner.close()
 
 
-def test_xcd_chunked_task_order(P, monkeypatch):
+def test_xcd_chunked_task_order(P):
     """The other order of the workgroup tasks (block row by block row, each XCD walking one
     contiguous stretch of the list) computes the same tables."""
-    monkeypatch.setenv("OOB_TUNE_XCD", "1")
     for inp in (inputs.config(2), inputs.config(3),
                 inputs.random_small(3, 37, 3, 1, 5, 9, f=1, tight_mem=True),
                 inputs.random_small(5, 60, 2, 1, 6, 11, f=2),
                 inputs.random_small(4, 30, 3, 2, 30, 0, f=2)):
         print("xcd", inp.name, inp.L, flush=True)
         planner = P.Planner(inp.L, inp.n_max, inp.gpus_per_node)
+        planner.set_option(P.OOB_OPT_XCD_ORDER, 1)
         full_check(P, planner, inp)
         planner.close()
 

@@ -44,6 +44,40 @@ def test_hand_case():
     assert E.exact_minimum(inp) == [32, 20, 16, 13]
 
 
+def boundary_heavy_case():
+    """Four layers of time 2 on one GPU per node; the boundary term after layer 3 is 10, the others
+    0.  The stage [2, 3) costs 2 + 10 = 12, the model's last stage [2, 4) pays no boundary term and
+    costs 4: a longer stage that is FASTER than the one ending a layer earlier."""
+    from conftest import simple_input
+
+    return simple_input([2, 2, 2, 2], M=1, n_min=1, n_max=3, nb=4, bnd=[0, 0, 10, 0])
+
+
+def test_stage_times_are_not_monotone_in_the_last_layer():
+    """Worked with C = sum t + (N_b - S + k* - 1) t_max + sum_{k >= k*} t, N_b = 4:
+    one stage: t = 8: 8 + 2*8 + 8 = 32.
+    two stages: (2 | 6) -> 8 + 2*6 + 6 = 26; (4 | 4) -> 8 + 1*4 + 8 = 20;
+                (6+10 | 2) -> 18 + 1*16 + 18 = 52.                      minimum 20
+    three stages: (2, 2, 4) -> k* = 2: 8 + 2*4 + 4 = 20; (2, 4+10, 2) -> k* = 1: 18 + 1*14 + 16 = 48;
+                  (4, 2+10, 2) -> k* = 1: 18 + 1*12 + 14 = 44.          minimum 20
+    A search that stops at the first too-slow stage [2, 3) (12 > tau = 4) never sees [2, 4)."""
+    inp = boundary_heavy_case()
+    assert E.exact_minimum(inp) == [32, 20, 20]
+    for n in (1, 2, 3):
+        assert bf.brute_min(inp, n)[0] == [32, 20, 20][n - 1]
+
+
+def test_small_times_large_boundary_terms_against_exhaustive_enumeration():
+    """Times 1..4 with boundary terms 0..5: the boundary term often exceeds a layer, so stage times
+    go down when a stage grows to the model's end."""
+    for seed in range(1000, 1060):
+        inp = inputs.random_small(seed, 6, 2, 1, 3, 8, t_lo=1, t_hi=4)
+        got = E.exact_minimum(inp)
+        for n in range(1, 4):
+            b = bf.brute_min(inp, n)
+            assert got[n - 1] == (None if b is None else b[0]), (seed, n)
+
+
 def test_never_above_the_recursion_and_gap_on_the_configurations():
     for cfg in (1, 2, 3):
         inp = inputs.config(cfg)
