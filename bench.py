@@ -21,49 +21,85 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# Arithmetic per candidate split (s, k, m) in the int64 formulation of Eq. 1-3: 4 adds, one
-# 64-bit compare with 3 selects, one 64x32 multiply, one (cost, index) compare-and-select;
-# about 9 int64-class operations = 30 32-bit lane operations.  The kernels need fewer (6 fp64
-# vector instructions per executed candidate); the roofline figure is quoted on this
-# algorithmic count.
-OPS_PER_CANDIDATE = 30
-PEAK_LANE_OPS = 256 * 64 * 2.4e9  # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T 32-bit lane-ops/s
-# HBM bytes of the level kernels of one call on configuration 4, from the two rocprofv3 --pmc
-# runs (FETCH_SIZE, WRITE_SIZE) summarised in profiles/k_split_key_config4.md, scaled by what
-# the same counters read for a 256 MiB copy: 21.01 GB read + 5.72 GB written.
-# Vector-ALU wave-instructions the level kernels execute per call on configuration 4 (SQ_INSTS_VALU of
-# the same summary): what the hardware actually issues, as opposed to the algorithmic count above.
-VALU_WAVE_INSTS_PER_CALL_CONFIG4 = 4.06e9 + 0.09e9  # k_split_key + k_select
-HBM_BYTES_PER_CALL_CONFIG4 = 21.01e9 + 5.72e9
+# Arithmetic per candidate split (s, k, m) as the level kernels execute it (Eq. 1-3 with the child's
+# own total stored, every time an exact integer in a double): 2 adds, 1 compare, 2 selects, 1 min
+# = 6 fp64 vector instructions.  gfx950 issues fp64 add / min / compare / select at one lane
+# per SIMD lane and clock: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-instructions/s
+# (half of the 78.6 TFLOP/s quoted for fp64 FMA, which counts two flops per lane-instruction).
+# `roofline.frac` = structural candidates x 6 / time of the level launches / that peak.
+FP64_OPS_PER_CANDIDATE = 6
+PEAK_LANE_OPS = 256 * 64 * 2.4e9
+# The same work in the int64 formulation of Eq. 1-3 (4 adds, one 64-bit compare with 3 selects, one
+# 64x32 multiply, one (cost, index) compare-and-select: about 30 32-bit lane operations), kept as
+# a secondary figure under `int64_formulation` (how the run compares with an int64 kernel at the
+# 32-bit integer roof of the same 39.3 T lane-op/s; a ratio, not a roofline fraction).
+INT64_OPS_PER_CANDIDATE = 30
+# Constants copied from the tracked profile of the level kernels on configuration 4
+# (profiles/k_split_key_config4.md; not measured by this script): HBM bytes per call from the two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE over all level kernels, each scaled by what the same
+# counter reads for one 256 MiB device-to-device copy), and vector-ALU wave-instructions per call
+# (SQ_INSTS_VALU of k_split_key + k_select).
+PROFILE_CONFIG4 = {"source": "profiles/k_split_key_config4.md",
+                   "hbm_read_bytes_per_call": 21.01e9, "hbm_written_bytes_per_call": 5.72e9,
+                   "valu_wave_insts_per_call": 4.06e9 + 0.09e9}
+
+
+def median(xs):
+    xs = sorted(xs)
+    return xs[len(xs) // 2]
 
 
 def cpu_baseline(inp):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: all host threads
-    on (most of) the workload, and one thread on the two smallest templates."""
+    on the templates for the smaller half of the node counts, and one thread on the two smallest
+    templates; each the median of three runs."""
     from oracle import capi
 
     cores = capi.lib().oob_oracle_threads()
-    # about 15 s of oracle time on 16 cores for the whole headline workload; fewer cores take
-    # the first nine node counts only
-    sample = inp if cores >= 16 else dataclasses.replace(inp, n_max=min(inp.n_max, 16))
-    t0 = time.time()
-    o = capi.Oracle(sample)
-    dt = time.time() - t0
-    res = {"value": o.states / dt, "unit": "states/s", "cores": cores,
-           "kind": "oracle", "seconds": round(dt, 2), "candidates_per_s": o.candidates / dt,
+    sample = dataclasses.replace(inp, n_max=min(inp.n_max, 32 if cores >= 16 else 16))
+
+    def timed(job, threads):
+        runs = []
+        for _ in range(3):
+            t0 = time.time()
+            o = capi.Oracle(job, threads=threads)
+            runs.append((time.time() - t0, o.states, o.candidates))
+            o.close()
+        return median(runs), [round(r[0], 2) for r in runs]
+
+    (dt, states, cands), runs = timed(sample, 0)
+    res = {"value": states / dt, "unit": "states/s", "cores": cores,
+           "kind": "oracle", "seconds": round(dt, 2), "runs_seconds": runs, "candidates_per_s": cands / dt,
            "sample": f"same profile, templates for {sample.n_min}..{sample.n_max} nodes: "
-                     f"{o.states} states, {o.candidates} candidates"}
-    o.close()
+                     f"{states} states, {cands} candidates; median of 3 runs"}
     one = dataclasses.replace(inp, n_max=min(inp.n_max, inp.n_min + 1))
-    t0 = time.time()
-    o = capi.Oracle(one, threads=1)
-    dt = time.time() - t0
-    res["single_thread"] = {"value": o.states / dt, "unit": "states/s", "cores": 1, "seconds": round(dt, 2),
-                            "candidates_per_s": o.candidates / dt,
-                            "sample": f"templates for {one.n_min}..{one.n_max} nodes: {o.states} states, "
-                                      f"{o.candidates} candidates"}
-    o.close()
+    (dt, states, cands), runs = timed(one, 1)
+    res["single_thread"] = {"value": states / dt, "unit": "states/s", "cores": 1, "seconds": round(dt, 2),
+                            "runs_seconds": runs, "candidates_per_s": cands / dt,
+                            "sample": f"templates for {one.n_min}..{one.n_max} nodes: {states} states, "
+                                      f"{cands} candidates; median of 3 runs"}
     return res
+
+
+def call_latency(P, planner, inp, reps=7):
+    """One call at a time, from a profile in host memory to the results in host memory: the four
+    profile arrays are copied to the device, oob_plan_templates is enqueued, and the host waits for
+    the templates, the stage lists and the coverage to arrive (wall clock around all of it)."""
+    import torch
+
+    out = planner.new_outputs(inp)
+    times = []
+    for _ in range(reps + 1):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        prof = P.DeviceProfile(inp)
+        planner.enqueue(prof, out)
+        res = out.to_host()
+        times.append((time.perf_counter() - t0) * 1e3)
+        assert int(res["status"][0]) == 0
+    return {"median": median(times[1:]), "min": min(times[1:]), "max": max(times[1:]), "calls": reps,
+            "what": "host clock: H2D of the profile, all kernels of one oob_plan_templates call, D2H of every "
+                    "result array; one call at a time, first call dropped"}
 
 
 def bench_instantiation(P, inp, res, reps=20):
@@ -183,9 +219,8 @@ def bench_distribution(P, inp, res, Q=512, reps=3, oracle_sample=40):
     torch.cuda.synchronize()
     dt = ev[0].elapsed_time(ev[1]) / reps * 1e-3
     status, vx, slow, base, extra = d.solve()
-    t0 = time.perf_counter()
     best = d.choose(off)
-    t_choose = time.perf_counter() - t0
+    t_choose = d.time_choose(off)
     assert (status == P.OOB_DIST_OK).all(), "distribution"
     X = x.cpu().numpy().view("uint16").T
     rng = np.random.Generator(np.random.PCG64(1))
@@ -198,7 +233,7 @@ def bench_distribution(P, inp, res, Q=512, reps=3, oracle_sample=40):
     nbytes = total * (6.0 * p + 28)
     return {"workload": f"all {total} plans of template sizes {n0}..{n_hi}, f={inp.f}, N'={(inp.f + 1) * n0}..{N}; "
                         f"{Q} microbatches; time per microbatch = T1 of the template",
-            "value": total / dt, "unit": "plans/s", "ms": dt * 1e3, "choose_ms_with_sync": t_choose * 1e3,
+            "value": total / dt, "unit": "plans/s", "ms": dt * 1e3, "choose_us": t_choose * 1e6,
             "best_plan_for_all_nodes": X[int(best[-1])].nonzero()[0].tolist() if best[-1] >= 0 else None,
             "roofline": {"bound": "hbm", "achieved": nbytes / dt / 1e9, "peak": 8000.0, "unit": "GB/s",
                          "frac": nbytes / dt / 8e12, "traffic": None, "kernel": "k_dist_solve",
@@ -282,7 +317,7 @@ def bench_batch(P, insts, args):
     assert all(int(o.t["status"].item()) == 0 for o in outs), "device status"
     states = sum(o.c.states for o in outs)
     cands = sum(o.c.candidates for o in outs)
-    achieved = cands * OPS_PER_CANDIDATE * args.steps / elapsed
+    achieved = cands * FP64_OPS_PER_CANDIDATE * args.steps / elapsed
     print(json.dumps({
         "metric": "DP states/sec (wall-ms per batch of 256 instances in ms_per_step)",
         "value": states * args.steps / elapsed, "unit": "states/s", "n_gpus": 1, "steps": args.steps,
@@ -293,9 +328,9 @@ def bench_batch(P, insts, args):
                    "lanes": args.lanes,
                    "states": states, "candidates": cands},
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12,
-                     "unit": "T lane-op/s", "frac": achieved / PEAK_LANE_OPS, "traffic": None,
+                     "unit": "T fp64 lane-instr/s", "frac": achieved / PEAK_LANE_OPS, "traffic": None,
                      "kernel": "whole batched call (all kernels, host enqueue included)",
-                     "ops_per_candidate": OPS_PER_CANDIDATE}}))
+                     "ops_per_candidate": FP64_OPS_PER_CANDIDATE}}))
 
 
 def main():
@@ -367,9 +402,9 @@ def main():
     Smax = P.oob_plan_max_stages(inp.L, inp.n_max, inp.gpus_per_node, inp.microbatches)
     launches = max(1, Smax - 1)
     lvl_ms = sum(level_ms) / len(level_ms)
-    achieved = cands * OPS_PER_CANDIDATE / (lvl_ms * 1e-3)
+    achieved = cands * FP64_OPS_PER_CANDIDATE / (lvl_ms * 1e-3)
     measured_peak = planner.valu_peak()  # add / compare / select microbenchmark on this GPU
-    traffic = HBM_BYTES_PER_CALL_CONFIG4 / launches if args.config == 4 else None
+    prof4 = PROFILE_CONFIG4 if args.config == 4 and not args.paper_nb else None
     line = {
         "metric": "DP states/sec (wall-ms per full template set in ms_per_step)",
         "value": states * args.steps / elapsed,
@@ -383,17 +418,28 @@ def main():
                                f"templates n={inp.n_min}..{inp.n_max} x {inp.gpus_per_node} GPUs, "
                                f"N_b={inp.microbatches if inp.microbatches else '4S (per state)'}, f={inp.f}",
                    "states": states, "candidates": cands, "levels": Smax},
+        "latency_ms": call_latency(P, planner, inp),
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12,
-                     "unit": "T lane-op/s", "frac": achieved / PEAK_LANE_OPS, "traffic": traffic,
-                     "measured_peak": measured_peak / 1e12, "frac_of_measured_peak": achieved / measured_peak,
-                     "frac_at_6_ops_per_candidate": cands * 6 / (lvl_ms * 1e-3) / PEAK_LANE_OPS,
-                     "valu_issue_utilisation": (VALU_WAVE_INSTS_PER_CALL_CONFIG4 * 4 / (1024 * 2.4e9 * lvl_ms * 1e-3)
-                                                if args.config == 4 else None),
+                     "unit": "T fp64 lane-instr/s", "frac": achieved / PEAK_LANE_OPS,
+                     "traffic": ((prof4["hbm_read_bytes_per_call"] + prof4["hbm_written_bytes_per_call"]) / launches
+                                 if prof4 else None),
                      "traffic_unit": "HBM bytes per level (one launch group), rocprofv3 --pmc",
-                     "kernel": "level kernels S'>=2 (divide/combine, Eq. 1-3)",
-                     "ops_per_candidate": OPS_PER_CANDIDATE, "launches": launches,
+                     "kernel": "level kernels S'>=2 (divide/combine, Eq. 1-3): k_split_key + k_select",
+                     "ops_per_candidate": FP64_OPS_PER_CANDIDATE, "launches": launches,
                      "avg_launch_ms": lvl_ms / launches, "levels_ms_per_step": lvl_ms,
-                     "candidates_per_s": cands / (lvl_ms * 1e-3)},
+                     "candidates_per_s": cands / (lvl_ms * 1e-3),
+                     "measured_peak_int32": measured_peak / 1e12,
+                     "int64_formulation": {"ops_per_candidate": INT64_OPS_PER_CANDIDATE,
+                                           "lane_ops_per_s": cands * INT64_OPS_PER_CANDIDATE / (lvl_ms * 1e-3) / 1e12,
+                                           "ratio_to_int32_peak": cands * INT64_OPS_PER_CANDIDATE / (lvl_ms * 1e-3)
+                                                                  / PEAK_LANE_OPS,
+                                           "note": "a ratio to an int64 kernel running at the roof, not a "
+                                                   "roofline fraction"},
+                     "from_profile": ({"source": prof4["source"], "constants_not_measured_in_this_run": True,
+                                       "valu_issue_utilisation": prof4["valu_wave_insts_per_call"] * 4
+                                                                 / (1024 * 2.4e9 * lvl_ms * 1e-3),
+                                       "valu_lane_insts_per_candidate": prof4["valu_wave_insts_per_call"] * 64 / cands}
+                                      if prof4 else None)},
     }
     line["instantiation"] = bench_instantiation(P, inp, res)
     line["reconfiguration"] = bench_reconfiguration(P, inp, res)

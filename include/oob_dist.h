@@ -64,10 +64,13 @@ int oob_dist_solve(const uint16_t *x, int64_t count, int64_t capacity, int p, co
 /* Chooses, for each of `segments` consecutive groups of plans (offsets[g] .. offsets[g+1]-1, the
  * offsets array of oob_inst_count: one group per cluster size N'), the plan with the smallest
  * `slowest` among those with status OOB_DIST_OK, the first of equals.
- *   best  [segments] out: index of the chosen plan, -1 if the group has none
+ *   count  number of plans the groups cover at most (offsets[segments] - offsets[0] <= count; the
+ *          count given to oob_dist_solve): sizes the launch, the groups themselves are read on
+ *          the device; plans beyond offsets[segments] are ignored
+ *   best   [segments] out: index of the chosen plan, -1 if the group has none
  * Requires oob_dist_solve earlier on the same stream (or completed). */
-int oob_dist_choose(const int64_t *offsets, int segments, const int64_t *slowest, const int32_t *status,
-                    int64_t *best, void *stream);
+int oob_dist_choose(const int64_t *offsets, int segments, int64_t count, const int64_t *slowest,
+                    const int32_t *status, int64_t *best, void *stream);
 
 #ifdef __cplusplus
 }

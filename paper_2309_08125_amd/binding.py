@@ -102,7 +102,7 @@ def load():
         L.oob_dist_solve.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_int, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.oob_dist_solve.restype = C.c_int
-        L.oob_dist_choose.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oob_dist_choose.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.oob_dist_choose.restype = C.c_int
         L.oob_exact_workspace_size.argtypes = [C.c_int] * 3
         L.oob_exact_workspace_size.restype = C.c_size_t
@@ -194,8 +194,8 @@ def oob_dist_solve(x_ptr, count, capacity, p, template_T_ptr, Q, vx_ptr, slowest
                                  C.c_void_p(extra_ptr), C.c_void_p(status_ptr), C.c_void_p(stream_ptr))
 
 
-def oob_dist_choose(offsets_ptr, segments, slowest_ptr, status_ptr, best_ptr, stream_ptr) -> int:
-    return load().oob_dist_choose(C.c_void_p(offsets_ptr), segments, C.c_void_p(slowest_ptr),
+def oob_dist_choose(offsets_ptr, segments, count, slowest_ptr, status_ptr, best_ptr, stream_ptr) -> int:
+    return load().oob_dist_choose(C.c_void_p(offsets_ptr), segments, count, C.c_void_p(slowest_ptr),
                                   C.c_void_p(status_ptr), C.c_void_p(best_ptr), C.c_void_p(stream_ptr))
 
 
@@ -556,10 +556,29 @@ class Distributor:
         off = torch.from_numpy(np.asarray(offsets, dtype=np.int64)).to(self.device)
         best = torch.full((len(offsets) - 1,), -99, dtype=torch.int64, device=self.device)
         s = torch.cuda.current_stream(self.device)
-        check(oob_dist_choose(off.data_ptr(), len(offsets) - 1, self.slowest.data_ptr(), self.status.data_ptr(),
-                              best.data_ptr(), s.cuda_stream), "oob_dist_choose")
+        check(oob_dist_choose(off.data_ptr(), len(offsets) - 1, self.count, self.slowest.data_ptr(),
+                              self.status.data_ptr(), best.data_ptr(), s.cuda_stream), "oob_dist_choose")
         torch.cuda.synchronize(self.device)
         return best.cpu().numpy()
+
+    def time_choose(self, offsets, reps: int = 20) -> float:
+        """Seconds per oob_dist_choose call, from events on the stream the kernels are launched on."""
+        import numpy as np
+        import torch
+
+        off = torch.from_numpy(np.asarray(offsets, dtype=np.int64)).to(self.device)
+        best = torch.full((len(offsets) - 1,), -99, dtype=torch.int64, device=self.device)
+        s = torch.cuda.current_stream(self.device)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        args = (off.data_ptr(), len(offsets) - 1, self.count, self.slowest.data_ptr(), self.status.data_ptr(),
+                best.data_ptr(), s.cuda_stream)
+        check(oob_dist_choose(*args), "oob_dist_choose")
+        ev[0].record(s)
+        for _ in range(reps):
+            check(oob_dist_choose(*args), "oob_dist_choose")
+        ev[1].record(s)
+        torch.cuda.synchronize(self.device)
+        return ev[0].elapsed_time(ev[1]) / reps * 1e-3
 
 
 def template_stages(r: dict, i: int):

@@ -214,23 +214,61 @@ __global__ void __launch_bounds__(kLanes) k_dist_solve(Args a) {
     a.slowest[i] = slow;
 }
 
-// One workgroup (one wave) per group of plans: the smallest `slowest` among the solved plans, the
-// first of equals.
-constexpr int kChooseLanes = 64;
-__global__ void __launch_bounds__(kChooseLanes) k_dist_choose(const long long *offsets, const long long *slowest,
-                                                        const int *status, long long *best) {
-    __shared__ long long s_v[kChooseLanes], s_i[kChooseLanes];
-    const int lane = threadIdx.x;
-    const long long lo = offsets[blockIdx.x], hi = offsets[blockIdx.x + 1];
-    long long bv = 0, bi = -1;
-    for (long long i = lo + lane; i < hi; i += kChooseLanes) // ascending: a lane keeps its first minimum
-        if (status[i] == OOB_DIST_OK && (bi < 0 || slowest[i] < bv)) { bv = slowest[i]; bi = i; }
-    s_v[lane] = bv; s_i[lane] = bi;
-    __syncthreads();
-    if (lane == 0) {
-        for (int l = 1; l < kChooseLanes; ++l)
-            if (s_i[l] >= 0 && (bi < 0 || s_v[l] < bv || (s_v[l] == bv && s_i[l] < bi))) { bv = s_v[l]; bi = s_i[l]; }
-        best[blockIdx.x] = bi;
+// Plan choice: the smallest `slowest` among the solved plans of a group, the first of equals.
+// A workgroup reduces one chunk of kChooseChunk consecutive plans of one group (lanes keep the
+// first minimum of their strided share, waves and then the workgroup combine (value, index) pairs
+// lexicographically) and merges its winner into best[group] with a compare-and-swap on the index:
+// `slowest` does not change during the launch, so "is plan i better than the plan best[group]
+// names now" is decided by reading both values, and the loop ends as soon as the entry names a plan
+// that is at least as good.  k_dist_choose_init sets every entry to -1 ("no plan") first.
+constexpr int kChooseThreads = 256, kChooseChunk = 2048;
+__global__ void k_dist_choose_init(long long *best, int segments) {
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g < segments) best[g] = -1;
+}
+__device__ __forceinline__ bool better(long long v, long long i, long long bv, long long bi) {
+    return i >= 0 && (bi < 0 || v < bv || (v == bv && i < bi));
+}
+__global__ void __launch_bounds__(kChooseThreads) k_dist_choose(const long long *offsets, int segments,
+                                                          const long long *slowest, const int *status,
+                                                          long long *best) {
+    __shared__ long long s_v[kChooseThreads / 64], s_i[kChooseThreads / 64];
+    // this workgroup's chunk of the plans, cut to the plans the groups cover
+    long long lo = offsets[0] + (long long)blockIdx.x * kChooseChunk;
+    const long long all = offsets[segments], hi = lo + kChooseChunk < all ? lo + kChooseChunk : all;
+    if (lo >= hi) return; // the same for the whole workgroup
+    int g = 0;            // last group that starts at or before lo (empty groups before it are skipped)
+    for (int a = 0, b = segments - 1; a <= b;) {
+        const int mid = (a + b) >> 1;
+        if (offsets[mid] <= lo) { g = mid; a = mid + 1; } else b = mid - 1;
+    }
+    for (; g < segments && lo < hi; ++g) { // every group that has plans in the chunk (uniform loop)
+        const long long gend = offsets[g + 1], end = gend < hi ? gend : hi;
+        if (end <= lo) continue;
+        long long bv = 0, bi = -1;
+        for (long long i = lo + threadIdx.x; i < end; i += kChooseThreads) // ascending: a lane keeps its first minimum
+            if (status[i] == OOB_DIST_OK && (bi < 0 || slowest[i] < bv)) { bv = slowest[i]; bi = i; }
+        for (int d = 32; d >= 1; d >>= 1) {
+            const long long ov = __shfl_down(bv, d, 64), oi = __shfl_down(bi, d, 64);
+            if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+        }
+        __syncthreads(); // the previous group's partial results have been read
+        if ((threadIdx.x & 63) == 0) { s_v[threadIdx.x >> 6] = bv; s_i[threadIdx.x >> 6] = bi; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int w = 1; w < kChooseThreads / 64; ++w)
+                if (better(s_v[w], s_i[w], bv, bi)) { bv = s_v[w]; bi = s_i[w]; }
+            if (bi >= 0) {
+                unsigned long long *slot = (unsigned long long *)&best[g];
+                long long cur = (long long)atomicAdd(slot, 0ull); // coherent read of the entry
+                while (better(bv, bi, cur >= 0 ? slowest[cur] : 0, cur)) {
+                    const long long seen = (long long)atomicCAS(slot, (unsigned long long)cur, (unsigned long long)bi);
+                    if (seen == cur) break;
+                    cur = seen;
+                }
+            }
+        }
+        lo = end;
     }
 }
 
@@ -252,12 +290,17 @@ extern "C" int oob_dist_solve(const uint16_t *x, int64_t count, int64_t capacity
     return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
 }
 
-extern "C" int oob_dist_choose(const int64_t *offsets, int segments, const int64_t *slowest, const int32_t *status,
-                               int64_t *best, void *stream) {
+extern "C" int oob_dist_choose(const int64_t *offsets, int segments, int64_t count, const int64_t *slowest,
+                               const int32_t *status, int64_t *best, void *stream) {
     using namespace oob_dist;
-    if (!offsets || !slowest || !status || !best || segments < 0) return OOB_EINVAL;
+    if (!offsets || !slowest || !status || !best || segments < 0 || count < 0) return OOB_EINVAL;
     if (segments == 0) return OOB_OK;
-    hipLaunchKernelGGL(k_dist_choose, dim3((unsigned)segments), dim3(kChooseLanes), 0, (hipStream_t)stream,
-                       (const long long *)offsets, (const long long *)slowest, status, (long long *)best);
+    const long long chunks = (count + kChooseChunk - 1) / kChooseChunk;
+    if (chunks > 0x7fffffffll) return OOB_EINVAL;
+    hipLaunchKernelGGL(k_dist_choose_init, dim3((unsigned)((segments + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       (long long *)best, segments);
+    if (chunks > 0)
+        hipLaunchKernelGGL(k_dist_choose, dim3((unsigned)chunks), dim3(kChooseThreads), 0, (hipStream_t)stream,
+                           (const long long *)offsets, segments, (const long long *)slowest, status, (long long *)best);
     return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
 }

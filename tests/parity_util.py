@@ -56,9 +56,16 @@ def compare_block(gblk: dict, oblk: dict, S: int, L: int):
     uu, vv = np.broadcast_to(u, (n, n))[ex], np.broadcast_to(v, (n, n))[ex]
     for key in ("T", "T1", "T3", "tmax"):
         g = gblk[key][ex]
-        assert np.all(g == np.floor(g)) and np.all(np.abs(g) < 2.0**53)
+        bad = ~((g == np.floor(g)) & (np.abs(g) < 2.0**53))
+        if bad.any():
+            i = int(np.flatnonzero(bad)[0])
+            raise AssertionError(f"{key} is not an exact integer at S'={S} u={int(uu[i])} v={int(vv[i])}: "
+                                 f"{g[i]!r} (oracle {int(oblk[key][uu[i], vv[i]])}); {int(bad.sum())} such records")
         w = oblk[key][uu, vv]
-        assert np.array_equal(g.astype(np.int64), w), f"{key} differs at S'={S}"
+        if not np.array_equal(g.astype(np.int64), w):
+            i = int(np.flatnonzero(g.astype(np.int64) != w)[0])
+            raise AssertionError(f"{key} differs at S'={S} u={int(uu[i])} v={int(vv[i])}: {int(g[i])} vs oracle "
+                                 f"{int(w[i])}; {int((g.astype(np.int64) != w).sum())} such records")
     assert np.array_equal(gblk["kstar"][ex], oblk["kstar"][uu, vv]), f"kstar differs at S'={S}"
     if S > 1:
         ch = gblk["choice"][ex]

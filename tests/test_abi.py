@@ -101,10 +101,11 @@ def test_distribution_entry_points_validate_arguments_without_touching_the_gpu()
                 dict(base=fake), dict(extra=fake)):
         assert solve(**bad) == P.OOB_EINVAL, bad
     assert solve(count=0, capacity=0) == P.OOB_OK
-    assert P.oob_dist_choose(0, 1, fake, fake, fake, 0) == P.OOB_EINVAL
-    assert P.oob_dist_choose(fake, -1, fake, fake, fake, 0) == P.OOB_EINVAL
-    assert P.oob_dist_choose(fake, 1, fake, fake, 0, 0) == P.OOB_EINVAL
-    assert P.oob_dist_choose(fake, 0, fake, fake, fake, 0) == P.OOB_OK
+    assert P.oob_dist_choose(0, 1, 1, fake, fake, fake, 0) == P.OOB_EINVAL
+    assert P.oob_dist_choose(fake, -1, 1, fake, fake, fake, 0) == P.OOB_EINVAL
+    assert P.oob_dist_choose(fake, 1, -1, fake, fake, fake, 0) == P.OOB_EINVAL
+    assert P.oob_dist_choose(fake, 1, 1, fake, fake, 0, 0) == P.OOB_EINVAL
+    assert P.oob_dist_choose(fake, 0, 1, fake, fake, fake, 0) == P.OOB_OK
 
 
 def test_max_stages_and_workspace_size():
