@@ -66,6 +66,26 @@ int oob_inst_enumerate(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, 
                        uint16_t *x, int64_t capacity, const int64_t *offsets, int32_t *status,
                        void *stream);
 
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight serving
+ * loops, harnesses that forbid it: oob_inst_count followed by oob_inst_enumerate as ONE call that
+ * takes no workspace.  The count table lives in an array of OOB_INST_STATIC_BYTES bytes that is
+ * part of the library's code object: every GPU the library runs on holds it from the first use
+ * until the process ends, and no hipMalloc, hipFree or other allocating routine is called.
+ *   sizes, p, n0, N_lo, N_hi, f, x, capacity, status, stream   as for the two calls above
+ *   offsets   [N_hi-N_lo+2] OUT (written by this call, read by its second kernel)
+ * Returns OOB_ECAPACITY, and enqueues nothing, when oob_inst_workspace_size(p, N_hi, f) exceeds
+ * OOB_INST_STATIC_BYTES (the headline node specification, 57 sizes up to 128 nodes with f = 8, needs
+ * 1 MB); OOB_EINVAL / OOB_EHIP as above.  *status as for oob_inst_enumerate: OOB_ECAPACITY when the
+ * total exceeds `capacity` (offsets are still valid, x is untouched), else the vectors are in x.
+ * The first call on a GPU looks the array's address up (make it outside a graph capture).  All
+ * calls on one GPU share the one array: calls that overlap in time on the same GPU (different
+ * streams, or another thread) race and must be serialised by the caller; results of a completed
+ * call do not depend on what earlier calls left in the array. */
+#define OOB_INST_STATIC_BYTES (4u << 20)
+int oob_inst_enumerate_static(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, int f,
+                              uint16_t *x, int64_t capacity, int64_t *offsets, int32_t *status,
+                              void *stream);
+
 /* Test hook (process-wide): on != 0 makes oob_inst_count keep the table in 64 bits even when every
  * count is below 2^32, so that the path for longer lists can be exercised on cases small enough
  * to enumerate.  Results are identical either way.  Returns the previous setting. */

@@ -9,4 +9,5 @@ from .binding import (  # noqa: F401
     OOB_DIST_OK, OOB_DIST_TOO_FEW_MICROBATCHES, OOB_DIST_TOO_MANY_TEMPLATES, OOB_DIST_BAD_TIME, OOB_DIST_NO_PIPELINE,
     RECONF_ROWS, RECONF_SYMBOLS, FailureSimulator, oob_reconf_simulate,
     INST_SYMBOLS, Instantiator, oob_inst_count, oob_inst_enumerate, oob_inst_workspace_size,
+    OOB_INST_STATIC_BYTES, oob_inst_enumerate_static,
 )

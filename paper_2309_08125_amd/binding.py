@@ -23,7 +23,9 @@ SYMBOLS = ["oob_plan_max_stages", "oob_plan_workspace_size", "oob_plan_create",
            "oob_plan_level_timing", "oob_plan_last_level_ms", "oob_plan_export_flags", "oob_plan_valu_peak",
            "oob_plan_set_option"]
 OOB_OPT_PLAIN_SPLIT, OOB_OPT_XCD_ORDER, OOB_OPT_ONE_STREAM = 1, 2, 3
-INST_SYMBOLS = ["oob_inst_workspace_size", "oob_inst_count", "oob_inst_enumerate", "oob_inst_keep_wide_table"]
+INST_SYMBOLS = ["oob_inst_workspace_size", "oob_inst_count", "oob_inst_enumerate", "oob_inst_keep_wide_table",
+                "oob_inst_enumerate_static"]
+OOB_INST_STATIC_BYTES = 4 << 20
 RECONF_SYMBOLS = ["oob_reconf_simulate"]
 DIST_SYMBOLS = ["oob_dist_solve", "oob_dist_choose"]
 EXACT_SYMBOLS = ["oob_exact_workspace_size", "oob_exact_minimum"]
@@ -86,6 +88,9 @@ def load():
         L.oob_plan_valu_peak.restype = C.c_int
         L.oob_plan_set_option.argtypes = [C.c_void_p, C.c_int, C.c_int]
         L.oob_plan_set_option.restype = C.c_int
+        L.oob_inst_enumerate_static.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                                C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oob_inst_enumerate_static.restype = C.c_int
         L.oob_inst_keep_wide_table.argtypes = [C.c_int]
         L.oob_inst_keep_wide_table.restype = C.c_int
         L.oob_inst_workspace_size.argtypes = [C.c_int] * 3
@@ -178,6 +183,12 @@ def oob_inst_enumerate(sizes_ptr, p, n0, N_lo, N_hi, f, dev_workspace_ptr, works
                                      C.c_void_p(dev_workspace_ptr), workspace_bytes, C.c_void_p(x_ptr),
                                      capacity, C.c_void_p(offsets_ptr), C.c_void_p(status_ptr),
                                      C.c_void_p(stream_ptr))
+
+
+def oob_inst_enumerate_static(sizes_ptr, p, n0, N_lo, N_hi, f, x_ptr, capacity, offsets_ptr, status_ptr,
+                              stream_ptr) -> int:
+    return load().oob_inst_enumerate_static(C.c_void_p(sizes_ptr), p, n0, N_lo, N_hi, f, C.c_void_p(x_ptr), capacity,
+                                            C.c_void_p(offsets_ptr), C.c_void_p(status_ptr), C.c_void_p(stream_ptr))
 
 
 def oob_reconf_simulate(sizes0_ptr, c0, n0, n_hi, f, draws_ptr, steps, burst, T, trace_ptr, final_sizes_ptr,

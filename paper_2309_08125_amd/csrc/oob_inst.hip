@@ -16,6 +16,7 @@
 #include <stdlib.h>
 
 #include <atomic>
+#include <mutex>
 #include <type_traits>
 
 #include "oob_inst.h"
@@ -275,6 +276,31 @@ static int launch_unrank(const Spec &s, const int64_t *offsets, int32_t *status,
     return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
 }
 
+// The count table of oob_inst_enumerate_static: one array per GPU, part of the loaded code object
+// (so nothing is ever allocated for it), held until the process ends.  `scratch` itself is a
+// host-side stand-in, not a device address: host code uses the address hipGetSymbolAddress reports
+// for the current device, looked up once per device.
+static __device__ __align__(256) unsigned char scratch[OOB_INST_STATIC_BYTES];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[kMaxDevices];
+
+static int static_table(void **ws) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return OOB_EHIP;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return OOB_EHIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *ws = g_scratch_ptr[dev];
+    return OOB_OK;
+}
+
 } // namespace oob_inst
 
 extern "C" {
@@ -304,6 +330,25 @@ int oob_inst_enumerate(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, 
                               status, &s);
     if (rc != OOB_OK) return rc;
     if (capacity < 0 || (capacity > 0 && !x)) return OOB_EINVAL;
+    return launch_unrank(s, offsets, status, x, capacity, (hipStream_t)stream);
+}
+
+int oob_inst_enumerate_static(const int32_t *sizes, int p, int n0, int N_lo, int N_hi, int f, uint16_t *x,
+                              int64_t capacity, int64_t *offsets, int32_t *status, void *stream) {
+    using namespace oob_inst;
+    if (!args_ok(p, N_lo, N_hi, f) || !offsets || !status || (!sizes && n0 < 1)) return OOB_EINVAL;
+    if (capacity < 0 || (capacity > 0 && !x)) return OOB_EINVAL;
+    if (table_bytes(p, N_hi, f) > OOB_INST_STATIC_BYTES) return OOB_ECAPACITY;
+    void *ws = nullptr;
+    const int rs = static_table(&ws);
+    if (rs != OOB_OK) return rs;
+    Spec s;
+    const int rc = check_spec(sizes, p, n0, N_lo, N_hi, f, ws, OOB_INST_STATIC_BYTES, offsets, status, &s);
+    if (rc != OOB_OK) return rc;
+    // every entry of the table that is read is written by the counting kernel first: nothing of the
+    // previous call's contents survives into this one, and nothing has to be cleared
+    const int rl = launch_count(s, offsets, status, (hipStream_t)stream);
+    if (rl != OOB_OK) return rl;
     return launch_unrank(s, offsets, status, x, capacity, (hipStream_t)stream);
 }
 

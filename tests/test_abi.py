@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, name), name
     assert sorted(B.SYMBOLS) == names
     inst = declared_symbols("oob_inst.h", "oob_inst_")
-    assert len(inst) == 4
+    assert len(inst) == 5
     for name in inst:
         assert hasattr(lib, name), name
     assert sorted(B.INST_SYMBOLS) == inst
