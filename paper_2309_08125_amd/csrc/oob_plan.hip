@@ -395,7 +395,7 @@ __device__ __forceinline__ void stage_store(const Stage &g, double2 *pair, doubl
 
 // Candidate slots an assignment of roles executes: per block of eight stationary unit counts the
 // streaming range that pairs with it (targets a0..a1), times eight.
-__device__ __forceinline__ int role_cost(int y0, int y1, int q0, int q1, int a0, int a1) {
+__host__ __device__ __forceinline__ int role_cost(int y0, int y1, int q0, int q1, int a0, int a1) {
     int c = 0;
     for (int qb = q0; qb <= q1; qb += 8) {
         const int lo = imax(y0, a0 - (qb + 7)), hi = imin(y1, a1 - qb);
@@ -1057,8 +1057,10 @@ static hipEvent_t borrow_event() {
 constexpr int kMaxLanes = 8;
 struct Lane {
     hipStream_t main = nullptr;       // lanes >= 1: borrowed; lane 0 runs on the caller's stream
-    hipStream_t aux = nullptr;        // second stream for the odd levels, borrowed (null: one stream)
-    std::vector<hipEvent_t> ev_level; // [S'] "level S' selected", borrowed; ev_level[0]: fork
+    hipStream_t aux = nullptr;        // streams for the inner splits of the even / odd levels, borrowed
+    hipStream_t aux2 = nullptr;       // (null: everything on one stream)
+    std::vector<hipEvent_t> ev_level; // [2 S'] "level S' selected", [2 S' + 1] "inner splits of level S' done",
+                                      // borrowed
     hipEvent_t ev_join = nullptr;     // lanes >= 1: end of the lane's work in a batch, borrowed
 };
 
@@ -1133,6 +1135,7 @@ extern "C" int oob_plan_destroy(oob_plan *h) {
             for (hipEvent_t e : ln.ev_level) p.events.push_back(e);
             if (ln.ev_join) p.events.push_back(ln.ev_join);
             if (ln.aux) p.streams.push_back(ln.aux);
+            if (ln.aux2) p.streams.push_back(ln.aux2);
             if (ln.main) p.streams.push_back(ln.main);
         }
         if (h->ev_fork) p.events.push_back(h->ev_fork);
@@ -1173,15 +1176,39 @@ static bool out_ok(const oob_templates *o) {
 
 // The splits s0, s0 + sstep, ... (scount of them) of level S.
 struct SplitRange { int s0, sstep, scount; };
+// Waves per workgroup of a keyed launch: as many as the split with the most work items (8-blocks of
+// the stationary side) offers per split point, at most kKeyWaves.  The low levels have one or two
+// items per split point: more waves would only idle at the barriers and take up residency.
+static int waves_for(const Shape &sh, int S, int fam, const SplitPlan &sp, SplitRange sr) {
+    int t_lo, t_hi;
+    target_units(fam, S, sh.M, sh.n_max, &t_lo, &t_hi);
+    int most = 1;
+    for (int i = 0; i < sr.scount; ++i) {
+        const int s = sr.s0 + i * sr.sstep, r = S - s;
+        int A_lo, A_hi, B_lo, B_hi;
+        child_units(fam, s, sh.M, sh.n_max, &A_lo, &A_hi);
+        child_units(fam, r, sh.M, sh.n_max, &B_lo, &B_hi);
+        for (int g = 0; g < sp.groups; ++g) {
+            const int a0 = t_lo + g * kKeyTargets, a1 = imin(t_hi, a0 + kKeyTargets - 1);
+            const int mA0 = imax(A_lo, a0 - B_hi), mA1 = imin(A_hi, a1 - B_lo);
+            const int mB0 = imax(B_lo, a0 - A_hi), mB1 = imin(B_hi, a1 - A_lo);
+            if (mA0 > mA1 || mB0 > mB1) continue;
+            const bool y_left = role_cost(mA0, mA1, mB0, mB1, a0, a1) <= role_cost(mB0, mB1, mA0, mA1, a0, a1);
+            most = imax(most, cdiv(y_left ? mB1 - mB0 + 1 : mA1 - mA0 + 1, 8));
+        }
+    }
+    return imin(kKeyWaves, most);
+}
+
 template <int NTAB, int NA>
 static void launch_split_key_c(const Tables &t, int S, int fam, const SplitPlan &sp, int NT, int NAall,
                                SplitRange sr, hipStream_t st) {
     if (kKeyNbuf == 2)
         hipLaunchKernelGGL((k_split_key<NTAB, NA, 2>), dim3(seg_count(t.sh.L, S), sr.scount, sp.groups),
-                           dim3(sp.waves * 64), 0, st, t, S, fam, NT, NAall, sp.pc, sr.s0, sr.sstep);
+                           dim3(waves_for(t.sh, S, fam, sp, sr) * 64), 0, st, t, S, fam, NT, NAall, sp.pc, sr.s0, sr.sstep);
     else
         hipLaunchKernelGGL((k_split_key<NTAB, NA, 1>), dim3(seg_count(t.sh.L, S), sr.scount, sp.groups),
-                           dim3(sp.waves * 64), 0, st, t, S, fam, NT, NAall, sp.pc, sr.s0, sr.sstep);
+                           dim3(waves_for(t.sh, S, fam, sp, sr) * 64), 0, st, t, S, fam, NT, NAall, sp.pc, sr.s0, sr.sstep);
 }
 // LDS capacity classes of k_split_key: (tables staged, targets); the smallest that fits is used.
 static const int kKeyClasses[][2] = {{24, 16}, {48, 40}, {64, 48}, {96, 48}, {96, 64}, {136, 64}};
@@ -1257,32 +1284,31 @@ static int enqueue_job(oob_plan *h, int ln, bool want_overlap, const oob_profile
     const long long slot_stride = h->cv.slots * 64; // distance between the two buffers of per-split minima
     hipLaunchKernelGGL(k_fill_keys, dim3((unsigned)((2 * slot_stride + 255) / 256)), dim3(256), 0, st, t.partKey,
                        2 * slot_stride);
-    // Levels.  The splits 2 <= s <= S'-2 of level S' need the levels up to S'-2 only, so they may
-    // start while level S'-1 is still being finished: even levels run on the caller's stream, odd
-    // ones on the handle's second stream, each level waiting for the other stream's last select
-    // only before its two outer splits (s = 1 and S'-1).  Two levels side by side fill the idle
-    // tails of each other's launches.  Each stream has its own buffer of per-split minima.
+    // Levels.  Level S' depends on the lower levels like this: its inner splits 2 <= s <= S'-2 read the
+    // levels up to S'-2 only, its two outer splits (s = 1 and S'-1) read level S'-1, and its select
+    // needs all its splits.  So the chain that cannot be shortened is outer splits -> select ->
+    // outer splits of the next level ..., two small launches per level, and it runs on the caller's
+    // stream.  The inner splits, nearly all of the arithmetic, run on two streams of the library (even
+    // and odd levels), each launch waiting for the select of level S'-2 and awaited by the select of its
+    // own level; they fill the machine around the chain.  Each parity has its own buffer of per-split
+    // minima (a select hands its buffer back reset before the inner splits of level S'+2 start).
     bool overlap = want_overlap && !force_plain && sh.Smax >= 4;
     if (overlap && !lane.aux) lane.aux = borrow_stream();
-    if (overlap && lane.aux) {
-        while ((int)lane.ev_level.size() < sh.Smax + 1) {
+    if (overlap && !lane.aux2) lane.aux2 = borrow_stream();
+    if (overlap && lane.aux && lane.aux2) {
+        while ((int)lane.ev_level.size() < 2 * sh.Smax + 2) {
             hipEvent_t e = borrow_event();
             if (!e) break;
             lane.ev_level.push_back(e);
         }
     }
-    overlap = overlap && lane.aux && (int)lane.ev_level.size() >= sh.Smax + 1;
+    overlap = overlap && lane.aux && lane.aux2 && (int)lane.ev_level.size() >= 2 * sh.Smax + 2;
     const bool timed = ln == 0 && h->ev_begin;
     if (timed) OOB_HIP_CHECK(hipEventRecord(h->ev_begin, st));
-    if (overlap) { // the second stream starts after everything enqueued so far
-        OOB_HIP_CHECK(hipEventRecord(lane.ev_level[0], st));
-        OOB_HIP_CHECK(hipStreamWaitEvent(lane.aux, lane.ev_level[0], 0));
-    }
     for (int S = 2; S <= sh.Smax; ++S) {
         const int NAall = dhi_of(S, M, n_max) - dlo_of(S, M) + 1;
         if (NAall <= 0) continue;
         const int NT = tile_count(L, S);
-        hipStream_t sx = overlap && (S & 1) ? lane.aux : st;
         Tables tl = t; // this level's buffer of per-split minima
         tl.partT = t.partT + (S & 1) * slot_stride;
         tl.partKey = t.partKey + (S & 1) * slot_stride;
@@ -1292,24 +1318,26 @@ static int enqueue_job(oob_plan *h, int ln, bool want_overlap, const oob_profile
             have[fam] = plan_split(sh, S, fam, &sp[fam]) && plan_split_key(sh, S, fam, h->opt_xcd, &kp[fam]);
             if (have[fam]) kp[fam].cls = key_class(kp[fam].ntab, kp[fam].na);
         }
-        if (overlap) {
-            for (int fam = 0; fam < 2; ++fam) // inner splits: in order behind this stream's level S'-2
+        const bool inner = overlap && S >= 4;
+        if (inner) {
+            hipStream_t sx = (S & 1) ? lane.aux2 : lane.aux;
+            OOB_HIP_CHECK(hipStreamWaitEvent(sx, lane.ev_level[2 * (S - 2)], 0)); // select of level S'-2
+            for (int fam = 0; fam < 2; ++fam)
                 if (have[fam]) launch_split_key(tl, S, fam, kp[fam], NT, NAall, SplitRange{2, 1, S - 3}, sx);
-            if (S >= 3) OOB_HIP_CHECK(hipStreamWaitEvent(sx, lane.ev_level[S - 1], 0));
+            OOB_HIP_CHECK(hipEventRecord(lane.ev_level[2 * S + 1], sx));
         }
         for (int fam = 0; fam < 2; ++fam) {
             if (!have[fam]) continue;
-            const SplitRange sr = overlap ? SplitRange{1, imax(S - 2, 1), S == 2 ? 1 : 2} : SplitRange{1, 1, S - 1};
-            if (!force_plain) launch_split_key(tl, S, fam, kp[fam], NT, NAall, sr, sx);
-            else if (sp[fam].pc == 4) launch_split<4>(tl, S, fam, sp[fam], NT, NAall, sx);
-            else if (sp[fam].pc == 2) launch_split<2>(tl, S, fam, sp[fam], NT, NAall, sx);
-            else launch_split<1>(tl, S, fam, sp[fam], NT, NAall, sx);
+            const SplitRange sr = inner ? SplitRange{1, S - 2, 2} : SplitRange{1, 1, S - 1};
+            if (!force_plain) launch_split_key(tl, S, fam, kp[fam], NT, NAall, sr, st);
+            else if (sp[fam].pc == 4) launch_split<4>(tl, S, fam, sp[fam], NT, NAall, st);
+            else if (sp[fam].pc == 2) launch_split<2>(tl, S, fam, sp[fam], NT, NAall, st);
+            else launch_split<1>(tl, S, fam, sp[fam], NT, NAall, st);
         }
-        hipLaunchKernelGGL(k_select, dim3(NT, NAall), dim3(64), 0, sx, tl, S, NT, NAall);
-        if (overlap) OOB_HIP_CHECK(hipEventRecord(lane.ev_level[S], sx));
+        if (inner) OOB_HIP_CHECK(hipStreamWaitEvent(st, lane.ev_level[2 * S + 1], 0));
+        hipLaunchKernelGGL(k_select, dim3(NT, NAall), dim3(64), 0, st, tl, S, NT, NAall);
+        if (overlap) OOB_HIP_CHECK(hipEventRecord(lane.ev_level[2 * S], st));
     }
-    if (overlap) // whatever the second stream did last is awaited on the caller's stream
-        OOB_HIP_CHECK(hipStreamWaitEvent(st, lane.ev_level[sh.Smax & 1 ? sh.Smax : sh.Smax - 1], 0));
     if (timed) { OOB_HIP_CHECK(hipEventRecord(h->ev_end, st)); h->timed = true; }
     hipLaunchKernelGGL(k_pick, dim3((sh.count + 63) / 64), dim3(64), 0, st, t, *out);
     hipLaunchKernelGGL(k_backtrack, dim3((sh.count + 1 + 63) / 64), dim3(64), 0, st, t, *out);
