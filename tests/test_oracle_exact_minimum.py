@@ -92,7 +92,70 @@ def test_never_above_the_recursion_and_gap_on_the_configurations():
               f"equal for {sum(g == 0 for g in gaps)} of {len(gaps)} templates")
 
 
+STAGED_SHAPES = [(5, 1, 1, 3, 6), (6, 2, 1, 3, 8), (7, 2, 1, 2, 9), (6, 4, 1, 2, 12), (6, 3, 1, 2, 7),
+                 # the stage-count limit binds: N_b below min(L, n M)
+                 (7, 1, 1, 4, 3), (7, 2, 1, 3, 4), (8, 2, 1, 3, 3), (6, 4, 1, 2, 5), (9, 3, 1, 2, 2),
+                 # N_b = 4 S per pipeline (the paper's planning-time choice)
+                 (7, 3, 1, 2, 0), (6, 2, 1, 3, 0), (8, 1, 1, 4, 0)]
+
+
+@pytest.mark.parametrize("shape", STAGED_SHAPES)
+def test_stage_limit_and_4S_mode_equal_exhaustive_enumeration(shape):
+    """Both dynamic programs against every pipeline enumerated one by one: the one with the stage
+    count in its tables always; the one without it wherever the limit cannot bind, and never above
+    the exhaustive minimum (it minimises over a larger set) where it can."""
+    L, M, n_min, n_max, nb = shape
+    differ = 0
+    for seed in range(4):
+        for var in ("plain", "tight", "forbid"):
+            inp = inputs.random_small(seed, L, M, n_min, n_max, nb, f=1, tight_mem=(var == "tight"),
+                                      forbid_some_d=(var == "forbid"))
+            staged, loose = E.exact_minimum_staged(inp), E.exact_minimum(inp, allow_bound=True)
+            for n in range(n_min, n_max + 1):
+                b = bf.brute_min(inp, n)
+                b = None if b is None else b[0]
+                assert staged[n - n_min] == b, (shape, seed, var, n)
+                if E.is_tight(inp, n):
+                    assert loose[n - n_min] == b, (shape, seed, var, n)
+                elif b is not None:
+                    assert loose[n - n_min] is not None and loose[n - n_min] <= b
+                    differ += loose[n - n_min] < b
+                else:
+                    differ += loose[n - n_min] is not None  # pipelines exist only beyond the limit
+    if 0 < nb < min(L, n_max * M):
+        assert differ > 0, "the limit never changed a minimum: the shape does not test it"
+
+
+def test_4S_mode_hand_case():
+    """Layers (F+B) = 3, 1, 2, 2, one GPU per node, N_b = 4 S: C = sum t + (3 S + k* - 1) t_max + sum_{k >= k*} t.
+    one stage: 8 + 2*8 + 8 = 32; two stages (4 | 4): 8 + 5*4 + 8 = 36, (3 | 5): k* = 1: 8 + 6*5 + 5 = 43,
+    (6 | 2): 8 + 5*6 + 8 = 46; three stages: (3,1,4): k* = 2: 8 + 10*4 + 4 = 52, (3,3,2): 8 + 8*3 + 8 = 40,
+    (4,2,2): 8 + 8*4 + 8 = 48; four stages (3,1,2,2): 8 + 11*3 + 8 = 49."""
+    from conftest import simple_input
+
+    inp = simple_input([3, 1, 2, 2], M=1, n_min=1, n_max=4, nb=0)
+    assert E.exact_minimum(inp) == E.exact_minimum_staged(inp) == [32, 36, 40, 49]
+    for n in range(1, 5):
+        assert bf.brute_min(inp, n)[0] == [32, 36, 40, 49][n - 1]
+
+
+def test_stage_limit_hand_case():
+    """The same four layers with N_b = 2: pipelines of more than two stages do not exist.
+    C = sum t + (2 - S + k* - 1) t_max + sum_{k >= k*} t: one stage: 8 + 0 + 8 = 16;
+    two stages: (3 | 5): k* = 1: 8 + 0 + 5 = 13, (4 | 4): 8 - 4 + 8 = 12, (6 | 2): 8 - 6 + 8 = 10."""
+    from conftest import simple_input
+
+    inp = simple_input([3, 1, 2, 2], M=1, n_min=1, n_max=4, nb=2)
+    assert E.exact_minimum_staged(inp) == [16, 10, None, None]
+    with pytest.raises(ValueError):
+        E.exact_minimum(inp)
+    # without the limit three and four stages exist (and cost less: the bound is below)
+    loose = E.exact_minimum(inp, allow_bound=True)
+    assert loose[:2] == [16, 10] and loose[2] is not None and loose[3] is not None
+
+
 def test_rejects_what_it_does_not_model():
     inp = inputs.random_small(0, 9, 2, 1, 3, 4)   # N_b = 4 < min(L, n_max M) = 6
     with pytest.raises(ValueError):
         E.exact_minimum(inp)
+    assert E.exact_minimum(inp, allow_bound=True)[0] == E.exact_minimum_staged(inp)[0]  # n = 1: min(L, M) = 2 <= 4
