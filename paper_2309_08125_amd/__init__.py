@@ -5,6 +5,7 @@ from .binding import (  # noqa: F401
     oob_plan_max_stages, oob_plan_templates, oob_plan_templates_batch, oob_plan_workspace_size,
     template_stages, OOB_OPT_PLAIN_SPLIT, OOB_OPT_XCD_ORDER, OOB_OPT_ONE_STREAM, OOB_OPT_NO_THIN_SPLITS,
     EXACT_SYMBOLS, ExactMinimum, oob_exact_minimum, oob_exact_workspace_size,
+    OOB_EXACT_LIMIT_CAN_BIND, oob_exact_minimum_staged, oob_exact_staged_workspace_size,
     DIST_SYMBOLS, Distributor, oob_dist_choose, oob_dist_solve,
     OOB_DIST_OK, OOB_DIST_TOO_FEW_MICROBATCHES, OOB_DIST_TOO_MANY_TEMPLATES, OOB_DIST_BAD_TIME, OOB_DIST_NO_PIPELINE,
     RECONF_ROWS, RECONF_SYMBOLS, FailureSimulator, oob_reconf_simulate,

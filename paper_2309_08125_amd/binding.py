@@ -28,7 +28,9 @@ INST_SYMBOLS = ["oob_inst_workspace_size", "oob_inst_count", "oob_inst_enumerate
 OOB_INST_STATIC_BYTES = 4 << 20
 RECONF_SYMBOLS = ["oob_reconf_simulate"]
 DIST_SYMBOLS = ["oob_dist_solve", "oob_dist_choose"]
-EXACT_SYMBOLS = ["oob_exact_workspace_size", "oob_exact_minimum"]
+EXACT_SYMBOLS = ["oob_exact_workspace_size", "oob_exact_minimum", "oob_exact_staged_workspace_size",
+                 "oob_exact_minimum_staged"]
+OOB_EXACT_LIMIT_CAN_BIND = -2
 OOB_DIST_OK, OOB_DIST_TOO_FEW_MICROBATCHES, OOB_DIST_TOO_MANY_TEMPLATES, OOB_DIST_BAD_TIME, OOB_DIST_NO_PIPELINE = range(5)
 RECONF_ROWS = ("survived", "reinstantiated", "borrowed", "merges", "alive", "nodes", "violations", "stop")
 
@@ -114,6 +116,10 @@ def load():
         L.oob_exact_minimum.argtypes = [C.POINTER(oob_profile), C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64,
                                         C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
         L.oob_exact_minimum.restype = C.c_int
+        L.oob_exact_staged_workspace_size.argtypes = [C.c_int] * 4
+        L.oob_exact_staged_workspace_size.restype = C.c_size_t
+        L.oob_exact_minimum_staged.argtypes = L.oob_exact_minimum.argtypes
+        L.oob_exact_minimum_staged.restype = C.c_int
         _lib = L
     return _lib
 
@@ -220,6 +226,18 @@ def oob_exact_minimum(profile, L, n_min, n_max, gpus_per_node, microbatches, mem
                                     gpus_per_node, microbatches, mem_cap, C.c_void_p(dev_workspace_ptr),
                                     workspace_bytes, C.c_void_p(best_ptr), C.c_void_p(status_ptr),
                                     C.c_void_p(stream_ptr))
+
+
+def oob_exact_staged_workspace_size(L, n_max, gpus_per_node, microbatches) -> int:
+    return load().oob_exact_staged_workspace_size(L, n_max, gpus_per_node, microbatches)
+
+
+def oob_exact_minimum_staged(profile, L, n_min, n_max, gpus_per_node, microbatches, mem_cap, dev_workspace_ptr,
+                             workspace_bytes, best_ptr, status_ptr, stream_ptr) -> int:
+    return load().oob_exact_minimum_staged(C.byref(profile) if profile is not None else None, L, n_min, n_max,
+                                           gpus_per_node, microbatches, mem_cap, C.c_void_p(dev_workspace_ptr),
+                                           workspace_bytes, C.c_void_p(best_ptr), C.c_void_p(status_ptr),
+                                           C.c_void_p(stream_ptr))
 
 
 # ---- convenience layer over torch device memory ------------------------------------------
@@ -482,18 +500,19 @@ class FailureSimulator:
 
 
 class ExactMinimum:
-    """Device buffers for oob_exact_minimum of one planning job."""
+    """Device buffers for oob_exact_minimum (staged=False) or oob_exact_minimum_staged of one planning job."""
 
-    def __init__(self, inp, device="cuda:0"):
+    def __init__(self, inp, staged: bool = False, device="cuda:0", workspace_bytes: int = 0):
         import torch
 
         self.device = torch.device(device)
-        self.inp = inp
+        self.inp, self.staged = inp, staged
         self.prof = DeviceProfile(inp, self.device)
-        nbytes = oob_exact_workspace_size(inp.L, inp.n_max, inp.gpus_per_node)
+        nbytes = (oob_exact_staged_workspace_size(inp.L, inp.n_max, inp.gpus_per_node, inp.microbatches) if staged
+                  else oob_exact_workspace_size(inp.L, inp.n_max, inp.gpus_per_node))
         if nbytes == 0:
             raise ValueError("oob_exact_workspace_size: dimensions out of range")
-        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.workspace = torch.empty(workspace_bytes or nbytes, dtype=torch.uint8, device=self.device)
         self.best = torch.full((inp.n_max - inp.n_min + 1,), -99, dtype=torch.int64, device=self.device)
         self.status = torch.full((1,), -99, dtype=torch.int32, device=self.device)
 
@@ -502,17 +521,19 @@ class ExactMinimum:
 
         i = self.inp
         s = torch.cuda.current_stream(self.device)
-        return oob_exact_minimum(self.prof.c, i.L, i.n_min, i.n_max, i.gpus_per_node, i.microbatches, i.mem_cap,
-                                 self.workspace.data_ptr(), self.workspace.numel(), self.best.data_ptr(),
-                                 self.status.data_ptr(), s.cuda_stream)
+        fn = oob_exact_minimum_staged if self.staged else oob_exact_minimum
+        return fn(self.prof.c, i.L, i.n_min, i.n_max, i.gpus_per_node, i.microbatches, i.mem_cap,
+                  self.workspace.data_ptr(), self.workspace.numel(), self.best.data_ptr(),
+                  self.status.data_ptr(), s.cuda_stream)
 
     def run(self):
-        """(status, exact minimum per template as a list, None where no pipeline exists)."""
+        """(status, exact minimum per template as a list: None where no pipeline exists,
+        OOB_EXACT_LIMIT_CAN_BIND where the entry point without stage counts does not answer)."""
         import torch
 
         check(self.enqueue(), "oob_exact_minimum")
         torch.cuda.synchronize(self.device)
-        return int(self.status.item()), [None if v < 0 else int(v) for v in self.best.cpu().numpy()]
+        return int(self.status.item()), [None if v == -1 else int(v) for v in self.best.cpu().numpy()]
 
 
 class Distributor:

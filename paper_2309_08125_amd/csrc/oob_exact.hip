@@ -2,17 +2,27 @@
 // Eq. 1-4) over all explicit pipelines, for gfx950.
 //
 // With k* the first slowest stage and tau its time,
-//     C = sum_{i<k*} t_i + N_b tau + sum_{i>k*} (2 t_i - tau),
+//     C = sum_{i<k*} t_i + N_b tau + sum_{i>k*} (2 t_i - tau)                        (N_b given)
+//     C = sum_{i<k*} (t_i + 4 tau) + 4 tau + sum_{i>k*} (2 t_i + 3 tau)              (N_b = 4 S)
 // so around a FIXED slowest stage (u, v, d) the stages before and after it are two independent
-// shortest-path problems over (layer, GPUs used):
-//     Pre[p][D] = least sum of t over sequences covering layers [0, p) on exactly the first D GPUs, t < tau
-//     Suf[p][E] = least sum of (2 t - tau) over sequences covering [p, L) on exactly the last E GPUs, t <= tau
-// (no stage crosses a node boundary; boundaries are the multiples of M from either end), and
-//     C(u, v, d; n) = min over D of  Pre[u][D] + N_b tau + Suf[v][n M - D - d].
-// One workgroup takes one candidate slowest stage at a time (a grid-stride loop over all of
-// them), keeps its two tables in its own slice of the workspace (they stay in L2), walks the
-// layers with one barrier per layer, each thread owning GPU positions, and merges its minima per
-// template into LDS and, at the end, into the result with 64-bit atomic minima.
+// shortest-path problems.  A stage never crosses a node boundary and the stages fill node after
+// node, so a pipeline around (u, v, d) is: `a` whole nodes covering layers [0, q), then g GPUs of the
+// slowest stage's node covering [q, u), the stage itself, the remaining h = M - g - d GPUs of that
+// node covering [v, x), and b whole nodes covering [x, L); n = a + 1 + b.
+//
+// k_exact_lds (the fast path; everything in LDS, times as exact integers in doubles).  One
+// workgroup per slowest stage.  Phase 1, per wave and start layer q, no workgroup barrier: the
+// one-node table G_q[p][g] = least cost of covering [q, p) with stages on exactly the first g GPUs
+// of a node; it yields W[q][p] = G_q[p][M] (a whole node) and GU[q][g] = G_q[u][g].  Phase 2: the
+// node-level recurrence NP_a[p] = min_q NP_{a-1}[q] + W[q][p] and PreU[a][g] = min_q NP_a[q] +
+// GU[q][g], one barrier per node count.  The same two phases mirrored for the layers after v,
+// then every (template, a, g) combination.  Global memory is read for the stage times only (one
+// table for the whole call, resident in L2).
+//
+// k_exact_flat (tables in the caller's workspace, int64): the plain recurrence over (layer, GPUs
+// used [, stages used]).  It serves shapes whose tables exceed LDS and, with the stage count as a
+// third index (plain sums of t; the coefficient of tau follows from the counts at the end), the
+// limit S <= N_b: oob_exact_minimum_staged.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -21,33 +31,55 @@
 
 namespace oob_exact {
 
-constexpr int kThreads = 256;
-constexpr int kSlots = 2048;                    // workgroups in flight (8 waves per SIMD), each with tables of its own
+constexpr int kThreads = 256;       // k_exact_flat
+constexpr int kFlatSlots = 2048;    // its workgroups in flight at most, each with tables of its own
 constexpr long long kInf = 1ll << 61;
 constexpr long long kForbidden = 1ll << 62;
+constexpr long long kDoubleExact = 1ll << 52;
+constexpr double kNone = __builtin_huge_val();
+constexpr size_t kLdsLimit = 160 * 1024;
 
 struct Args {
     oob_profile prof;
-    int L, M, n_min, n_max, Nb, Dmax;
+    int L, M, n_min, n_max, Nb, Dmax, Smax;
     long long cap;
-    long long *t;     // [(u (L+1) + v) M + d-1] stage times, -1: impossible
-    long long *slots; // [kSlots][2][(L+1)][(Dmax+1)]
-    long long *best;
+    long long limit;      // every cost must stay below this (2^52 for the LDS path, 2^61 otherwise)
+    long long *t;         // [(u (L+1) + v) M + d-1] stage times, -1: impossible
+    double *td;           // the same as doubles
+    long long *slots;     // k_exact_flat: [slots][2][(L+1)][(Dmax+1)][J]
+    unsigned long long *best; // per template: smallest cost so far
+    unsigned *counter;    // work counter of k_exact_lds
     int *status;
 };
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
-inline size_t table_bytes(int L, int M) { return align_up(sizeof(long long) * (size_t)(L + 1) * (L + 1) * M); }
-inline size_t slot_bytes(int L, int Dmax) { return align_up(sizeof(long long) * 2 * (size_t)(L + 1) * (Dmax + 1)); }
+inline size_t table_entries(int L, int M) { return (size_t)(L + 1) * (L + 1) * M; }
+inline size_t head_bytes(int L, int M) { return 256 + 2 * align_up(8 * table_entries(L, M)); }
 
-// Clears the result and validates the magnitudes: every cost is at most (N_b + 2) w, w = the sum
-// over the layers of the slowest allowed F + B of the layer plus its boundary term (a bound on the
-// sum of all stage times of any pipeline).  status = OOB_EOVERFLOW unless that stays below 2^61.
-// One workgroup; runs before k_exact_stages, which only ever lowers the status.
+// LDS of k_exact_lds for `nw` waves, in bytes (all arrays 8-byte entries; see the kernel).
+__host__ __device__ inline size_t tri(int L) { return (size_t)L * (L + 1) / 2; }
+inline size_t lds_bytes(int L, int M, int n_max, int count, int nw) {
+    const size_t n = tri(L) + (size_t)(L + 1) * M + 2 * (size_t)(L + 1) + 2 * (size_t)n_max * M +
+                     ((size_t)(L + 1) * M + 1) / 2 + (size_t)(L + 1) / 2 + 1 + L + count +
+                     (size_t)nw * (L + 1) * (M + 1);
+    return 8 * n + 64;
+}
+inline int lds_waves(int L, int M, int n_max, int count) { // 0: does not fit
+    for (int nw = 8; nw >= 2; nw >>= 1)
+        if (lds_bytes(L, M, n_max, count, nw) <= kLdsLimit) return nw;
+    return 0;
+}
+
+// Clears the result and validates the magnitudes: every cost is at most mult * w, w = the sum over
+// the layers of the slowest allowed F + B of the layer plus its boundary term (a bound on the sum
+// of all stage times of any pipeline), mult = N_b + 2 (4 S_max + 2 when N_b = 4 S).  status =
+// OOB_EOVERFLOW unless that stays below the limit of the path.  One workgroup; runs before
+// k_exact_stages, which only ever sets the status to OOB_EINVAL.
 __global__ void __launch_bounds__(kThreads) k_exact_init(Args a) {
     __shared__ long long s_sum[kThreads];
     const int count = a.n_max - a.n_min + 1;
-    for (int i = threadIdx.x; i < count; i += kThreads) a.best[i] = kInf;
+    for (int i = threadIdx.x; i < count; i += kThreads) a.best[i] = 0x7FF0000000000000ull; // +inf as a double, huge as an integer
+    if (threadIdx.x == 0) *a.counter = 0;
     const long long *fwd = (const long long *)a.prof.fwd_ns, *bwd = (const long long *)a.prof.bwd_ns;
     const long long *bnd = (const long long *)a.prof.boundary_ns;
     long long acc = 0;
@@ -68,7 +100,8 @@ __global__ void __launch_bounds__(kThreads) k_exact_init(Args a) {
     if (threadIdx.x == 0) {
         long long w = 0;
         for (int i = 0; i < kThreads; ++i) w = (w + s_sum[i] >= kInf) ? kInf : w + s_sum[i];
-        *a.status = w >= kInf / ((long long)a.Nb + 2) ? OOB_EOVERFLOW : OOB_OK;
+        const long long mult = (a.Nb > 0 ? (long long)a.Nb : 4ll * a.Smax) + 2;
+        *a.status = w >= a.limit / mult ? OOB_EOVERFLOW : OOB_OK;
     }
 }
 
@@ -90,111 +123,374 @@ __global__ void k_exact_stages(Args a) {
         bytes += mem[v - 1];
         long long val = -1;
         if (ok && (bytes + d - 1) / d <= a.cap) val = time + (v < a.L ? bnd[v - 1] : 0);
-        a.t[((size_t)u * (a.L + 1) + v) * a.M + d - 1] = val;
+        const size_t o = ((size_t)u * (a.L + 1) + v) * a.M + d - 1;
+        a.t[o] = val;
+        a.td[o] = (double)val;
     }
     if (bad) atomicExch(a.status, OOB_EINVAL);
 }
 
-__global__ void __launch_bounds__(kThreads) k_exact(Args a) {
-    HIP_DYNAMIC_SHARED(long long, s_dyn) // [L * M] stage times into (or out of) the current layer, then [count] minima
-    const int L = a.L, M = a.M, W = a.Dmax + 1, count = a.n_max - a.n_min + 1;
-    long long *s_col = s_dyn, *s_best = s_dyn + (size_t)L * M;
-    long long *Pre = a.slots + (size_t)blockIdx.x * 2 * (L + 1) * W, *Suf = Pre + (size_t)(L + 1) * W;
-    const long long *bnd = (const long long *)a.prof.boundary_ns;
+// ---------------------------------------------------------------------------------------------
+// The fast path.
+// ---------------------------------------------------------------------------------------------
+// What one wave has written to LDS is read by its other lanes: program order of the LDS operations
+// of a wave is execution order, the fences keep the compiler from moving them.
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+__device__ __forceinline__ double shfl_xor_f64(double x, int m) { return __shfl_xor(x, m, 64); }
+
+struct Lds {
+    double *W;    // [tri(L)]  one whole node covering [q, p), q < p: index q L - q (q-1)/2 + p - q - 1
+    double *GU;   // [(L+1)][M]  g GPUs (entry g, 1 <= g < M) of a node covering [q, u) / (mirrored) [v, x)
+    double *NP;   // [2][L+1]  node-level tables of the previous and the current node count
+    double *PU;   // [n_max][M]  PreU[a][g]
+    double *SV;   // [n_max][M]  SufV[b][h]
+    int *lo;      // [(L+1)][M]  first (prefix) / last (suffix) layer a stage into / out of p can reach
+    int *lomin;   // [L+1]       the extreme of lo over the GPU counts
+    double *bnd;  // [L]
+    unsigned long long *best; // [count]
+    double *G;    // [waves][(L+1)][(M+1)]
+};
+__device__ __forceinline__ size_t widx(int q, int p, int L) { return (size_t)q * L - (size_t)q * (q - 1) / 2 + (p - q - 1); }
+
+// One side of the slowest stage.  MIRROR = false: the layers [0, e) before it (e = u); a one-node
+// table starts at layer q and grows to the right, a stage [q', p) into p costs t + ptau * tau and needs
+// t < tau.  MIRROR = true: the layers [e, L) after it (e = v); a one-node table ends at layer q and
+// grows to the left, a stage [p, w) out of p costs 2 t + stau * tau and needs t <= tau.  Result:
+// OUT[c][g] = least cost of covering the side with c whole nodes and g more GPUs next to the
+// slowest stage, g = 0 .. M-1.
+template <bool MIRROR>
+__device__ void one_side(const Args &a, const Lds &s, int e, double tau, double wt, double wtau, double *OUT) {
+    const int L = a.L, M = a.M, nw = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int gi = lane >> 3, di = lane & 7;
+    const double add = wtau * tau;
+    // layers of the side: prefix p in (0, e], suffix p in [e, L); starts q: prefix [0, e), suffix (e, L]
+    // ---- reach of a stage into / out of every layer p, per GPU count -------------------------
+    for (int i = threadIdx.x; i < (L + 1) * M; i += blockDim.x) {
+        const int p = i / M, dd = i % M + 1;
+        int r = p;
+        if (!MIRROR) {
+            if (p >= 1 && p <= e)
+                for (int q = p - 1; q >= 0; --q) { // [q, p) only gets slower and heavier as q goes down
+                    const double tt = a.td[((size_t)q * (L + 1) + p) * M + dd - 1];
+                    if (tt < 0.0 || tt >= tau) break;
+                    r = q;
+                }
+        } else {
+            if (p >= e && p < L)
+                for (int w = p + 1; w <= L; ++w) { // impossible stays impossible, the time without the boundary term only grows
+                    const double tt = a.td[((size_t)p * (L + 1) + w) * M + dd - 1];
+                    if (tt < 0.0 || tt - (w < L ? s.bnd[w - 1] : 0.0) > tau) break;
+                    r = w;
+                }
+        }
+        s.lo[i] = r;
+    }
+    __syncthreads();
+    for (int p = threadIdx.x; p <= L; p += blockDim.x) {
+        int m = s.lo[p * M];
+        for (int dd = 2; dd <= M; ++dd) m = MIRROR ? max(m, s.lo[p * M + dd - 1]) : min(m, s.lo[p * M + dd - 1]);
+        s.lomin[p] = m;
+    }
+    for (int i = threadIdx.x; i < (L + 1) * M; i += blockDim.x) s.GU[i] = kNone;
+    __syncthreads();
+    // ---- phase 1: one-node tables, one start layer per wave at a time ----------------------
+    double *G = s.G + (size_t)wave * (L + 1) * (M + 1);
+    const int nstart = MIRROR ? L - e : e;
+    for (int qi = wave; qi < nstart; qi += nw) {
+        const int q = MIRROR ? L - qi : qi;            // prefix: q = 0 .. e-1; suffix: q = L .. e+1
+        // row r of G = layer q + r (prefix) / q - r (suffix); row 0: nothing covered
+        for (int g = lane; g <= M; g += 64) G[g] = g == 0 ? 0.0 : kNone;
+        wave_sync();
+        const int rows = MIRROR ? q - e : e - q;
+        for (int r = 1; r <= rows; ++r) {
+            const int p = MIRROR ? q - r : q + r;
+            const int far = MIRROR ? min(q, s.lomin[p]) : max(q, s.lomin[p]); // farthest layer any stage of this row reaches
+            for (int gt = 0; gt * 8 < M; ++gt) {
+                const int g = gt * 8 + gi + 1;
+                double acc = kNone;
+                for (int dt = 0; dt <= gt; ++dt) {
+                    const int dd = dt * 8 + di + 1;
+                    const bool on = g <= M && dd <= g;
+                    const int reach = on ? s.lo[p * M + dd - 1] : p;
+                    // every lane walks the row's whole reach (uniform trip count, loads without
+                    // conditions so that they can be issued ahead); what lies beyond the lane's own reach
+                    // or GPU count reads a valid entry and is discarded
+                    const int ddc = on ? dd : 1, gc = on ? g - dd : 0;
+                    if (!MIRROR) {
+                        const int qlo = max(q, reach);
+                        const double *tp = a.td + (size_t)p * M + ddc - 1; // + x (L+1) M
+#pragma unroll 4
+                        for (int x = p - 1; x >= far; --x) { // stage [x, p)
+                            const double tt = tp[(size_t)x * (L + 1) * M];
+                            const double cand = G[(x - q) * (M + 1) + gc] + (wt * tt + add);
+                            acc = fmin(acc, x >= qlo ? cand : kNone);
+                        }
+                    } else {
+                        const int qhi = min(q, reach);
+                        const double *tp = a.td + (size_t)p * (L + 1) * M + ddc - 1; // + x M
+#pragma unroll 4
+                        for (int x = p + 1; x <= far; ++x) { // stage [p, x)
+                            const double tt = tp[(size_t)x * M];
+                            const double cand = G[(q - x) * (M + 1) + gc] + (wt * tt + add);
+                            acc = fmin(acc, (x <= qhi && tt <= tau) ? cand : kNone);
+                        }
+                    }
+                }
+                acc = fmin(acc, shfl_xor_f64(acc, 1));
+                acc = fmin(acc, shfl_xor_f64(acc, 2));
+                acc = fmin(acc, shfl_xor_f64(acc, 4));
+                if (di == 0 && g <= M) G[r * (M + 1) + g] = acc;
+            }
+            if (lane == 0) G[r * (M + 1)] = kNone;
+            wave_sync();
+        }
+        // a whole node covering [q, p) (prefix) / [p, q) (suffix), and the partial covers next to the slowest stage
+        for (int r = 1 + lane; r <= rows; r += 64) {
+            const int p = MIRROR ? q - r : q + r;
+            s.W[MIRROR ? widx(p, q, L) : widx(q, p, L)] = G[r * (M + 1) + M];
+        }
+        for (int g = 1 + lane; g < M; g += 64) s.GU[q * M + g] = G[rows * (M + 1) + g];
+        wave_sync();
+    }
+    __syncthreads();
+    // ---- phase 2: node after node ------------------------------------------------------------
+    // NP_c[p]: c whole nodes cover [0, p) (prefix) / [p, L) (suffix); p runs over the side's layers
+    double *cur = s.NP, *nxt = s.NP + (L + 1);
+    const int origin = MIRROR ? L : 0;
+    for (int p = threadIdx.x; p <= L; p += blockDim.x) cur[p] = p == origin ? 0.0 : kNone;
+    __syncthreads();
+    const int h4 = threadIdx.x & 3;
+    for (int c = 0; c < a.n_max; ++c) {
+        // OUT[c][g] from NP_c, and NP_{c+1} from NP_c, in one phase
+        for (int i = threadIdx.x; i < M * 4; i += blockDim.x) { // four threads per g
+            const int g = i >> 2;
+            double m = kNone;
+            if (g == 0) { if (h4 == 0) m = cur[e]; }
+            else if (!MIRROR) for (int q = h4; q < e; q += 4) m = fmin(m, cur[q] + s.GU[q * M + g]);
+            else              for (int q = e + 1 + h4; q <= L; q += 4) m = fmin(m, cur[q] + s.GU[q * M + g]);
+            m = fmin(m, shfl_xor_f64(m, 1));
+            m = fmin(m, shfl_xor_f64(m, 2));
+            if (h4 == 0) OUT[c * M + g] = m;
+        }
+        if (c + 1 < a.n_max) {
+            const int np = MIRROR ? L - e + 1 : e + 1; // layers of the side, origin included
+            for (int i = threadIdx.x; i < ((np * 4 + 63) & ~63); i += blockDim.x) { // whole waves: the shuffles need every lane
+                const int pi = i >> 2;
+                double m = kNone;
+                if (pi < np) {
+                    const int p = MIRROR ? L - pi : pi;
+                    if (!MIRROR) for (int q = h4; q < p; q += 4) m = fmin(m, cur[q] + s.W[widx(q, p, L)]);
+                    else         for (int q = p + 1 + h4; q <= L; q += 4) m = fmin(m, cur[q] + s.W[widx(p, q, L)]);
+                }
+                m = fmin(m, shfl_xor_f64(m, 1));
+                m = fmin(m, shfl_xor_f64(m, 2));
+                if (h4 == 0 && pi < np) nxt[MIRROR ? L - pi : pi] = m;
+            }
+        }
+        __syncthreads();
+        double *tmp = cur; cur = nxt; nxt = tmp;
+    }
+}
+
+__global__ void __launch_bounds__(512) k_exact_lds(Args a) {
+    HIP_DYNAMIC_SHARED(double, s_dyn)
+    __shared__ unsigned s_next;
     if (*a.status != OOB_OK) return; // the same for every thread: nothing is computed from a bad profile
+    const int L = a.L, M = a.M, count = a.n_max - a.n_min + 1, nw = blockDim.x >> 6;
+    Lds s;
+    double *p = s_dyn;
+    s.W = p;    p += tri(L);
+    s.GU = p;   p += (size_t)(L + 1) * M;
+    s.NP = p;   p += 2 * (size_t)(L + 1);
+    s.PU = p;   p += (size_t)a.n_max * M;
+    s.SV = p;   p += (size_t)a.n_max * M;
+    s.lo = (int *)p;    p += ((size_t)(L + 1) * M + 1) / 2;
+    s.lomin = (int *)p; p += (size_t)(L + 1) / 2 + 1;
+    s.bnd = p;  p += L;
+    s.best = (unsigned long long *)p; p += count;
+    s.G = p;
+    const long long *bnd = (const long long *)a.prof.boundary_ns;
+    for (int i = threadIdx.x; i < L; i += blockDim.x) s.bnd[i] = (double)bnd[i];
+    for (int i = threadIdx.x; i < count; i += blockDim.x) s.best[i] = 0x7FF0000000000000ull;
+    // weights of a stage before / after the slowest one and of the slowest one, as (t, tau) coefficients
+    const double ptau = a.Nb > 0 ? 0.0 : 4.0, stau = a.Nb > 0 ? -1.0 : 3.0, mid = a.Nb > 0 ? (double)a.Nb : 4.0;
+    const unsigned ncand = (unsigned)((long long)L * (L + 1) / 2 * M);
+    for (;;) {
+        __syncthreads(); // the previous candidate is done with LDS (and s_next has been read)
+        if (threadIdx.x == 0) s_next = atomicAdd(a.counter, 1u);
+        __syncthreads();
+        const unsigned c = s_next;
+        if (c >= ncand) break; // every wave of every workgroup gets here
+        // candidate c -> (u, v, d): pairs u < v in row order, d fastest
+        const int d = (int)(c % M) + 1;
+        unsigned pr = c / M;
+        int u = 0;
+        while (pr >= (unsigned)(L - u)) { pr -= L - u; ++u; }
+        const int v = u + 1 + (int)pr;
+        const double tau = a.td[((size_t)u * (L + 1) + v) * M + d - 1];
+        if (tau < 0.0) continue; // the same for the whole workgroup
+        one_side<false>(a, s, u, tau, 1.0, ptau, s.PU);
+        one_side<true>(a, s, v, tau, 2.0, stau, s.SV);
+        // the slowest stage at every place it fits, for every template whose stage limit cannot bind
+        const int places = M - d + 1; // g = 0 .. M - d GPUs of its node before it
+        for (int n = a.n_min; n <= a.n_max; ++n) {
+            if (a.Nb > 0 && a.Nb < min(L, n * M)) continue;
+            double m = kNone;
+            for (int i = threadIdx.x; i < n * places; i += blockDim.x) {
+                const int ca = i / places, g = i % places;
+                m = fmin(m, s.PU[ca * M + g] + s.SV[(n - 1 - ca) * M + (M - d - g)]);
+            }
+            m += mid * tau;
+            if (m < kNone) atomicMin(&s.best[n - a.n_min], (unsigned long long)__double_as_longlong(m));
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < count; i += blockDim.x)
+        if (s.best[i] != 0x7FF0000000000000ull) atomicMin(&a.best[i], s.best[i]);
+    (void)nw;
+}
+
+// Results as int64: -1 where no pipeline exists, -2 (unstaged entry point) where the stage limit
+// can bind, so that the minimum without it is not the answer.
+__global__ void k_exact_finish(Args a, int from_double, int staged) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > a.n_max - a.n_min) return;
+    const int n = a.n_min + i;
+    long long out;
+    if (!staged && a.Nb > 0 && a.Nb < min(a.L, n * a.M)) out = -2;
+    else if (from_double) { const double x = __longlong_as_double((long long)a.best[i]); out = x < kNone ? (long long)x : -1; }
+    else out = (long long)a.best[i] >= kInf / 2 ? -1 : (long long)a.best[i];
+    ((long long *)a.best)[i] = out;
+}
+
+// ---------------------------------------------------------------------------------------------
+// The general path: tables in the workspace.
+//   Pre[p][D][j] = least sum over sequences covering [0, p) on exactly the first D GPUs (with j stages), t < tau
+//   Suf[p][E][j] = the same for [p, L) on exactly the last E GPUs, t <= tau
+// STAGED = false: J = 1, the sums carry the weights of the cost; STAGED = true: plain sums of t, the
+// stage counts choose the coefficient of tau at the end and obey j1 + 1 + j2 <= N_b.
+// One workgroup takes one candidate slowest stage at a time (a grid-stride loop), walks the layers
+// with two barriers per layer (the stage times into / out of the layer are staged in LDS), each
+// thread owning (GPUs, stages) positions.
+// ---------------------------------------------------------------------------------------------
+template <bool STAGED>
+__global__ void __launch_bounds__(kThreads) k_exact_flat(Args a) {
+    HIP_DYNAMIC_SHARED(long long, s_flat) // [L * M] stage times into (or out of) the current layer, then [count] minima
+    const int L = a.L, M = a.M, W = a.Dmax + 1, J = STAGED ? a.Smax + 1 : 1, count = a.n_max - a.n_min + 1;
+    long long *s_col = s_flat, *s_best = s_flat + (size_t)L * M;
+    const size_t plane = (size_t)W * J;
+    long long *Pre = a.slots + (size_t)blockIdx.x * 2 * (L + 1) * plane, *Suf = Pre + (size_t)(L + 1) * plane;
+    const long long *bnd = (const long long *)a.prof.boundary_ns;
+    if (*a.status != OOB_OK) return;
+    const long long ptau = STAGED ? 0 : (a.Nb > 0 ? 0 : 4), stau = STAGED ? 0 : (a.Nb > 0 ? -1 : 3);
+    const long long wsuf = STAGED ? 1 : 2;
     for (int i = threadIdx.x; i < count; i += kThreads) s_best[i] = kInf;
     const long long ncand = (long long)L * (L + 1) / 2 * M;
     for (long long c = blockIdx.x; c < ncand; c += gridDim.x) {
-        // candidate c -> (u, v, d): pairs u < v in row order, d fastest
         const int d = (int)(c % M) + 1;
         long long pr = c / M;
         int u = 0;
         while (pr >= L - u) { pr -= L - u; ++u; }
         const int v = u + 1 + (int)pr;
         const long long tau = a.t[((size_t)u * (L + 1) + v) * M + d - 1];
-        if (tau < 0) continue; // the same for the whole workgroup
-        __syncthreads();       // the tables of the previous candidate are no longer read
-
-        // Pre[p][.] for p = 0..u
-        for (int D = threadIdx.x; D < W; D += kThreads) Pre[D] = D == 0 ? 0 : kInf;
+        if (tau < 0) continue;
+        __syncthreads(); // the tables of the previous candidate are no longer read
+        for (size_t i = threadIdx.x; i < plane; i += kThreads) Pre[i] = i == 0 ? 0 : kInf;
         for (int p = 1; p <= u; ++p) {
-            __syncthreads(); // row p-1 written; s_col free
+            __syncthreads();
             for (int i = threadIdx.x; i < p * M; i += kThreads) // times of the stages [q, p) on dd GPUs
                 s_col[i] = a.t[((size_t)(i / M) * (L + 1) + p) * M + i % M];
             __syncthreads();
-            for (int D = threadIdx.x; D < W; D += kThreads) {
+            for (size_t i = threadIdx.x; i < plane; i += kThreads) {
+                const int D = (int)(i / J), j = (int)(i % J);
                 long long m = kInf;
-                for (int dd = 1; dd <= M && dd <= D; ++dd) {
-                    const int D0 = D - dd;
-                    if (D0 % M + dd > M) continue; // would cross a node boundary
-                    // a stage [q, p) only gets longer and heavier as q goes down: once it is too slow (or
-                    // impossible) it stays so, and the loop ends
-                    for (int q = p - 1; q >= 0; --q) {
-                        const long long tt = s_col[q * M + dd - 1];
-                        if (tt < 0 || tt >= tau) break;
-                        const long long x = Pre[(size_t)q * W + D0] + tt;
-                        m = x < m ? x : m;
+                if (!STAGED || j >= 1)
+                    for (int dd = 1; dd <= M && dd <= D; ++dd) {
+                        const int D0 = D - dd;
+                        if (D0 % M + dd > M) continue; // would cross a node boundary
+                        const size_t src = (size_t)D0 * J + (STAGED ? j - 1 : 0);
+                        for (int q = p - 1; q >= 0; --q) { // [q, p) only gets slower and heavier as q goes down
+                            const long long tt = s_col[q * M + dd - 1];
+                            if (tt < 0 || tt >= tau) break;
+                            const long long x = Pre[(size_t)q * plane + src] + tt + ptau * tau;
+                            m = x < m ? x : m;
+                        }
                     }
-                }
-                Pre[(size_t)p * W + D] = m;
+                Pre[(size_t)p * plane + i] = m;
             }
         }
-        // Suf[p][.] for p = L..v
         __syncthreads();
-        for (int E = threadIdx.x; E < W; E += kThreads) Suf[(size_t)L * W + E] = E == 0 ? 0 : kInf;
+        for (size_t i = threadIdx.x; i < plane; i += kThreads) Suf[(size_t)L * plane + i] = i == 0 ? 0 : kInf;
         for (int p = L - 1; p >= v; --p) {
             __syncthreads();
             for (int i = threadIdx.x; i < (L - p) * M; i += kThreads) // times of the stages [p, p+1+i/M) on dd GPUs
                 s_col[i] = a.t[((size_t)p * (L + 1) + p + 1 + i / M) * M + i % M];
             __syncthreads();
-            for (int E = threadIdx.x; E < W; E += kThreads) {
+            for (size_t i = threadIdx.x; i < plane; i += kThreads) {
+                const int E = (int)(i / J), j = (int)(i % J);
                 long long m = kInf;
-                for (int dd = 1; dd <= M && dd <= E; ++dd) {
-                    const int E0 = E - dd;
-                    if (E0 % M + dd > M) continue;
-                    // [p, w) as w goes up: impossible stays impossible and the time without the boundary
-                    // term only grows, so those end the loop.  The time WITH the boundary term does not
-                    // grow (the term belongs to the last layer and the model's last stage pays none):
-                    // a stage that is only too slow because of it is skipped, not the rest of the run.
-                    for (int w = p + 1; w <= L; ++w) {
-                        const long long tt = s_col[(w - p - 1) * M + dd - 1];
-                        if (tt < 0) break;
-                        if (tt > tau) {
-                            if (w == L || tt - bnd[w - 1] > tau) break;
-                            continue;
+                if (!STAGED || j >= 1)
+                    for (int dd = 1; dd <= M && dd <= E; ++dd) {
+                        const int E0 = E - dd;
+                        if (E0 % M + dd > M) continue;
+                        const size_t src = (size_t)E0 * J + (STAGED ? j - 1 : 0);
+                        // [p, w) as w goes up: impossible stays impossible and the time without the boundary
+                        // term only grows, so those end the loop; a stage that is only too slow because of
+                        // the boundary term of its last layer is skipped, not the rest of the run
+                        for (int w = p + 1; w <= L; ++w) {
+                            const long long tt = s_col[(w - p - 1) * M + dd - 1];
+                            if (tt < 0) break;
+                            if (tt > tau) {
+                                if (w == L || tt - bnd[w - 1] > tau) break;
+                                continue;
+                            }
+                            const long long x = Suf[(size_t)w * plane + src] + wsuf * tt + stau * tau;
+                            m = x < m ? x : m;
                         }
-                        const long long x = Suf[(size_t)w * W + E0] + 2 * tt - tau;
-                        m = x < m ? x : m;
                     }
-                }
-                Suf[(size_t)p * W + E] = m;
+                Suf[(size_t)p * plane + i] = m;
             }
         }
         __syncthreads();
         // the slowest stage at every place it fits, for every template
-        for (int D = threadIdx.x; D + d < W; D += kThreads) {
+        for (size_t i = threadIdx.x; i < plane; i += kThreads) {
+            const int D = (int)(i / J), j1 = (int)(i % J);
+            if (D + d > a.Dmax) continue;
             if (D % M + d > M) continue;
-            const long long pre = Pre[(size_t)u * W + D];
+            const long long pre = Pre[(size_t)u * plane + i];
             if (pre >= kInf / 2) continue;
             for (int n = a.n_min; n <= a.n_max; ++n) {
                 const int E = n * M - D - d;
                 if (E < 0) continue;
-                const long long suf = Suf[(size_t)v * W + E];
-                if (suf >= kInf / 2) continue;
-                const long long tot = pre + (long long)a.Nb * tau + suf;
-                if (tot < s_best[n - a.n_min]) atomicMin((unsigned long long *)&s_best[n - a.n_min], (unsigned long long)tot);
+                if (!STAGED) {
+                    if (a.Nb > 0 && a.Nb < min(L, n * M)) continue;
+                    const long long suf = Suf[(size_t)v * plane + E];
+                    if (suf >= kInf / 2) continue;
+                    const long long tot = pre + (a.Nb > 0 ? (long long)a.Nb : 4ll) * tau + suf;
+                    if (tot < s_best[n - a.n_min]) atomicMin((unsigned long long *)&s_best[n - a.n_min], (unsigned long long)tot);
+                } else {
+                    for (int j2 = 0; j1 + 1 + j2 <= a.Smax; ++j2) {
+                        const long long suf = Suf[(size_t)v * plane + (size_t)E * J + j2];
+                        if (suf >= kInf / 2) continue;
+                        const long long coef = a.Nb > 0 ? (long long)a.Nb - j2 : 4ll * j1 + 4 + 3ll * j2;
+                        const long long tot = pre + coef * tau + 2 * suf;
+                        if (tot < s_best[n - a.n_min]) atomicMin((unsigned long long *)&s_best[n - a.n_min], (unsigned long long)tot);
+                    }
+                }
             }
         }
     }
     __syncthreads();
     for (int i = threadIdx.x; i < count; i += kThreads)
-        if (s_best[i] < kInf) atomicMin((unsigned long long *)&a.best[i], (unsigned long long)s_best[i]);
+        if (s_best[i] < kInf) atomicMin(&a.best[i], (unsigned long long)s_best[i]);
 }
 
-__global__ void k_exact_finish(long long *best, int count) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < count && best[i] >= kInf / 2) best[i] = -1;
-}
+inline size_t slot_bytes(int L, int Dmax, int J) { return align_up(sizeof(long long) * 2 * (size_t)(L + 1) * (Dmax + 1) * J); }
 
 } // namespace oob_exact
 
@@ -202,37 +498,88 @@ static bool exact_dims_ok(int L, int n_max, int M) {
     return L >= 1 && L <= OOB_EXACT_MAX_L && n_max >= 1 && M >= 1 && M <= OOB_MAX_GPUS &&
            (long long)n_max * M <= OOB_EXACT_MAX_GPUS;
 }
+static int exact_smax(int L, int n_max, int M, int Nb) {
+    int s = L < n_max * M ? L : n_max * M;
+    return Nb > 0 && Nb < s ? Nb : s;
+}
 
 extern "C" size_t oob_exact_workspace_size(int L, int n_max, int gpus_per_node) {
     using namespace oob_exact;
     if (!exact_dims_ok(L, n_max, gpus_per_node)) return 0;
-    return table_bytes(L, gpus_per_node) + (size_t)kSlots * slot_bytes(L, n_max * gpus_per_node);
+    size_t n = head_bytes(L, gpus_per_node);
+    if (lds_waves(L, gpus_per_node, n_max, n_max) == 0) // tables beyond LDS: the general path
+        n += (size_t)kFlatSlots * slot_bytes(L, n_max * gpus_per_node, 1);
+    return n;
+}
+
+extern "C" size_t oob_exact_staged_workspace_size(int L, int n_max, int gpus_per_node, int microbatches) {
+    using namespace oob_exact;
+    if (!exact_dims_ok(L, n_max, gpus_per_node) || microbatches < 0) return 0;
+    const size_t slot = slot_bytes(L, n_max * gpus_per_node, exact_smax(L, n_max, gpus_per_node, microbatches) + 1);
+    const size_t want = (size_t)1 << 30; // about a gigabyte of tables, at least 16 and at most kFlatSlots workgroups in flight
+    size_t slots = want / slot;
+    slots = slots < 16 ? 16 : slots > (size_t)kFlatSlots ? (size_t)kFlatSlots : slots;
+    return head_bytes(L, gpus_per_node) + slots * slot;
+}
+
+static int exact_launch(const oob_profile *profile, int L, int n_min, int n_max, int M, int microbatches, int64_t mem_cap,
+                        void *dev_workspace, size_t workspace_bytes, int64_t *best, int32_t *status, void *stream,
+                        bool staged) {
+    using namespace oob_exact;
+    if (!profile || !profile->fwd_ns || !profile->bwd_ns || !profile->mem_bytes || !profile->boundary_ns) return OOB_EINVAL;
+    if (!best || !status || !dev_workspace || ((uintptr_t)dev_workspace & 255) != 0) return OOB_EINVAL;
+    if (n_min < 1 || n_min > n_max || mem_cap <= 0 || microbatches < 0 || !exact_dims_ok(L, n_max, M)) return OOB_EINVAL;
+    const int count = n_max - n_min + 1, Dmax = n_max * M;
+    Args a;
+    a.prof = *profile; a.L = L; a.M = M; a.n_min = n_min; a.n_max = n_max; a.Nb = microbatches; a.Dmax = Dmax;
+    a.Smax = exact_smax(L, n_max, M, microbatches);
+    a.cap = mem_cap;
+    char *ws = (char *)dev_workspace;
+    a.counter = (unsigned *)ws;
+    a.t = (long long *)(ws + 256);
+    a.td = (double *)(ws + 256 + align_up(8 * table_entries(L, M)));
+    a.slots = (long long *)(ws + head_bytes(L, M));
+    a.best = (unsigned long long *)best; a.status = status;
+    hipStream_t st = (hipStream_t)stream;
+    const int nw = staged ? 0 : lds_waves(L, M, n_max, count);
+    const int J = staged ? a.Smax + 1 : 1;
+    size_t slots = 0;
+    if (nw == 0) {
+        if (workspace_bytes < head_bytes(L, M) + 16 * slot_bytes(L, Dmax, J)) return OOB_ECAPACITY;
+        slots = (workspace_bytes - head_bytes(L, M)) / slot_bytes(L, Dmax, J);
+        if (slots > (size_t)kFlatSlots) slots = kFlatSlots;
+    } else if (workspace_bytes < head_bytes(L, M)) return OOB_ECAPACITY;
+    a.limit = nw ? kDoubleExact : kInf;
+    hipLaunchKernelGGL(k_exact_init, dim3(1), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL(k_exact_stages, dim3((L * M + 63) / 64), dim3(64), 0, st, a);
+    const long long ncand = (long long)L * (L + 1) / 2 * M;
+    if (nw) {
+        const size_t lds = lds_bytes(L, M, n_max, count, nw);
+        if (lds > 64 * 1024 &&
+            hipFuncSetAttribute((const void *)k_exact_lds, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return OOB_EHIP;
+        const unsigned grid = (unsigned)(ncand < 512 ? ncand : 512); // two rounds of workgroups per compute unit; a counter hands out the work
+        hipLaunchKernelGGL(k_exact_lds, dim3(grid), dim3(nw * 64), lds, st, a);
+    } else {
+        const unsigned grid = (unsigned)(ncand < (long long)slots ? ncand : (long long)slots);
+        const size_t lds = sizeof(long long) * ((size_t)L * M + count);
+        if (staged) hipLaunchKernelGGL(k_exact_flat<true>, dim3(grid), dim3(kThreads), lds, st, a);
+        else        hipLaunchKernelGGL(k_exact_flat<false>, dim3(grid), dim3(kThreads), lds, st, a);
+    }
+    hipLaunchKernelGGL(k_exact_finish, dim3((count + 63) / 64), dim3(64), 0, st, a, nw ? 1 : 0, staged ? 1 : 0);
+    return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
 }
 
 extern "C" int oob_exact_minimum(const oob_profile *profile, int L, int n_min, int n_max, int gpus_per_node,
                                  int microbatches, int64_t mem_cap, void *dev_workspace, size_t workspace_bytes,
                                  int64_t *best, int32_t *status, void *stream) {
-    using namespace oob_exact;
-    if (!profile || !profile->fwd_ns || !profile->bwd_ns || !profile->mem_bytes || !profile->boundary_ns) return OOB_EINVAL;
-    if (!best || !status || !dev_workspace || ((uintptr_t)dev_workspace & 255) != 0) return OOB_EINVAL;
-    if (n_min < 1 || n_min > n_max || mem_cap <= 0 || !exact_dims_ok(L, n_max, gpus_per_node)) return OOB_EINVAL;
-    const int M = gpus_per_node, Dmax = n_max * M;
-    if (microbatches < (L < Dmax ? L : Dmax)) return OOB_EINVAL; // the limit S <= N_b is not modelled
-    if (workspace_bytes < oob_exact_workspace_size(L, n_max, M)) return OOB_ECAPACITY;
-    Args a;
-    a.prof = *profile; a.L = L; a.M = M; a.n_min = n_min; a.n_max = n_max; a.Nb = microbatches; a.Dmax = Dmax;
-    a.cap = mem_cap;
-    a.t = (long long *)dev_workspace;
-    a.slots = (long long *)((char *)dev_workspace + table_bytes(L, M));
-    a.best = (long long *)best; a.status = status;
-    hipStream_t st = (hipStream_t)stream;
-    const int count = n_max - n_min + 1;
-    hipLaunchKernelGGL(k_exact_init, dim3(1), dim3(kThreads), 0, st, a);
-    hipLaunchKernelGGL(k_exact_stages, dim3((L * M + 63) / 64), dim3(64), 0, st, a);
-    const long long ncand = (long long)L * (L + 1) / 2 * M;
-    const unsigned grid = (unsigned)(ncand < kSlots ? ncand : kSlots);
-    const size_t lds = sizeof(long long) * ((size_t)L * M + count);
-    hipLaunchKernelGGL(k_exact, dim3(grid), dim3(kThreads), lds, st, a);
-    hipLaunchKernelGGL(k_exact_finish, dim3((count + 63) / 64), dim3(64), 0, st, (long long *)best, count);
-    return hipGetLastError() == hipSuccess ? OOB_OK : OOB_EHIP;
+    return exact_launch(profile, L, n_min, n_max, gpus_per_node, microbatches, mem_cap, dev_workspace, workspace_bytes,
+                        best, status, stream, false);
+}
+
+extern "C" int oob_exact_minimum_staged(const oob_profile *profile, int L, int n_min, int n_max, int gpus_per_node,
+                                        int microbatches, int64_t mem_cap, void *dev_workspace, size_t workspace_bytes,
+                                        int64_t *best, int32_t *status, void *stream) {
+    return exact_launch(profile, L, n_min, n_max, gpus_per_node, microbatches, mem_cap, dev_workspace, workspace_bytes,
+                        best, status, stream, true);
 }

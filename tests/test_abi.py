@@ -34,7 +34,8 @@ def test_library_exports_every_declared_symbol():
     assert dist == ["oob_dist_choose", "oob_dist_solve"] and all(hasattr(lib, n) for n in dist)
     assert sorted(B.DIST_SYMBOLS) == dist
     exact = declared_symbols("oob_exact.h", "oob_exact_")
-    assert exact == ["oob_exact_minimum", "oob_exact_workspace_size"] and all(hasattr(lib, n) for n in exact)
+    assert exact == ["oob_exact_minimum", "oob_exact_minimum_staged", "oob_exact_staged_workspace_size",
+                     "oob_exact_workspace_size"] and all(hasattr(lib, n) for n in exact)
     assert sorted(B.EXACT_SYMBOLS) == exact
     assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["oob_dist.h", "oob_exact.h", "oob_inst.h", "oob_plan.h",
                                                                   "oob_reconf.h"]
@@ -49,9 +50,16 @@ def test_exact_minimum_entry_point_validates_arguments_without_touching_the_gpu(
                                             kw.get("M", 2), kw.get("nb", 8), kw.get("cap", 1 << 30), kw.get("ws", fake),
                                             kw.get("nbytes", 1 << 40), kw.get("best", fake), kw.get("st", fake), 0)
     for bad in (dict(prof=None), dict(L=0), dict(L=256), dict(n_min=0), dict(n_min=5), dict(M=0), dict(cap=0),
-                dict(ws=0), dict(ws=0x10001), dict(best=0), dict(st=0), dict(nb=7)):   # nb = 7 < min(L, n_max M) = 8
+                dict(ws=0), dict(ws=0x10001), dict(best=0), dict(st=0), dict(nb=-1)):
         assert call(**bad) == P.OOB_EINVAL, bad
     assert call(nbytes=1024) == P.OOB_ECAPACITY
+    # the workspace of the entry point without stage counts is the two stage-time tables while its tables
+    # fit LDS; the staged entry point wants at least 16 workgroups' worth of tables
+    assert P.oob_exact_workspace_size(98, 64, 8) < (2 << 20) and P.oob_exact_workspace_size(250, 16, 8) > (1 << 28)
+    assert P.oob_exact_staged_workspace_size(40, 8, 4, 16) % 256 == 0 and P.oob_exact_staged_workspace_size(40, 8, 4, -1) == 0
+    staged = lambda **kw: P.oob_exact_minimum_staged(prof, 12, 1, 4, 2, kw.get("nb", 3), 1 << 30, fake,
+                                                     kw.get("nbytes", 1 << 40), fake, fake, 0)
+    assert staged(nb=-1) == P.OOB_EINVAL and staged(nbytes=4096) == P.OOB_ECAPACITY
 
 
 def test_reconfiguration_entry_point_validates_arguments_without_touching_the_gpu():

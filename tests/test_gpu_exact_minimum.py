@@ -59,6 +59,43 @@ def test_stage_times_that_are_not_monotone_in_the_last_layer(P):
         assert st == P.OOB_OK and got == E.exact_minimum(inp), seed
 
 
+MODE_SHAPES = [(7, 3, 1, 2, 0), (6, 2, 1, 3, 0), (8, 1, 1, 4, 0), (12, 4, 1, 3, 0), (25, 8, 1, 4, 0), (40, 2, 1, 9, 0),
+               (7, 1, 1, 4, 3), (7, 2, 1, 3, 4), (8, 2, 1, 3, 3), (6, 4, 1, 2, 3), (14, 4, 1, 4, 6), (20, 2, 2, 6, 7),
+               (9, 3, 1, 2, 2), (16, 8, 1, 2, 5)]
+
+
+@pytest.mark.parametrize("shape", MODE_SHAPES)
+def test_4S_mode_and_stage_limit_against_the_oracle(P, shape):
+    """N_b = 4 S per pipeline (microbatches = 0) and N_b below min(L, n M), where the limit S <= N_b
+    binds: the entry point with the stage count in its tables against the oracle that carries it too;
+    the one without it against the oracle without it on the templates it answers for, -2 on the others."""
+    L, M, n_min, n_max, nb = shape
+    for seed in range(3):
+        for var in ("plain", "tight", "forbid"):
+            inp = inputs.random_small(seed, L, M, n_min, n_max, nb, f=1, tight_mem=(var == "tight"),
+                                      forbid_some_d=(var == "forbid"))
+            print("case", inp.name, shape, var, flush=True)
+            st, got = P.ExactMinimum(inp, staged=True).run()
+            assert st == P.OOB_OK and got == E.exact_minimum_staged(inp), (shape, seed, var)
+            st, got = P.ExactMinimum(inp).run()
+            want = E.exact_minimum(inp, allow_bound=True)
+            want = [w if E.is_tight(inp, n_min + i) else P.OOB_EXACT_LIMIT_CAN_BIND for i, w in enumerate(want)]
+            assert st == P.OOB_OK and got == want, (shape, seed, var)
+
+
+def test_shapes_beyond_lds_take_the_general_path(P):
+    """More layers or GPUs per node than the LDS tables hold: the recurrence over tables in the
+    workspace, same results."""
+    for shape in [(200, 2, 1, 2, 200), (120, 48, 1, 1, 0), (140, 1, 1, 3, 140), (150, 2, 1, 2, 0)]:
+        L, M, n_min, n_max, nb = shape
+        inp = inputs.random_small(7, L, M, n_min, n_max, nb, f=1, tight_mem=True)
+        print("case", shape, flush=True)
+        if shape[0] >= 200 or shape[1] >= 48:
+            assert P.oob_exact_workspace_size(L, n_max, M) > (16 << 20)   # tables of the workgroups in flight
+        st, got = P.ExactMinimum(inp).run()
+        assert st == P.OOB_OK and got == E.exact_minimum(inp), shape
+
+
 @pytest.mark.parametrize("cfg", [1, 2, 3])
 def test_configurations_1_to_3(P, cfg):
     inp = inputs.config(cfg)
@@ -110,9 +147,16 @@ def test_status_for_times_too_large_to_be_exact(P):
     import dataclasses
 
     inp = inputs.random_small(4, 8, 2, 1, 3, 8)
-    big = dataclasses.replace(inp, fwd_ns=inp.fwd_ns + (1 << 57))  # (N_b + 2) * 8 * 2^57 >= 2^61
+    # tables in LDS hold doubles: (N_b + 2) * sum of the layers' slowest times must stay below 2^52
+    big = dataclasses.replace(inp, fwd_ns=inp.fwd_ns + (1 << 50))
     st, _ = P.ExactMinimum(big).run()
     assert st == P.OOB_EOVERFLOW
-    ok = dataclasses.replace(inp, fwd_ns=inp.fwd_ns + (1 << 50))
+    ok = dataclasses.replace(inp, fwd_ns=inp.fwd_ns + (1 << 44))
     st, got = P.ExactMinimum(ok).run()
     assert st == P.OOB_OK and got == E.exact_minimum(ok)
+    # tables in the workspace hold int64: below 2^61
+    st, got = P.ExactMinimum(big, staged=True).run()
+    assert st == P.OOB_OK and got == E.exact_minimum_staged(big)
+    huge = dataclasses.replace(inp, fwd_ns=inp.fwd_ns + (1 << 57))
+    st, _ = P.ExactMinimum(huge, staged=True).run()
+    assert st == P.OOB_EOVERFLOW
