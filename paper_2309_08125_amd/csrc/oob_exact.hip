@@ -174,19 +174,29 @@ __device__ void one_side(const Args &a, const Lds &s, int e, double tau, double 
         const int p = i / M, dd = i % M + 1;
         int r = p;
         if (!MIRROR) {
-            if (p >= 1 && p <= e)
-                for (int q = p - 1; q >= 0; --q) { // [q, p) only gets slower and heavier as q goes down
-                    const double tt = a.td[((size_t)q * (L + 1) + p) * M + dd - 1];
-                    if (tt < 0.0 || tt >= tau) break;
-                    r = q;
+            if (p >= 1 && p <= e) {
+                // [x, p) only gets slower and heavier as x goes down (impossible at the far end): the stages
+                // with 0 <= t < tau are x = r .. p-1; bisection for r
+                int lo = 0, hi = p; // answer in [lo, hi]; hi = p: none
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    const double tt = a.td[((size_t)mid * (L + 1) + p) * M + dd - 1];
+                    if (tt >= 0.0 && tt < tau) hi = mid; else lo = mid + 1;
                 }
+                r = lo;
+            }
         } else {
-            if (p >= e && p < L)
-                for (int w = p + 1; w <= L; ++w) { // impossible stays impossible, the time without the boundary term only grows
-                    const double tt = a.td[((size_t)p * (L + 1) + w) * M + dd - 1];
-                    if (tt < 0.0 || tt - (w < L ? s.bnd[w - 1] : 0.0) > tau) break;
-                    r = w;
+            if (p >= e && p < L) {
+                // [p, w) as w goes up: impossible stays impossible and the time without the boundary term only
+                // grows: those stages are w = p+1 .. r; bisection for r
+                int lo = p, hi = L; // answer in [lo, hi]; lo = p: none
+                while (lo < hi) {
+                    const int mid = (lo + hi + 1) >> 1;
+                    const double tt = a.td[((size_t)p * (L + 1) + mid) * M + dd - 1];
+                    if (tt >= 0.0 && tt - (mid < L ? s.bnd[mid - 1] : 0.0) <= tau) lo = mid; else hi = mid - 1;
                 }
+                r = lo;
+            }
         }
         s.lo[i] = r;
     }
@@ -207,9 +217,16 @@ __device__ void one_side(const Args &a, const Lds &s, int e, double tau, double 
         for (int g = lane; g <= M; g += 64) G[g] = g == 0 ? 0.0 : kNone;
         wave_sync();
         const int rows = MIRROR ? q - e : e - q;
+        int lastfin = q; // the layer farthest from q that some number of GPUs can be made to reach
         for (int r = 1; r <= rows; ++r) {
             const int p = MIRROR ? q - r : q + r;
             const int far = MIRROR ? min(q, s.lomin[p]) : max(q, s.lomin[p]); // farthest layer any stage of this row reaches
+            if (MIRROR ? lastfin > far : lastfin < far) { // no stage of this row starts from a layer the table has reached
+                for (int g = lane; g <= M; g += 64) G[r * (M + 1) + g] = kNone;
+                wave_sync();
+                continue;
+            }
+            bool fin = false;
             for (int gt = 0; gt * 8 < M; ++gt) {
                 const int g = gt * 8 + gi + 1;
                 double acc = kNone;
@@ -245,8 +262,10 @@ __device__ void one_side(const Args &a, const Lds &s, int e, double tau, double 
                 acc = fmin(acc, shfl_xor_f64(acc, 2));
                 acc = fmin(acc, shfl_xor_f64(acc, 4));
                 if (di == 0 && g <= M) G[r * (M + 1) + g] = acc;
+                fin = fin || acc < kNone;
             }
             if (lane == 0) G[r * (M + 1)] = kNone;
+            if (__any(fin)) lastfin = p; // the same in every lane
             wave_sync();
         }
         // a whole node covering [q, p) (prefix) / [p, q) (suffix), and the partial covers next to the slowest stage
@@ -265,7 +284,10 @@ __device__ void one_side(const Args &a, const Lds &s, int e, double tau, double 
     for (int p = threadIdx.x; p <= L; p += blockDim.x) cur[p] = p == origin ? 0.0 : kNone;
     __syncthreads();
     const int h4 = threadIdx.x & 3;
-    for (int c = 0; c < a.n_max; ++c) {
+    // a node covers at least one layer: more whole nodes than the side has layers cover nothing
+    const int cend = min(a.n_max, (MIRROR ? L - e : e) + 1);
+    for (int i = threadIdx.x + cend * M; i < a.n_max * M; i += blockDim.x) OUT[i] = kNone;
+    for (int c = 0; c < cend; ++c) {
         // OUT[c][g] from NP_c, and NP_{c+1} from NP_c, in one phase
         for (int i = threadIdx.x; i < M * 4; i += blockDim.x) { // four threads per g
             const int g = i >> 2;
@@ -277,7 +299,7 @@ __device__ void one_side(const Args &a, const Lds &s, int e, double tau, double 
             m = fmin(m, shfl_xor_f64(m, 2));
             if (h4 == 0) OUT[c * M + g] = m;
         }
-        if (c + 1 < a.n_max) {
+        if (c + 1 < cend) {
             const int np = MIRROR ? L - e + 1 : e + 1; // layers of the side, origin included
             for (int i = threadIdx.x; i < ((np * 4 + 63) & ~63); i += blockDim.x) { // whole waves: the shuffles need every lane
                 const int pi = i >> 2;
