@@ -142,48 +142,109 @@ def bench_instantiation(P, inp, res, reps=20):
                          "kernel": "k_inst_unrank", "bytes_per_vector": 2 * p}}
 
 
-def bench_exact(P, inp, res, reps=3):
-    """The exact minimum of the template cost for every template of the workload, and the gap of the
-    recursion's result to it.  Timed with events on the stream the kernels are launched on; the
-    oracle (all host cores) is timed on the same job when that takes seconds, else on a part of it."""
+def exact_relaxations(inp):
+    """Relaxations (one stage appended to one partial cover: an add and a min) that the exact-minimum
+    kernel evaluates on this job, counted on the host from the stage times alone: for every possible
+    slowest stage (u, v, d) with time tau, the one-node tables before u and after v -- a stage on dd
+    GPUs into layer p reaches back over the layers whose stage time stays below tau (at most to the
+    table's start layer q) and serves M - dd + 1 GPU counts -- plus the node-level recurrences.
+    Returns (possible slowest stages, one-node relaxations, node-level relaxations)."""
+    import numpy as np
+
+    L, M, n_max = inp.L, inp.gpus_per_node, inp.n_max
+    fb = (inp.fwd_ns + inp.bwd_ns).astype(np.float64)
+    forb = (inp.fwd_ns >= (1 << 62)) | (inp.bwd_ns >= (1 << 62))
+    fb[forb] = 0
+    PT = np.vstack([np.zeros((1, M)), np.cumsum(fb, axis=0)])
+    PF = np.vstack([np.zeros((1, M)), np.cumsum(forb, axis=0)])
+    PM = np.concatenate([[0], np.cumsum(inp.mem_bytes.astype(np.int64))])
+    d = np.arange(1, M + 1)
+    t0 = np.full((L + 1, L + 1, M), np.inf)  # stage time without the boundary term, inf = impossible
+    for u in range(L):
+        for v in range(u + 1, L + 1):
+            ok = (PF[v] - PF[u] == 0) & (-(-(PM[v] - PM[u]) // d) <= inp.mem_cap)
+            t0[u, v, ok] = (PT[v] - PT[u])[ok]
+    bnd = np.concatenate([[0], inp.boundary_ns.astype(np.float64)])
+    bnd[L] = 0
+    t = t0 + bnd[None, :, None]
+    uu, vv, dd = np.nonzero(np.isfinite(t))
+    taus = t[uu, vv, dd]
+    w = (M - d + 1).astype(np.float64)
+
+    def h(cnt, j):  # sum_{i=1..j} min(cnt, i): the table starts q = p-1 .. p-j against a reach of cnt layers
+        c = np.minimum(cnt, j)
+        return c * (c + 1) / 2 + c * (j - c)
+
+    pre_rows = np.zeros((len(taus), L + 1))
+    suf_rows = np.zeros((len(taus), L + 1))
+    for p in range(1, L + 1):
+        for k in range(M):
+            pre_rows[:, p] += w[k] * h(np.searchsorted(t[p - 1::-1, p, k], taus, side="left"), p)
+    for p in range(L):
+        for k in range(M):
+            suf_rows[:, p] += w[k] * h(np.searchsorted(t0[p, p + 1:, k], taus, side="right"), L - p)
+    pre = np.cumsum(pre_rows, axis=1)[np.arange(len(taus)), uu]
+    suf = np.cumsum(suf_rows[:, ::-1], axis=1)[:, ::-1][np.arange(len(taus)), vv]
+    lu, lv = uu.astype(np.float64), (L - vv).astype(np.float64)
+    node = (np.minimum(n_max, lu + 1) * (lu * (lu + 1) / 2 + (M - 1) * lu) +
+            np.minimum(n_max, lv + 1) * (lv * (lv + 1) / 2 + (M - 1) * lv))
+    return len(taus), float(pre.sum() + suf.sum()), float(node.sum())
+
+
+def bench_exact(P, planner, inp, res, reps=3):
+    """The exact minimum of the template cost for every template of the workload, under the workload's
+    N_b and under N_b = 4 S (the paper's planning-time choice), and the gap of the recursion's result
+    to each.  Timed with events on the stream the kernels are launched on; the oracle (all host cores)
+    is timed on the same job when that takes seconds, else on a part of it."""
     import torch
     from oracle import capi, exact_minimum
 
-    if inp.microbatches < min(inp.L, inp.n_max * inp.gpus_per_node):
-        return None
-    ex = P.ExactMinimum(inp)
+    out = {}
     stream = torch.cuda.current_stream()
-    st, got = ex.run()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    ev[0].record(stream)
-    for _ in range(reps):
-        ex.enqueue()
-    ev[1].record(stream)
-    torch.cuda.synchronize()
-    dt = ev[0].elapsed_time(ev[1]) / reps * 1e-3
-    assert st == P.OOB_OK, "exact minimum"
-    gaps = [int(res["T"][i]) / e - 1 for i, e in enumerate(got) if e is not None]
+    for mode, job, plan in (("given_nb", inp, res),
+                            ("nb_4S", dataclasses.replace(inp, microbatches=0), None)):
+        if plan is None:
+            plan = planner.plan(job)
+        ex = P.ExactMinimum(job)
+        st, got = ex.run()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record(stream)
+        for _ in range(reps):
+            ex.enqueue()
+        ev[1].record(stream)
+        torch.cuda.synchronize()
+        dt = ev[0].elapsed_time(ev[1]) / reps * 1e-3
+        assert st == P.OOB_OK, "exact minimum"
+        answered = [(i, e) for i, e in enumerate(got) if e is not None and e != P.OOB_EXACT_LIMIT_CAN_BIND]
+        gaps = [int(plan["T"][i]) / e - 1 for i, e in answered]
+        assert all(g >= 0 for g in gaps), "the recursion below the exact minimum"
+        out[mode] = {"ms": dt * 1e3, "templates_answered": len(answered), "templates": len(got),
+                     "recursion_gap_max": max(gaps) if gaps else None,
+                     "recursion_exact_for": sum(g == 0 for g in gaps)}
+        if mode == "given_nb":
+            got_given, dt_given = got, dt
     small = dataclasses.replace(inp, n_max=min(inp.n_max, inp.n_min + 7)) if capi.lib().oob_oracle_threads() < 16 else inp
     t0 = time.time()
-    want = exact_minimum.exact_minimum(small)
+    want = exact_minimum.exact_minimum(small, allow_bound=True)
     t_cpu = time.time() - t0
-    assert want == got[: len(want)], "exact minimum against the oracle"
-    L, M, Dmax = inp.L, inp.gpus_per_node, inp.n_max * inp.gpus_per_node
-    cand = L * (L + 1) // 2 * M
-    # relaxations the two tables of a candidate take: (earlier layer, GPU count, position) triples per layer
-    per_layer_pair = sum(sum(1 for D0 in range(0, Dmax - dd + 1) if D0 % M + dd <= M) for dd in range(1, M + 1))
-    relax = sum(M * per_layer_pair * (u * (u + 1) // 2 + (L - v) * (L - v + 1) // 2)
-                for u in range(L) for v in range(u + 1, L + 1))
-    ops = 8  # per relaxation: 64-bit add, compare and select (2 lane-ops each) and the test of the stage time
-    return {"workload": f"{len(got)} templates, {cand} candidate slowest stages, tables of {L + 1} x "
-                        f"{Dmax + 1} positions, {relax} relaxations",
-            "ms": dt * 1e3, "value": len(got) / dt, "unit": "templates/s",
-            "roofline": {"bound": "alu", "achieved": relax * ops / dt / 1e12, "peak": PEAK_LANE_OPS / 1e12,
-                         "unit": "T lane-op/s", "frac": relax * ops / dt / PEAK_LANE_OPS, "traffic": None,
-                         "kernel": "k_exact", "ops_per_relaxation": ops, "relaxations_per_s": relax / dt},
-            "recursion_gap_max": max(gaps) if gaps else None, "recursion_exact_for": sum(g == 0 for g in gaps),
-            "cpu_baseline": {"seconds": t_cpu, "cores": capi.lib().oob_oracle_threads(), "kind": "oracle",
-                             "sample": f"templates for {small.n_min}..{small.n_max} nodes"}}
+    tight = [exact_minimum.is_tight(small, n) for n in range(small.n_min, small.n_max + 1)]
+    assert [w for w, ok in zip(want, tight) if ok] == [g for g, ok in zip(got_given, tight) if ok], \
+        "exact minimum against the oracle"
+    ncand, relax_node_tables, relax_node_level = exact_relaxations(inp)
+    relax = relax_node_tables + relax_node_level
+    ops = 2  # per relaxation: one fp64 add and one fp64 min
+    out.update({
+        "workload": f"{len(got_given)} templates, {ncand} possible slowest stages, {relax:.4g} relaxations "
+                    f"({relax_node_tables:.4g} in one-node tables, {relax_node_level:.4g} node-level), counted on the host",
+        "ms": dt_given * 1e3, "value": len(got_given) / dt_given, "unit": "templates/s",
+        "roofline": {"bound": "alu", "achieved": relax * ops / dt_given / 1e12, "peak": PEAK_LANE_OPS / 1e12,
+                     "unit": "T fp64 lane-instr/s", "frac": relax * ops / dt_given / PEAK_LANE_OPS, "traffic": None,
+                     "kernel": "k_exact_lds", "ops_per_relaxation": ops, "relaxations_per_s": relax / dt_given,
+                     "note": "relaxations actually evaluated (host count); the kernel is bound by LDS and "
+                             "dependent-load latency at two waves per SIMD, not by the vector ALUs"},
+        "cpu_baseline": {"seconds": t_cpu, "cores": capi.lib().oob_oracle_threads(), "kind": "oracle",
+                         "sample": f"templates for {small.n_min}..{small.n_max} nodes, N_b = {inp.microbatches}"}})
+    return out
 
 
 def bench_distribution(P, inp, res, Q=512, reps=3, oracle_sample=40):
@@ -287,6 +348,48 @@ def bench_reconfiguration(P, inp, res, trajectories=1 << 20, reps=5, oracle_samp
                              "sample": f"{oracle_sample} of the sequences"}}
 
 
+def batch_exact_gaps(P, insts, results, staged_instances=4):
+    """Gap of the recursion to the exact minimum over the batched workload.  The kernel without stage
+    counts answers for the templates whose limit S <= N_b cannot bind (all templates of the instances
+    with L <= N_b, the templates up to N_b / M nodes of the others); the kernel with stage counts, whose
+    work grows with the fourth power of L, answers for every template of the few shortest instances
+    beyond that."""
+    import torch
+
+    t0 = time.time()
+    gaps, answered, total = [], 0, 0
+    for inp, res in zip(insts, results):
+        st, got = P.ExactMinimum(inp).run()
+        assert st == P.OOB_OK
+        for i, e in enumerate(got):
+            total += 1
+            if e is not None and e != P.OOB_EXACT_LIMIT_CAN_BIND:
+                answered += 1
+                gaps.append(int(res["T"][i]) / e - 1)
+    t_fast = time.time() - t0
+    assert min(gaps) >= 0
+    out = {"without_stage_counts": {"instances": len(insts), "templates": total, "templates_answered": answered,
+                                    "recursion_gap_max": max(gaps), "recursion_gap_mean": sum(gaps) / len(gaps),
+                                    "recursion_exact_for": sum(g == 0 for g in gaps), "seconds": round(t_fast, 2)}}
+    order = sorted((k for k, i in enumerate(insts) if i.L > i.microbatches), key=lambda k: insts[k].L)[:staged_instances]
+    gaps, t0 = [], time.time()
+    for k in order:
+        inp = insts[k]
+        nbytes = P.oob_exact_staged_workspace_size(inp.L, inp.n_max, inp.gpus_per_node, inp.microbatches)
+        st, got = P.ExactMinimum(inp, staged=True, workspace_bytes=8 * nbytes).run()
+        assert st == P.OOB_OK
+        gaps += [int(results[k]["T"][i]) / e - 1 for i, e in enumerate(got) if e is not None]
+        torch.cuda.empty_cache()
+    if order:
+        assert min(gaps) >= 0
+        out["with_stage_counts"] = {"instances": [insts[k].name for k in order], "L": [insts[k].L for k in order],
+                                    "templates_answered": len(gaps), "recursion_gap_max": max(gaps),
+                                    "recursion_gap_mean": sum(gaps) / len(gaps),
+                                    "recursion_exact_for": sum(g == 0 for g in gaps),
+                                    "seconds": round(time.time() - t0, 2)}
+    return out
+
+
 def bench_batch(P, insts, args):
     """Configuration 5: 256 independent instances through oob_plan_templates_batch, profiles
     resident in HBM; a step is the whole batch."""
@@ -318,6 +421,7 @@ def bench_batch(P, insts, args):
     states = sum(o.c.states for o in outs)
     cands = sum(o.c.candidates for o in outs)
     achieved = cands * FP64_OPS_PER_CANDIDATE * args.steps / elapsed
+    exact = batch_exact_gaps(P, insts, [o.to_host() for o in outs]) if not args.no_exact else None
     print(json.dumps({
         "metric": "DP states/sec (wall-ms per batch of 256 instances in ms_per_step)",
         "value": states * args.steps / elapsed, "unit": "states/s", "n_gpus": 1, "steps": args.steps,
@@ -330,7 +434,8 @@ def bench_batch(P, insts, args):
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12,
                      "unit": "T fp64 lane-instr/s", "frac": achieved / PEAK_LANE_OPS, "traffic": None,
                      "kernel": "whole batched call (all kernels, host enqueue included)",
-                     "ops_per_candidate": FP64_OPS_PER_CANDIDATE}}))
+                     "ops_per_candidate": FP64_OPS_PER_CANDIDATE},
+        "exact_minimum": exact}))
 
 
 def main():
@@ -345,6 +450,7 @@ def main():
     ap.add_argument("--paper-nb", action="store_true",
                     help="N_b = 4 S' per state (the paper's planning-time choice) instead of the configuration's N_b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-exact", action="store_true", help="--config 5 only: skip the exact-minimum gaps")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="before the steps, run one device-to-device copy of this many MiB (a plain "
                          "copy kernel of known size, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -444,7 +550,7 @@ def main():
     line["instantiation"] = bench_instantiation(P, inp, res)
     line["reconfiguration"] = bench_reconfiguration(P, inp, res)
     line["distribution"] = bench_distribution(P, inp, res)
-    line["exact_minimum"] = bench_exact(P, inp, res)
+    line["exact_minimum"] = bench_exact(P, planner, inp, res)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(inp)
     print(json.dumps(line))

@@ -83,6 +83,16 @@ def test_4S_mode_and_stage_limit_against_the_oracle(P, shape):
             assert st == P.OOB_OK and got == want, (shape, seed, var)
 
 
+def test_stage_limit_at_middle_sizes(P):
+    """Tables of 49 x 65 x 21 and 65 x 65 x 33 entries per workgroup, many workgroups in flight."""
+    for shape in [(24, 4, 1, 6, 10), (36, 2, 2, 12, 14), (48, 8, 1, 8, 20), (64, 4, 1, 16, 32)]:
+        L, M, n_min, n_max, nb = shape
+        inp = inputs.random_small(1, L, M, n_min, n_max, nb, f=1)
+        print("case", shape, flush=True)
+        st, got = P.ExactMinimum(inp, staged=True).run()
+        assert st == P.OOB_OK and got == E.exact_minimum_staged(inp), shape
+
+
 def test_shapes_beyond_lds_take_the_general_path(P):
     """More layers or GPUs per node than the LDS tables hold: the recurrence over tables in the
     workspace, same results."""
