@@ -141,13 +141,10 @@ int oob_plan_destroy(oob_plan *h);
  *                        HBM, slightly more time on the headline workload); default 0
  *   OOB_OPT_ONE_STREAM   1: all levels on the caller's stream (no second stream, no events);
  *                        default 0: consecutive levels overlap on a second stream of the library
- *   OOB_OPT_NO_THIN_SPLITS 1: the outer splits s = 1 and s = S'-1 of whole-node targets go through the
- *                        general split kernel instead of the one written for them; default 0
  * Returns OOB_EINVAL for an unknown option. */
 #define OOB_OPT_PLAIN_SPLIT 1
 #define OOB_OPT_XCD_ORDER 2
 #define OOB_OPT_ONE_STREAM 3
-#define OOB_OPT_NO_THIN_SPLITS 4
 int oob_plan_set_option(oob_plan *h, int option, int value);
 
 /* Measurement hook.  After oob_plan_level_timing(h, 1) every oob_plan_templates call records

@@ -120,10 +120,7 @@ __host__ __device__ inline void tile_decode(int L, int S, int t, int *ub, int *v
 // Split points k of a block of the plane at level S': kmin = 8 ub + s .. kmax = vmax - (S' - s),
 // vmax = min(8 vb + 7, L): their number does not depend on s.  The keyed split kernel cuts
 // this range into segments of kSegK consecutive k, one workgroup each.
-#ifndef OOB_SEGK
-#define OOB_SEGK 8
-#endif
-constexpr int kSegK = OOB_SEGK;
+constexpr int kSegK = 8;
 __host__ __device__ inline int tile_krange(int L, int S, int ub, int vb) {
     return imin(vb * 8 + 7, L) - ub * 8 - S + 1;
 }

@@ -337,9 +337,6 @@ __global__ void __launch_bounds__(512) k_split(Tables t, int Sp, int fam, int NT
 // (non-negative doubles order like their bit patterns).  The key makes the merge order-free
 // and yields, per (s, state), the smallest total and the first k reaching it at once.
 // ---------------------------------------------------------------------------------------
-#ifndef OOB_LB_NTAB
-#define OOB_LB_NTAB 0
-#endif
 constexpr int kKeyTargets = 64;
 constexpr int kFillBatch = 3; // records a thread has in flight while staging
 
@@ -411,7 +408,7 @@ __host__ __device__ __forceinline__ int role_cost(int y0, int y1, int q0, int q1
 // records of k+1 in flight from HBM/L2 and drops them into the buffer between the two barriers
 // of the pass (NBUF = 2: two buffers and one barrier; needs more LDS, measured slower).
 template <int NTAB, int NA, int NBUF>
-__global__ void __launch_bounds__(256, NTAB <= OOB_LB_NTAB ? 4 : 1) k_split_key(Tables t, int Sp, int fam, int NT, int NAall, int halves,
+__global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, int NT, int NAall, int halves,
                                                    int s0, int sstep) {
     // Static, separate arrays: the compiler then knows that the key merges (atomics on s_acc) never
     // touch the staged records, and keeps the reads of the next step ahead of them.
@@ -598,81 +595,6 @@ __global__ void __launch_bounds__(256, NTAB <= OOB_LB_NTAB ? 4 : 1) k_split_key(
         const int aidx = fam_base + a_g0 + (e >> 6) - dlo_of(Sp, M);
         const long long slot = ((long long)(s - 1) * NAall + aidx) * NT + tile;
         atomicMin(&t.partKey[slot * 64 + (e & 63)], key);
-    }
-}
-
-// ---------------------------------------------------------------------------------------
-// Levels S' >= 4, the two OUTER splits s = 1 and s = S'-1 of whole-node targets (keyed variant only).
-// One of the children is a single stage on one whole node: one unit count on that side, so a
-// candidate pairs one record of the thin child with one of the other child and the (m, m')
-// rectangles of k_split_key degenerate to lines (seven eighths of its slots would be padding).
-// These splits are also the part of a level that has to wait for level S'-1, so their latency is on
-// the dependency chain of the whole call.  Here: no staging, no barriers.  A workgroup takes one
-// (block, segment) task of the level and one of the two splits; wave w takes split point kmin + w,
-// lane = state (u, v) of the block, eight targets a per workgroup: the thin record sits in registers, the
-// other child's record of unit count a-1 comes straight from L2 (eight distinct records per wave and
-// load), the candidate's key goes into the level's key array with an atomic min, like the flush of
-// k_split_key, after a merge over the workgroup's split points in LDS.  grid (tasks, 2, groups of
-// kThinBatch targets), block kSegK waves: short waves, all loads of a wave in flight at once.
-// ---------------------------------------------------------------------------------------
-constexpr int kThinBatch = kSegK; // targets per workgroup of k_split_thin (one thread per (target, state) at the end)
-__global__ void __launch_bounds__(kSegK * 64) k_split_thin(Tables t, int Sp, int NT, int NAall) {
-    if (t.flags[0] == 0) return;
-    const int L = t.sh.L, M = t.sh.M, n_max = t.sh.n_max;
-    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int left_thin = blockIdx.y == 0;            // s = 1: the left child is the single stage
-    const int s = left_thin ? 1 : Sp - 1, r = Sp - s;
-    const int2 sg = t.seg_tab[(long long)(Sp - 2) * t.seg_stride + blockIdx.x];
-    const int tile = sg.x, ub = sg.y & 255, vb = (sg.y >> 8) & 255, seg = sg.y >> 16;
-    __shared__ unsigned long long s_key[kThinBatch * 64]; // minima over the workgroup's split points
-    const unsigned long long kNoneBits = 0x7FF0000000000000ull;
-    s_key[threadIdx.x] = kNoneBits;                   // kThinBatch * 64 = kSegK * 64 entries, one per thread
-    __syncthreads();
-    const int k = ub * 8 + s + seg * kSegK + wave;
-    int t_lo, t_hi, c_lo, c_hi;
-    target_units(1, Sp, M, n_max, &t_lo, &t_hi);
-    child_units(1, Sp - 1, M, n_max, &c_lo, &c_hi);   // unit counts of the child with S'-1 stages
-    const int a0 = imax(t_lo + blockIdx.z * kThinBatch, c_lo + 1);
-    const int a1 = imin(imin(t_hi, t_lo + blockIdx.z * kThinBatch + kThinBatch - 1), c_hi + 1);
-    const int fam_base = M - 2;
-    if (k <= imin(vb * 8 + 7, L) - r && a0 <= a1) {   // whole wave: a split point of the block, targets to serve
-        const int u = ub * 8 + (lane >> 3), v = vb * 8 + (lane & 7);
-        // record offsets of this lane inside a table: left child (., u, k), right child (., k, v)
-        const long long offL = (long long)tri_index(ub, k >> 3, t.NB) * 64 + ((u & 7) << 3) + (k & 7);
-        const long long offR = (long long)tri_index(k >> 3, vb, t.NB) * 64 + ((k & 7) << 3) + (v & 7);
-        const long long tab1 = t.lvl_tab[1] - dlo_of(1, M) + fam_base + 1;       // (1 stage, one whole node)
-        const long long tabC = t.lvl_tab[Sp - 1] - dlo_of(Sp - 1, M) + fam_base; // + unit count
-        const Rec thin = t.rec[tab1 * t.tab_recs + (left_thin ? offL : offR)];
-        const Rec *thick = t.rec + (left_thin ? offR : offL);
-        double T[kThinBatch], T1[kThinBatch], tm[kThinBatch]; // all records of the wave in flight at once
-#pragma unroll
-        for (int q = 0; q < kThinBatch; ++q) {
-            const int a = imin(a0 + q, a1);
-            const Rec *p = thick + (tabC + a - 1) * t.tab_recs;
-            const double2 w = *(const double2 *)p;
-            T[q] = w.x; T1[q] = w.y; tm[q] = p->tmax;
-        }
-        const double cl = t.sh.Nb > 0 ? -(double)r : 3.0 * r, cr = t.sh.Nb > 0 ? 0.0 : 4.0 * s;
-        // left-child form (T + cl tmax, T1), right-child form (2 T1, T + cr tmax), as k_split_key stages them
-        const double tx = left_thin ? thin.T + cl * thin.tmax : 2.0 * thin.T1;
-        const double ty = left_thin ? thin.T1 : thin.T + cr * thin.tmax;
-        const double KS = (double)(1 << key_bits(L)), kd = (double)k;
-#pragma unroll
-        for (int q = 0; q < kThinBatch; ++q) {
-            if (a0 + q > a1) break;
-            double cand;
-            if (left_thin) cand = thin.tmax >= tm[q] ? tx + 2.0 * T1[q] : ty + (T[q] + cr * tm[q]);
-            else           cand = tm[q] >= thin.tmax ? (T[q] + cl * tm[q]) + tx : T1[q] + ty;
-            if (cand < kNone) atomicMin(&s_key[q * 64 + lane], (unsigned long long)__double_as_longlong(fma(cand, KS, kd)));
-        }
-    }
-    __syncthreads();
-    // thread (q, lane) merges target a0 + q of state `lane` into the level's keys (other segments do the same)
-    const int q = threadIdx.x >> 6;
-    const unsigned long long key = s_key[threadIdx.x];
-    if (a0 + q <= a1 && key != kNoneBits) {
-        const long long slot = ((long long)(s - 1) * NAall + (fam_base + a0 + q - dlo_of(Sp, M))) * NT + tile;
-        atomicMin(&t.partKey[slot * 64 + lane], key);
     }
 }
 
@@ -1156,7 +1078,7 @@ struct oob_plan {
     bool have_last;
     hipEvent_t ev_begin, ev_end; // optional: recorded around the level launches
     bool timed;
-    int opt_plain, opt_xcd, opt_one_stream, opt_no_thin; // oob_plan_set_option
+    int opt_plain, opt_xcd, opt_one_stream; // oob_plan_set_option
 };
 
 #define OOB_HIP_CHECK(expr)                                                                   \
@@ -1198,7 +1120,7 @@ extern "C" int oob_plan_create(oob_plan **h, int max_L, int max_nodes, int max_g
     p->lane_bytes = align_up(cv.total);
     p->lanes = (int)std::min<size_t>(kMaxLanes, std::max<size_t>(1, workspace_bytes / p->lane_bytes));
     p->ev_fork = nullptr; p->last_lane = 0;
-    p->opt_plain = p->opt_xcd = p->opt_one_stream = p->opt_no_thin = 0;
+    p->opt_plain = p->opt_xcd = p->opt_one_stream = 0;
     *h = p;
     return OOB_OK;
 }
@@ -1406,14 +1328,7 @@ static int enqueue_job(oob_plan *h, int ln, bool want_overlap, const oob_profile
         }
         for (int fam = 0; fam < 2; ++fam) {
             if (!have[fam]) continue;
-            SplitRange sr = inner ? SplitRange{1, S - 2, 2} : SplitRange{1, 1, S - 1};
-            if (fam == 1 && S >= 4 && !force_plain && !h->opt_no_thin) {
-                // whole-node targets: the two outer splits are lines, not rectangles
-                hipLaunchKernelGGL(k_split_thin, dim3(seg_count(L, S), 2, cdiv(imin(S, n_max) - imax(2, cdiv(S, M)) + 1, kThinBatch)), dim3(kSegK * 64), 0, st, tl,
-                                   S, NT, NAall);
-                if (inner) continue;
-                sr = SplitRange{2, 1, S - 3};
-            }
+            const SplitRange sr = inner ? SplitRange{1, S - 2, 2} : SplitRange{1, 1, S - 1};
             if (!force_plain) launch_split_key(tl, S, fam, kp[fam], NT, NAall, sr, st);
             else if (sp[fam].pc == 4) launch_split<4>(tl, S, fam, sp[fam], NT, NAall, st);
             else if (sp[fam].pc == 2) launch_split<2>(tl, S, fam, sp[fam], NT, NAall, st);
@@ -1486,7 +1401,6 @@ extern "C" int oob_plan_set_option(oob_plan *h, int option, int value) {
     case OOB_OPT_PLAIN_SPLIT: h->opt_plain = value != 0; break;
     case OOB_OPT_XCD_ORDER: h->opt_xcd = value != 0; break;
     case OOB_OPT_ONE_STREAM: h->opt_one_stream = value != 0; break;
-    case OOB_OPT_NO_THIN_SPLITS: h->opt_no_thin = value != 0; break;
     default: return OOB_EINVAL;
     }
     return OOB_OK;
