@@ -220,13 +220,16 @@ __device__ void one_side(const Args &a, const Lds &s, int e, double tau, double 
         int lastfin = q; // the layer farthest from q that some number of GPUs can be made to reach
         for (int r = 1; r <= rows; ++r) {
             const int p = MIRROR ? q - r : q + r;
-            const int far = MIRROR ? min(q, s.lomin[p]) : max(q, s.lomin[p]); // farthest layer any stage of this row reaches
+            // farthest layer any stage of this row reaches (the same in every lane: say so, the loops below
+            // then count in scalar registers)
+            const int far = __builtin_amdgcn_readfirstlane(MIRROR ? min(q, s.lomin[p]) : max(q, s.lomin[p]));
             if (MIRROR ? lastfin > far : lastfin < far) { // no stage of this row starts from a layer the table has reached
                 for (int g = lane; g <= M; g += 64) G[r * (M + 1) + g] = kNone;
                 wave_sync();
                 continue;
             }
             bool fin = false;
+            const int trips = MIRROR ? far - p : p - far; // stages [x, p), x = p-1 .. far / [p, x), x = p+1 .. far
             for (int gt = 0; gt * 8 < M; ++gt) {
                 const int g = gt * 8 + gi + 1;
                 double acc = kNone;
@@ -234,27 +237,30 @@ __device__ void one_side(const Args &a, const Lds &s, int e, double tau, double 
                     const int dd = dt * 8 + di + 1;
                     const bool on = g <= M && dd <= g;
                     const int reach = on ? s.lo[p * M + dd - 1] : p;
-                    // every lane walks the row's whole reach (uniform trip count, loads without
-                    // conditions so that they can be issued ahead); what lies beyond the lane's own reach
-                    // or GPU count reads a valid entry and is discarded
+                    // every lane walks the row's whole reach (uniform trip count, loads without conditions
+                    // so that they can be issued ahead); a trip beyond the lane's own reach or GPU count
+                    // reads a valid stage time and, from the table, the entry (row 0, one GPU), which is
+                    // "impossible" in every table
                     const int ddc = on ? dd : 1, gc = on ? g - dd : 0;
+                    const int mine = MIRROR ? min(q, reach) - p : p - max(q, reach); // trips of this lane
                     if (!MIRROR) {
-                        const int qlo = max(q, reach);
-                        const double *tp = a.td + (size_t)p * M + ddc - 1; // + x (L+1) M
+                        int to = ((p - 1) * (L + 1) + p) * M + ddc - 1, go = (p - 1 - q) * (M + 1) + gc;
+                        const int tstep = (L + 1) * M;
 #pragma unroll 4
-                        for (int x = p - 1; x >= far; --x) { // stage [x, p)
-                            const double tt = tp[(size_t)x * (L + 1) * M];
-                            const double cand = G[(x - q) * (M + 1) + gc] + (wt * tt + add);
-                            acc = fmin(acc, x >= qlo ? cand : kNone);
+                        for (int i = 0; i < trips; ++i) { // stage [x, p), x = p - 1 - i; table row x - q
+                            const double tt = a.td[to];
+                            const double cand = G[i < mine ? go : 1] + (wt * tt + add);
+                            acc = fmin(acc, cand);
+                            to -= tstep; go -= M + 1;
                         }
                     } else {
-                        const int qhi = min(q, reach);
-                        const double *tp = a.td + (size_t)p * (L + 1) * M + ddc - 1; // + x M
+                        int to = (p * (L + 1) + p + 1) * M + ddc - 1, go = (q - p - 1) * (M + 1) + gc;
 #pragma unroll 4
-                        for (int x = p + 1; x <= far; ++x) { // stage [p, x)
-                            const double tt = tp[(size_t)x * M];
-                            const double cand = G[(q - x) * (M + 1) + gc] + (wt * tt + add);
-                            acc = fmin(acc, (x <= qhi && tt <= tau) ? cand : kNone);
+                        for (int i = 0; i < trips; ++i) { // stage [p, x), x = p + 1 + i; table row q - x
+                            const double tt = a.td[to];
+                            const double cand = G[(i < mine && tt <= tau) ? go : 1] + (wt * tt + add);
+                            acc = fmin(acc, cand);
+                            to += M; go -= M + 1;
                         }
                     }
                 }
