@@ -40,8 +40,8 @@ INT64_OPS_PER_CANDIDATE = 30
 # counter reads for one 256 MiB device-to-device copy), and vector-ALU wave-instructions per call
 # (SQ_INSTS_VALU of k_split_key + k_select).
 PROFILE_CONFIG4 = {"source": "profiles/k_split_key_config4.md",
-                   "hbm_read_bytes_per_call": 21.01e9, "hbm_written_bytes_per_call": 5.72e9,
-                   "valu_wave_insts_per_call": 4.06e9 + 0.09e9}
+                   "hbm_read_bytes_per_call": 21.04e9, "hbm_written_bytes_per_call": 5.72e9,
+                   "valu_wave_insts_per_call": 3.90e9 + 0.09e9}
 
 
 def median(xs):
@@ -296,9 +296,14 @@ def bench_distribution(P, inp, res, Q=512, reps=3, oracle_sample=40):
                         f"{Q} microbatches; time per microbatch = T1 of the template",
             "value": total / dt, "unit": "plans/s", "ms": dt * 1e3, "choose_us": t_choose * 1e6,
             "best_plan_for_all_nodes": X[int(best[-1])].nonzero()[0].tolist() if best[-1] >= 0 else None,
-            "roofline": {"bound": "hbm", "achieved": nbytes / dt / 1e9, "peak": 8000.0, "unit": "GB/s",
-                         "frac": nbytes / dt / 8e12, "traffic": None, "kernel": "k_dist_solve",
-                         "bytes_per_plan": 6 * p + 28},
+            # bound by instruction issue: 25 119 vector instructions per wave of 64 plans (SQ_INSTS_VALU / SQ_WAVES
+            # of profiles/k_dist_solve_config4.md, a constant of that profile, not measured here), each 4 cycles
+            # on one of 1024 SIMDs; the algorithmic HBM bytes are kept as a secondary figure
+            "roofline": {"bound": "alu", "achieved": total / 64 * 25119 * 64 / dt / 1e12, "peak": PEAK_LANE_OPS / 1e12,
+                         "unit": "T lane-instr/s (32/64-bit integer)", "frac": total / 64 * 25119 * 64 / dt / PEAK_LANE_OPS,
+                         "traffic": None, "kernel": "k_dist_solve", "valu_insts_per_wave_from_profile": 25119,
+                         "hbm_algorithmic": {"bytes_per_plan": 6 * p + 28, "GB_per_s": nbytes / dt / 1e9,
+                                             "frac_of_hbm_peak": nbytes / dt / 8e12}},
             "cpu_baseline": {"value": cpu, "unit": "plans/s", "cores": 1, "kind": "oracle",
                              "sample": f"{oracle_sample} of the plans"}}
 

@@ -20,7 +20,21 @@
  *     the host can see).  Errors that depend on the profile's values are
  *     reported in oob_templates.status on the device;
  *   - one handle must not be used by two calls at the same time (the tables
- *     live in its workspace).
+ *     live in its workspace);
+ *   - exact range: inside the tables every time is an exact integer held in a
+ *     double.  A profile is accepted (status OOB_OK) iff
+ *         (N_b + 4 Smax + 4) * w < 2^52,
+ *     where Smax = oob_plan_max_stages(...), N_b = microbatches (4 Smax when
+ *     microbatches = 0) and w = sum over the GPU counts d = 1..M of (sum over the
+ *     layers of F_{l,d} + B_{l,d}, forbidden entries left out) + sum of all
+ *     boundary_ns: a bound on the sum of the stage times of any pipeline that is
+ *     loose by about the factor 1 + 1/2 + ... + 1/M.  Otherwise the status is
+ *     OOB_EOVERFLOW and nothing else is valid.  The headline workload (98 layers
+ *     of about 0.14 s, 8 GPUs per node, N_b = 128) uses 2^44 of the 2^52;
+ *   - supported pattern: a handle is created once and used for many calls.
+ *     Creating and destroying handles at a high rate is legal (their streams and
+ *     events are recycled through a pool of the library) but it is the
+ *     one-handle pattern that the tests cover at length.
  */
 #ifndef OOB_PLAN_H
 #define OOB_PLAN_H
