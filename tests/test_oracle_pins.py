@@ -303,3 +303,25 @@ def test_configs_1_to_3_invariants():
         r = capi.plan(inp)
         assert r["feasible"].all()
         check_invariants(inp, r)
+
+
+def test_stored_digests_of_the_batched_configuration_are_the_oracles():
+    """tests/golden/cfg5_all_templates.json (written by make_golden.py cfg5_all, which calls only the
+    oracle) is what the GPU path is compared with at full size: the three shortest instances are
+    recomputed here and must reproduce their stored digest and their stored T, S and feasibility."""
+    import hashlib
+    import json
+    import os
+
+    import parity_util as PU
+
+    path = os.path.join(os.path.dirname(__file__), "golden", "cfg5_all_templates.json")
+    stored = json.load(open(path))["instances"]
+    insts = inputs.config(5)
+    for idx in sorted((int(k) for k in stored), key=lambda k: insts[k].L)[:3]:
+        inp, want = insts[idx], stored[str(idx)]
+        cnt = inp.n_max - inp.n_min + 1
+        t = capi.plan(inp)
+        assert [int(x) for x in t["T"][:cnt]] == want["T"] and [int(x) for x in t["S"][:cnt]] == want["S"]
+        assert [int(x) for x in t["feasible"][:cnt]] == want["feasible"]
+        assert hashlib.sha256(PU.canonical_templates(t, cnt, inp.f)).hexdigest() == want["sha256"]
