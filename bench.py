@@ -41,7 +41,8 @@ INT64_OPS_PER_CANDIDATE = 30
 # (SQ_INSTS_VALU of k_split_key + k_select).
 PROFILE_CONFIG4 = {"source": "profiles/k_split_key_config4.md",
                    "hbm_read_bytes_per_call": 21.04e9, "hbm_written_bytes_per_call": 5.72e9,
-                   "valu_wave_insts_per_call": 3.90e9 + 0.09e9}
+                   "valu_wave_insts_per_call": 3.90e9 + 0.09e9,
+                   "kernel_launches_per_call": 308}  # 204 k_split_key + 97 k_select + 7 others (kernel trace)
 
 
 def median(xs):
@@ -549,7 +550,8 @@ def main():
                      "from_profile": ({"source": prof4["source"], "constants_not_measured_in_this_run": True,
                                        "valu_issue_utilisation": prof4["valu_wave_insts_per_call"] * 4
                                                                  / (1024 * 2.4e9 * lvl_ms * 1e-3),
-                                       "valu_lane_insts_per_candidate": prof4["valu_wave_insts_per_call"] * 64 / cands}
+                                       "valu_lane_insts_per_candidate": prof4["valu_wave_insts_per_call"] * 64 / cands,
+                                       "kernel_launches_per_call": prof4["kernel_launches_per_call"]}
                                       if prof4 else None)},
     }
     line["instantiation"] = bench_instantiation(P, inp, res)
