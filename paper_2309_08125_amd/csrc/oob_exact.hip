@@ -45,7 +45,8 @@ struct Args {
     long long cap;
     long long limit;      // every cost must stay below this (2^52 for the LDS path, 2^61 otherwise)
     long long *t;         // [(u (L+1) + v) M + d-1] stage times, -1: impossible
-    double *td;           // the same as doubles
+    double *tds, *tdp;    // the same as doubles, laid out for the two walks of the fast path: tds[(u M + d-1)(L+1) + v]
+                          // (a stage out of u: v runs along a row), tdp[(v M + d-1)(L+1) + u] (a stage into v: u runs along a row)
     long long *slots;     // k_exact_flat: [slots][2][(L+1)][(Dmax+1)][J]
     unsigned long long *best; // per template: smallest cost so far
     unsigned *counter;    // work counter of k_exact_lds
@@ -53,19 +54,23 @@ struct Args {
 };
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
-inline size_t table_entries(int L, int M) { return (size_t)(L + 1) * (L + 1) * M; }
-inline size_t head_bytes(int L, int M) { return 256 + 2 * align_up(8 * table_entries(L, M)); }
+__host__ __device__ inline size_t table_entries(int L, int M) { return (size_t)(L + 1) * (L + 1) * M; }
+// the tables of doubles carry one more row, every entry "impossible", and a few entries of padding: the
+// walks of the fast path read up to three entries past their end, and idle lanes walk the extra row
+__host__ __device__ inline size_t dtable_entries(int L, int M) { return table_entries(L, M) + (size_t)(L + 1) + 8; }
+inline size_t head_bytes(int L, int M) { return 256 + align_up(8 * table_entries(L, M)) + 2 * align_up(8 * dtable_entries(L, M)); }
+constexpr int kGPad = 3; // rows of "impossible" in front of a one-node table
 
 // LDS of k_exact_lds for `nw` waves, in bytes (all arrays 8-byte entries; see the kernel).
 __host__ __device__ inline size_t tri(int L) { return (size_t)L * (L + 1) / 2; }
 inline size_t lds_bytes(int L, int M, int n_max, int count, int nw) {
     const size_t n = tri(L) + (size_t)(L + 1) * M + 2 * (size_t)(L + 1) + 2 * (size_t)n_max * M +
                      ((size_t)(L + 1) * M + 1) / 2 + (size_t)(L + 1) / 2 + 1 + L + count +
-                     (size_t)nw * (L + 1) * (M + 1);
+                     (size_t)nw * (L + 1 + kGPad) * (M + 1);
     return 8 * n + 64;
 }
 inline int lds_waves(int L, int M, int n_max, int count) { // 0: does not fit
-    for (int nw = 8; nw >= 2; nw >>= 1)
+    for (int nw : {16, 12, 8, 4, 2}) // the one-node phase is bound by the latency of a table row: as many waves as fit
         if (lds_bytes(L, M, n_max, count, nw) <= kLdsLimit) return nw;
     return 0;
 }
@@ -105,6 +110,15 @@ __global__ void __launch_bounds__(kThreads) k_exact_init(Args a) {
     }
 }
 
+// Every entry of the two tables of doubles, the extra row and the padding included: "impossible".
+__global__ void k_exact_fill(Args a) {
+    const size_t n = dtable_entries(a.L, a.M);
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        a.tds[i] = kNone;
+        a.tdp[i] = kNone;
+    }
+}
+
 // Stage times of all (u, v, d): one thread per (u, d) walks v.  A negative profile entry sets the
 // status to OOB_EINVAL (every writer stores the same value, so the order does not matter).
 __global__ void k_exact_stages(Args a) {
@@ -125,7 +139,10 @@ __global__ void k_exact_stages(Args a) {
         if (ok && (bytes + d - 1) / d <= a.cap) val = time + (v < a.L ? bnd[v - 1] : 0);
         const size_t o = ((size_t)u * (a.L + 1) + v) * a.M + d - 1;
         a.t[o] = val;
-        a.td[o] = (double)val;
+        if (val >= 0) { // an impossible stage keeps the fill value of the tables of doubles
+            a.tds[((size_t)u * a.M + d - 1) * (a.L + 1) + v] = (double)val;
+            a.tdp[((size_t)v * a.M + d - 1) * (a.L + 1) + u] = (double)val;
+        }
     }
     if (bad) atomicExch(a.status, OOB_EINVAL);
 }
@@ -140,7 +157,23 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
-__device__ __forceinline__ double shfl_xor_f64(double x, int m) { return __shfl_xor(x, m, 64); }
+// Minimum over aligned groups of 4 / 8 consecutive lanes, in every lane of the group, with data-parallel
+// moves (quad permutations 1,0,3,2 and 2,3,0,1; then the mirror image within each half row, which
+// hands every lane a lane of the other quad of its group of eight).
+template <int CTRL> __device__ __forceinline__ double dpp_f64(double x) {
+    int lo = __double2loint(x), hi = __double2hiint(x);
+    lo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xF, 0xF, false);
+    hi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double min4(double x) {
+    x = fmin(x, dpp_f64<0xB1>(x));
+    return fmin(x, dpp_f64<0x4E>(x));
+}
+__device__ __forceinline__ double min8(double x) {
+    x = min4(x);
+    return fmin(x, dpp_f64<0x141>(x));
+}
 
 struct Lds {
     double *W;    // [tri(L)]  one whole node covering [q, p), q < p: index q L - q (q-1)/2 + p - q - 1
@@ -180,8 +213,8 @@ __device__ void one_side(const Args &a, const Lds &s, int e, double tau, double 
                 int lo = 0, hi = p; // answer in [lo, hi]; hi = p: none
                 while (lo < hi) {
                     const int mid = (lo + hi) >> 1;
-                    const double tt = a.td[((size_t)mid * (L + 1) + p) * M + dd - 1];
-                    if (tt >= 0.0 && tt < tau) hi = mid; else lo = mid + 1;
+                    const double tt = a.tdp[((size_t)p * M + dd - 1) * (L + 1) + mid];
+                    if (tt < tau) hi = mid; else lo = mid + 1;
                 }
                 r = lo;
             }
@@ -192,8 +225,8 @@ __device__ void one_side(const Args &a, const Lds &s, int e, double tau, double 
                 int lo = p, hi = L; // answer in [lo, hi]; lo = p: none
                 while (lo < hi) {
                     const int mid = (lo + hi + 1) >> 1;
-                    const double tt = a.td[((size_t)p * (L + 1) + mid) * M + dd - 1];
-                    if (tt >= 0.0 && tt - (mid < L ? s.bnd[mid - 1] : 0.0) <= tau) lo = mid; else hi = mid - 1;
+                    const double tt = a.tds[((size_t)p * M + dd - 1) * (L + 1) + mid];
+                    if (tt - (mid < L ? s.bnd[mid - 1] : 0.0) <= tau) lo = mid; else hi = mid - 1;
                 }
                 r = lo;
             }
@@ -209,7 +242,9 @@ __device__ void one_side(const Args &a, const Lds &s, int e, double tau, double 
     for (int i = threadIdx.x; i < (L + 1) * M; i += blockDim.x) s.GU[i] = kNone;
     __syncthreads();
     // ---- phase 1: one-node tables, one start layer per wave at a time ----------------------
-    double *G = s.G + (size_t)wave * (L + 1) * (M + 1);
+    // rows -kGPad .. -1 stay "impossible": the walks below run in groups of four and may pass the table's first row
+    double *G = s.G + (size_t)wave * (L + 1 + kGPad) * (M + 1) + kGPad * (M + 1);
+    for (int g = lane; g < kGPad * (M + 1); g += 64) G[g - kGPad * (M + 1)] = kNone;
     const int nstart = MIRROR ? L - e : e;
     for (int qi = wave; qi < nstart; qi += nw) {
         const int q = MIRROR ? L - qi : qi;            // prefix: q = 0 .. e-1; suffix: q = L .. e+1
@@ -241,32 +276,40 @@ __device__ void one_side(const Args &a, const Lds &s, int e, double tau, double 
                     // so that they can be issued ahead); a trip beyond the lane's own reach or GPU count
                     // reads a valid stage time and, from the table, the entry (row 0, one GPU), which is
                     // "impossible" in every table
-                    const int ddc = on ? dd : 1, gc = on ? g - dd : 0;
                     const int mine = MIRROR ? min(q, reach) - p : p - max(q, reach); // trips of this lane
+                    // groups of four trips, the four table entries and the four stage times read before any
+                    // of them is used (one wait per group instead of one per trip)
                     if (!MIRROR) {
-                        int to = ((p - 1) * (L + 1) + p) * M + ddc - 1, go = (p - 1 - q) * (M + 1) + gc;
-                        const int tstep = (L + 1) * M;
-#pragma unroll 4
-                        for (int i = 0; i < trips; ++i) { // stage [x, p), x = p - 1 - i; table row x - q
-                            const double tt = a.td[to];
-                            const double cand = G[i < mine ? go : 1] + (wt * tt + add);
-                            acc = fmin(acc, cand);
-                            to -= tstep; go -= M + 1;
+                        const int ddc = on ? dd : 1, gc = on ? g - dd : 0;
+                        int to = (p * M + ddc - 1) * (L + 1) + p - 1, go = (p - 1 - q) * (M + 1) + gc;
+                        for (int i = 0; i < trips; i += 4) { // stage [x, p), x = p - 1 - i; table row x - q
+                            double tt[4], gv[4];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) tt[j] = a.tdp[to - j];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) gv[j] = G[i + j < mine ? go - j * (M + 1) : 1];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) acc = fmin(acc, gv[j] + (wt * tt[j] + add));
+                            to -= 4; go -= 4 * (M + 1);
                         }
                     } else {
-                        int to = (p * (L + 1) + p + 1) * M + ddc - 1, go = (q - p - 1) * (M + 1) + gc;
-#pragma unroll 4
-                        for (int i = 0; i < trips; ++i) { // stage [p, x), x = p + 1 + i; table row q - x
-                            const double tt = a.td[to];
-                            const double cand = G[(i < mine && tt <= tau) ? go : 1] + (wt * tt + add);
-                            acc = fmin(acc, cand);
-                            to += M; go -= M + 1;
+                        // a lane without a pair walks the row of impossible stages; the others take every stage
+                        // with t <= tau (t is not monotone along the walk, so the test is on the value)
+                        const int row = on ? p * M + dd - 1 : (L + 1) * M, gc = on ? g - dd : 0;
+                        int to = row * (L + 1) + p + 1, go = (q - p - 1) * (M + 1) + gc;
+                        for (int i = 0; i < trips; i += 4) { // stage [p, x), x = p + 1 + i; table row q - x
+                            double tt[4], gv[4];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) tt[j] = a.tds[to + j];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) gv[j] = G[go - j * (M + 1)];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) acc = fmin(acc, gv[j] + (wt * (tt[j] <= tau ? tt[j] : kNone) + add));
+                            to += 4; go -= 4 * (M + 1);
                         }
                     }
                 }
-                acc = fmin(acc, shfl_xor_f64(acc, 1));
-                acc = fmin(acc, shfl_xor_f64(acc, 2));
-                acc = fmin(acc, shfl_xor_f64(acc, 4));
+                acc = min8(acc);
                 if (di == 0 && g <= M) G[r * (M + 1) + g] = acc;
                 fin = fin || acc < kNone;
             }
@@ -301,8 +344,7 @@ __device__ void one_side(const Args &a, const Lds &s, int e, double tau, double 
             if (g == 0) { if (h4 == 0) m = cur[e]; }
             else if (!MIRROR) for (int q = h4; q < e; q += 4) m = fmin(m, cur[q] + s.GU[q * M + g]);
             else              for (int q = e + 1 + h4; q <= L; q += 4) m = fmin(m, cur[q] + s.GU[q * M + g]);
-            m = fmin(m, shfl_xor_f64(m, 1));
-            m = fmin(m, shfl_xor_f64(m, 2));
+            m = min4(m);
             if (h4 == 0) OUT[c * M + g] = m;
         }
         if (c + 1 < cend) {
@@ -315,8 +357,7 @@ __device__ void one_side(const Args &a, const Lds &s, int e, double tau, double 
                     if (!MIRROR) for (int q = h4; q < p; q += 4) m = fmin(m, cur[q] + s.W[widx(q, p, L)]);
                     else         for (int q = p + 1 + h4; q <= L; q += 4) m = fmin(m, cur[q] + s.W[widx(p, q, L)]);
                 }
-                m = fmin(m, shfl_xor_f64(m, 1));
-                m = fmin(m, shfl_xor_f64(m, 2));
+                m = min4(m);
                 if (h4 == 0 && pi < np) nxt[MIRROR ? L - pi : pi] = m;
             }
         }
@@ -325,7 +366,7 @@ __device__ void one_side(const Args &a, const Lds &s, int e, double tau, double 
     }
 }
 
-__global__ void __launch_bounds__(512) k_exact_lds(Args a) {
+__global__ void __launch_bounds__(1024) k_exact_lds(Args a) {
     HIP_DYNAMIC_SHARED(double, s_dyn)
     __shared__ unsigned s_next;
     if (*a.status != OOB_OK) return; // the same for every thread: nothing is computed from a bad profile
@@ -360,8 +401,8 @@ __global__ void __launch_bounds__(512) k_exact_lds(Args a) {
         int u = 0;
         while (pr >= (unsigned)(L - u)) { pr -= L - u; ++u; }
         const int v = u + 1 + (int)pr;
-        const double tau = a.td[((size_t)u * (L + 1) + v) * M + d - 1];
-        if (tau < 0.0) continue; // the same for the whole workgroup
+        const double tau = a.tds[((size_t)u * M + d - 1) * (L + 1) + v];
+        if (!(tau < kNone)) continue; // the same for the whole workgroup
         one_side<false>(a, s, u, tau, 1.0, ptau, s.PU);
         one_side<true>(a, s, v, tau, 2.0, stau, s.SV);
         // the slowest stage at every place it fits, for every template whose stage limit cannot bind
@@ -565,7 +606,8 @@ static int exact_launch(const oob_profile *profile, int L, int n_min, int n_max,
     char *ws = (char *)dev_workspace;
     a.counter = (unsigned *)ws;
     a.t = (long long *)(ws + 256);
-    a.td = (double *)(ws + 256 + align_up(8 * table_entries(L, M)));
+    a.tds = (double *)(ws + 256 + align_up(8 * table_entries(L, M)));
+    a.tdp = (double *)(ws + 256 + align_up(8 * table_entries(L, M)) + align_up(8 * dtable_entries(L, M)));
     a.slots = (long long *)(ws + head_bytes(L, M));
     a.best = (unsigned long long *)best; a.status = status;
     hipStream_t st = (hipStream_t)stream;
@@ -579,6 +621,7 @@ static int exact_launch(const oob_profile *profile, int L, int n_min, int n_max,
     } else if (workspace_bytes < head_bytes(L, M)) return OOB_ECAPACITY;
     a.limit = nw ? kDoubleExact : kInf;
     hipLaunchKernelGGL(k_exact_init, dim3(1), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL(k_exact_fill, dim3(64), dim3(256), 0, st, a);
     hipLaunchKernelGGL(k_exact_stages, dim3((L * M + 63) / 64), dim3(64), 0, st, a);
     const long long ncand = (long long)L * (L + 1) / 2 * M;
     if (nw) {
