@@ -64,7 +64,7 @@ constexpr int kGPad = 3; // rows of "impossible" in front of a one-node table
 // LDS of k_exact_lds for `nw` waves, in bytes (all arrays 8-byte entries; see the kernel).
 __host__ __device__ inline size_t tri(int L) { return (size_t)L * (L + 1) / 2; }
 inline size_t lds_bytes(int L, int M, int n_max, int count, int nw) {
-    const size_t n = tri(L) + (size_t)(L + 1) * M + 2 * (size_t)(L + 1) + 2 * (size_t)n_max * M +
+    const size_t n = tri(L) + (size_t)(L + 1) * M + 4 * (size_t)(L + 1) + 2 * (size_t)n_max * M +
                      ((size_t)(L + 1) * M + 1) / 2 + (size_t)(L + 1) / 2 + 1 + L + count +
                      (size_t)nw * (L + 1 + kGPad) * (M + 1);
     return 8 * n + 64;
@@ -178,7 +178,7 @@ __device__ __forceinline__ double min8(double x) {
 struct Lds {
     double *W;    // [tri(L)]  one whole node covering [q, p), q < p: index q L - q (q-1)/2 + p - q - 1
     double *GU;   // [(L+1)][M]  g GPUs (entry g, 1 <= g < M) of a node covering [q, u) / (mirrored) [v, x)
-    double *NP;   // [2][L+1]  node-level tables of the previous and the current node count
+    double *NP;   // [2][2][L+1]  per side: node-level tables of the previous and the current node count
     double *PU;   // [n_max][M]  PreU[a][g]
     double *SV;   // [n_max][M]  SufV[b][h]
     int *lo;      // [(L+1)][M]  first (prefix) / last (suffix) layer a stage into / out of p can reach
@@ -189,180 +189,149 @@ struct Lds {
 };
 __device__ __forceinline__ size_t widx(int q, int p, int L) { return (size_t)q * L - (size_t)q * (q - 1) / 2 + (p - q - 1); }
 
-// One side of the slowest stage.  MIRROR = false: the layers [0, e) before it (e = u); a one-node
-// table starts at layer q and grows to the right, a stage [q', p) into p costs t + ptau * tau and needs
-// t < tau.  MIRROR = true: the layers [e, L) after it (e = v); a one-node table ends at layer q and
-// grows to the left, a stage [p, w) out of p costs 2 t + stau * tau and needs t <= tau.  Result:
-// OUT[c][g] = least cost of covering the side with c whole nodes and g more GPUs next to the
-// slowest stage, g = 0 .. M-1.
+// The two sides of the slowest stage [u, v).  MIRROR = false: the layers [0, e) before it (e = u); a
+// one-node table starts at layer q and grows to the right, a stage [q', p) into p costs t + ptau * tau
+// and needs t < tau.  MIRROR = true: the layers [e, L) after it (e = v); a one-node table ends at
+// layer q and grows to the left, a stage [p, w) out of p costs 2 t + stau * tau and needs t <= tau.
+// Result per side: OUT[c][g] = least cost of covering the side with c whole nodes and g more GPUs
+// next to the slowest stage, g = 0 .. M-1.  The two sides use disjoint parts of every table that is
+// indexed by layers (W, GU, lo, lomin), so they run side by side.
+
+// Reach of a stage into / out of layer p on dd GPUs (entry i = p M + dd - 1), by bisection.
 template <bool MIRROR>
-__device__ void one_side(const Args &a, const Lds &s, int e, double tau, double wt, double wtau, double *OUT) {
-    const int L = a.L, M = a.M, nw = blockDim.x >> 6;
-    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int gi = lane >> 3, di = lane & 7;
-    const double add = wtau * tau;
-    // layers of the side: prefix p in (0, e], suffix p in [e, L); starts q: prefix [0, e), suffix (e, L]
-    // ---- reach of a stage into / out of every layer p, per GPU count -------------------------
-    for (int i = threadIdx.x; i < (L + 1) * M; i += blockDim.x) {
-        const int p = i / M, dd = i % M + 1;
-        int r = p;
-        if (!MIRROR) {
-            if (p >= 1 && p <= e) {
-                // [x, p) only gets slower and heavier as x goes down (impossible at the far end): the stages
-                // with 0 <= t < tau are x = r .. p-1; bisection for r
-                int lo = 0, hi = p; // answer in [lo, hi]; hi = p: none
-                while (lo < hi) {
-                    const int mid = (lo + hi) >> 1;
-                    const double tt = a.tdp[((size_t)p * M + dd - 1) * (L + 1) + mid];
-                    if (tt < tau) hi = mid; else lo = mid + 1;
-                }
-                r = lo;
-            }
-        } else {
-            if (p >= e && p < L) {
-                // [p, w) as w goes up: impossible stays impossible and the time without the boundary term only
-                // grows: those stages are w = p+1 .. r; bisection for r
-                int lo = p, hi = L; // answer in [lo, hi]; lo = p: none
-                while (lo < hi) {
-                    const int mid = (lo + hi + 1) >> 1;
-                    const double tt = a.tds[((size_t)p * M + dd - 1) * (L + 1) + mid];
-                    if (tt - (mid < L ? s.bnd[mid - 1] : 0.0) <= tau) lo = mid; else hi = mid - 1;
-                }
-                r = lo;
-            }
+__device__ __forceinline__ int side_reach(const Args &a, const Lds &s, int p, int dd, double tau) {
+    const int L = a.L, M = a.M;
+    if (!MIRROR) {
+        // [x, p) only gets slower and heavier as x goes down (impossible at the far end): the stages
+        // with t < tau are x = r .. p-1
+        int lo = 0, hi = p; // answer in [lo, hi]; hi = p: none
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            const double tt = a.tdp[((size_t)p * M + dd - 1) * (L + 1) + mid];
+            if (tt < tau) hi = mid; else lo = mid + 1;
         }
-        s.lo[i] = r;
+        return lo;
     }
-    __syncthreads();
-    for (int p = threadIdx.x; p <= L; p += blockDim.x) {
-        int m = s.lo[p * M];
-        for (int dd = 2; dd <= M; ++dd) m = MIRROR ? max(m, s.lo[p * M + dd - 1]) : min(m, s.lo[p * M + dd - 1]);
-        s.lomin[p] = m;
+    // [p, w) as w goes up: impossible stays impossible and the time without the boundary term only
+    // grows: those stages are w = p+1 .. r
+    int lo = p, hi = L; // answer in [lo, hi]; lo = p: none
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        const double tt = a.tds[((size_t)p * M + dd - 1) * (L + 1) + mid];
+        if (tt - (mid < L ? s.bnd[mid - 1] : 0.0) <= tau) lo = mid; else hi = mid - 1;
     }
-    for (int i = threadIdx.x; i < (L + 1) * M; i += blockDim.x) s.GU[i] = kNone;
-    __syncthreads();
-    // ---- phase 1: one-node tables, one start layer per wave at a time ----------------------
-    // rows -kGPad .. -1 stay "impossible": the walks below run in groups of four and may pass the table's first row
-    double *G = s.G + (size_t)wave * (L + 1 + kGPad) * (M + 1) + kGPad * (M + 1);
-    for (int g = lane; g < kGPad * (M + 1); g += 64) G[g - kGPad * (M + 1)] = kNone;
-    const int nstart = MIRROR ? L - e : e;
-    for (int qi = wave; qi < nstart; qi += nw) {
-        const int q = MIRROR ? L - qi : qi;            // prefix: q = 0 .. e-1; suffix: q = L .. e+1
-        // row r of G = layer q + r (prefix) / q - r (suffix); row 0: nothing covered
-        for (int g = lane; g <= M; g += 64) G[g] = g == 0 ? 0.0 : kNone;
-        wave_sync();
-        const int rows = MIRROR ? q - e : e - q;
-        int lastfin = q; // the layer farthest from q that some number of GPUs can be made to reach
-        for (int r = 1; r <= rows; ++r) {
-            const int p = MIRROR ? q - r : q + r;
-            // farthest layer any stage of this row reaches (the same in every lane: say so, the loops below
-            // then count in scalar registers)
-            const int far = __builtin_amdgcn_readfirstlane(MIRROR ? min(q, s.lomin[p]) : max(q, s.lomin[p]));
-            if (MIRROR ? lastfin > far : lastfin < far) { // no stage of this row starts from a layer the table has reached
-                for (int g = lane; g <= M; g += 64) G[r * (M + 1) + g] = kNone;
-                wave_sync();
-                continue;
-            }
-            bool fin = false;
-            const int trips = MIRROR ? far - p : p - far; // stages [x, p), x = p-1 .. far / [p, x), x = p+1 .. far
-            for (int gt = 0; gt * 8 < M; ++gt) {
-                const int g = gt * 8 + gi + 1;
-                double acc = kNone;
-                for (int dt = 0; dt <= gt; ++dt) {
-                    const int dd = dt * 8 + di + 1;
-                    const bool on = g <= M && dd <= g;
+    return lo;
+}
+
+// One-node table of start layer q (one wave): rows, then its contribution to W and GU.
+template <bool MIRROR>
+__device__ void one_node_table(const Args &a, const Lds &s, int e, int q, double tau, double wt, double add, double *G) {
+    const int L = a.L, M = a.M, lane = threadIdx.x & 63, gi = lane >> 3, di = lane & 7;
+    // row r of G = layer q + r (prefix) / q - r (suffix); row 0: nothing covered
+    for (int g = lane; g <= M; g += 64) G[g] = g == 0 ? 0.0 : kNone;
+    wave_sync();
+    const int rows = MIRROR ? q - e : e - q;
+    int lastfin = q; // the layer farthest from q that some number of GPUs can be made to reach
+    for (int r = 1; r <= rows; ++r) {
+        const int p = MIRROR ? q - r : q + r;
+        // farthest layer any stage of this row reaches (the same in every lane: say so, the loops below
+        // then count in scalar registers)
+        const int far = __builtin_amdgcn_readfirstlane(MIRROR ? min(q, s.lomin[p]) : max(q, s.lomin[p]));
+        if (MIRROR ? lastfin > far : lastfin < far) { // no stage of this row starts from a layer the table has reached
+            for (int g = lane; g <= M; g += 64) G[r * (M + 1) + g] = kNone;
+            wave_sync();
+            continue;
+        }
+        bool fin = false;
+        const int trips = MIRROR ? far - p : p - far; // stages [x, p), x = p-1 .. far / [p, x), x = p+1 .. far
+        for (int gt = 0; gt * 8 < M; ++gt) {
+            const int g = gt * 8 + gi + 1;
+            double acc = kNone;
+            for (int dt = 0; dt <= gt; ++dt) {
+                const int dd = dt * 8 + di + 1;
+                const bool on = g <= M && dd <= g;
+                // Every lane walks the row's whole reach (uniform trip count, loads without conditions),
+                // in groups of four trips: the four table entries and the four stage times are read
+                // before any of them is used (one wait per group instead of one per trip).
+                if (!MIRROR) {
+                    // a trip beyond the lane's own reach or GPU count reads a valid stage time and, from
+                    // the table, the entry (row 0, one GPU), which is "impossible" in every table
                     const int reach = on ? s.lo[p * M + dd - 1] : p;
-                    // every lane walks the row's whole reach (uniform trip count, loads without conditions
-                    // so that they can be issued ahead); a trip beyond the lane's own reach or GPU count
-                    // reads a valid stage time and, from the table, the entry (row 0, one GPU), which is
-                    // "impossible" in every table
-                    const int mine = MIRROR ? min(q, reach) - p : p - max(q, reach); // trips of this lane
-                    // groups of four trips, the four table entries and the four stage times read before any
-                    // of them is used (one wait per group instead of one per trip)
-                    if (!MIRROR) {
-                        const int ddc = on ? dd : 1, gc = on ? g - dd : 0;
-                        int to = (p * M + ddc - 1) * (L + 1) + p - 1, go = (p - 1 - q) * (M + 1) + gc;
-                        for (int i = 0; i < trips; i += 4) { // stage [x, p), x = p - 1 - i; table row x - q
-                            double tt[4], gv[4];
+                    const int mine = p - max(q, reach); // trips of this lane
+                    const int ddc = on ? dd : 1, gc = on ? g - dd : 0;
+                    int to = (p * M + ddc - 1) * (L + 1) + p - 1, go = (p - 1 - q) * (M + 1) + gc;
+                    for (int i = 0; i < trips; i += 4) { // stage [x, p), x = p - 1 - i; table row x - q
+                        double tt[4], gv[4];
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) tt[j] = a.tdp[to - j];
+                        for (int j = 0; j < 4; ++j) tt[j] = a.tdp[to - j];
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) gv[j] = G[i + j < mine ? go - j * (M + 1) : 1];
+                        for (int j = 0; j < 4; ++j) gv[j] = G[i + j < mine ? go - j * (M + 1) : 1];
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) acc = fmin(acc, gv[j] + (wt * tt[j] + add));
-                            to -= 4; go -= 4 * (M + 1);
-                        }
-                    } else {
-                        // a lane without a pair walks the row of impossible stages; the others take every stage
-                        // with t <= tau (t is not monotone along the walk, so the test is on the value)
-                        const int row = on ? p * M + dd - 1 : (L + 1) * M, gc = on ? g - dd : 0;
-                        int to = row * (L + 1) + p + 1, go = (q - p - 1) * (M + 1) + gc;
-                        for (int i = 0; i < trips; i += 4) { // stage [p, x), x = p + 1 + i; table row q - x
-                            double tt[4], gv[4];
+                        for (int j = 0; j < 4; ++j) acc = fmin(acc, gv[j] + (wt * tt[j] + add));
+                        to -= 4; go -= 4 * (M + 1);
+                    }
+                } else {
+                    // a lane without a pair walks the row of impossible stages; the others take every stage
+                    // with t <= tau (t is not monotone along the walk, so the test is on the value)
+                    const int row = on ? p * M + dd - 1 : (L + 1) * M, gc = on ? g - dd : 0;
+                    int to = row * (L + 1) + p + 1, go = (q - p - 1) * (M + 1) + gc;
+                    for (int i = 0; i < trips; i += 4) { // stage [p, x), x = p + 1 + i; table row q - x
+                        double tt[4], gv[4];
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) tt[j] = a.tds[to + j];
+                        for (int j = 0; j < 4; ++j) tt[j] = a.tds[to + j];
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) gv[j] = G[go - j * (M + 1)];
+                        for (int j = 0; j < 4; ++j) gv[j] = G[go - j * (M + 1)];
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) acc = fmin(acc, gv[j] + (wt * (tt[j] <= tau ? tt[j] : kNone) + add));
-                            to += 4; go -= 4 * (M + 1);
-                        }
+                        for (int j = 0; j < 4; ++j) acc = fmin(acc, gv[j] + (wt * (tt[j] <= tau ? tt[j] : kNone) + add));
+                        to += 4; go -= 4 * (M + 1);
                     }
                 }
-                acc = min8(acc);
-                if (di == 0 && g <= M) G[r * (M + 1) + g] = acc;
-                fin = fin || acc < kNone;
             }
-            if (lane == 0) G[r * (M + 1)] = kNone;
-            if (__any(fin)) lastfin = p; // the same in every lane
-            wave_sync();
+            acc = min8(acc);
+            if (di == 0 && g <= M) G[r * (M + 1) + g] = acc;
+            fin = fin || acc < kNone;
         }
-        // a whole node covering [q, p) (prefix) / [p, q) (suffix), and the partial covers next to the slowest stage
-        for (int r = 1 + lane; r <= rows; r += 64) {
-            const int p = MIRROR ? q - r : q + r;
-            s.W[MIRROR ? widx(p, q, L) : widx(q, p, L)] = G[r * (M + 1) + M];
-        }
-        for (int g = 1 + lane; g < M; g += 64) s.GU[q * M + g] = G[rows * (M + 1) + g];
+        if (lane == 0) G[r * (M + 1)] = kNone;
+        if (__any(fin)) lastfin = p; // the same in every lane
         wave_sync();
     }
-    __syncthreads();
-    // ---- phase 2: node after node ------------------------------------------------------------
-    // NP_c[p]: c whole nodes cover [0, p) (prefix) / [p, L) (suffix); p runs over the side's layers
-    double *cur = s.NP, *nxt = s.NP + (L + 1);
-    const int origin = MIRROR ? L : 0;
-    for (int p = threadIdx.x; p <= L; p += blockDim.x) cur[p] = p == origin ? 0.0 : kNone;
-    __syncthreads();
-    const int h4 = threadIdx.x & 3;
-    // a node covers at least one layer: more whole nodes than the side has layers cover nothing
-    const int cend = min(a.n_max, (MIRROR ? L - e : e) + 1);
-    for (int i = threadIdx.x + cend * M; i < a.n_max * M; i += blockDim.x) OUT[i] = kNone;
-    for (int c = 0; c < cend; ++c) {
-        // OUT[c][g] from NP_c, and NP_{c+1} from NP_c, in one phase
-        for (int i = threadIdx.x; i < M * 4; i += blockDim.x) { // four threads per g
-            const int g = i >> 2;
+    // a whole node covering [q, p) (prefix) / [p, q) (suffix), and the partial covers next to the slowest stage
+    for (int r = 1 + lane; r <= rows; r += 64) {
+        const int p = MIRROR ? q - r : q + r;
+        s.W[MIRROR ? widx(p, q, L) : widx(q, p, L)] = G[r * (M + 1) + M];
+    }
+    for (int g = 1 + lane; g < M; g += 64) s.GU[q * M + g] = G[rows * (M + 1) + g];
+    wave_sync();
+}
+
+// Node after node, one step: OUT[c][g] from NP_c, and NP_{c+1} from NP_c (cur -> nxt).  NP_c[p]: c whole
+// nodes cover [0, p) (prefix) / [p, L) (suffix).  Called by `nth` threads (whole waves), th = 0 .. nth-1.
+template <bool MIRROR>
+__device__ void node_step(const Args &a, const Lds &s, int e, int c, int cend, const double *cur, double *nxt,
+                          double *OUT, int th, int nth) {
+    const int L = a.L, M = a.M, h4 = th & 3;
+    for (int i = th; i < M * 4; i += nth) { // four threads per g
+        const int g = i >> 2;
+        double m = kNone;
+        if (g == 0) { if (h4 == 0) m = cur[e]; }
+        else if (!MIRROR) for (int q = c + h4; q < e; q += 4) m = fmin(m, cur[q] + s.GU[q * M + g]); // c nodes cover at least c layers
+        else              for (int q = e + 1 + h4; q <= L - c; q += 4) m = fmin(m, cur[q] + s.GU[q * M + g]);
+        m = min4(m);
+        if (h4 == 0) OUT[c * M + g] = m;
+    }
+    if (c + 1 < cend) {
+        const int np = MIRROR ? L - e + 1 : e + 1; // layers of the side, origin included
+        for (int i = th; i < ((np * 4 + 63) & ~63); i += nth) { // whole waves
+            const int pi = i >> 2;
             double m = kNone;
-            if (g == 0) { if (h4 == 0) m = cur[e]; }
-            else if (!MIRROR) for (int q = h4; q < e; q += 4) m = fmin(m, cur[q] + s.GU[q * M + g]);
-            else              for (int q = e + 1 + h4; q <= L; q += 4) m = fmin(m, cur[q] + s.GU[q * M + g]);
-            m = min4(m);
-            if (h4 == 0) OUT[c * M + g] = m;
-        }
-        if (c + 1 < cend) {
-            const int np = MIRROR ? L - e + 1 : e + 1; // layers of the side, origin included
-            for (int i = threadIdx.x; i < ((np * 4 + 63) & ~63); i += blockDim.x) { // whole waves: the shuffles need every lane
-                const int pi = i >> 2;
-                double m = kNone;
-                if (pi < np) {
-                    const int p = MIRROR ? L - pi : pi;
-                    if (!MIRROR) for (int q = h4; q < p; q += 4) m = fmin(m, cur[q] + s.W[widx(q, p, L)]);
-                    else         for (int q = p + 1 + h4; q <= L; q += 4) m = fmin(m, cur[q] + s.W[widx(p, q, L)]);
-                }
-                m = min4(m);
-                if (h4 == 0 && pi < np) nxt[MIRROR ? L - pi : pi] = m;
+            if (pi < np) {
+                const int p = MIRROR ? L - pi : pi;
+                if (!MIRROR) for (int q = c + h4; q < p; q += 4) m = fmin(m, cur[q] + s.W[widx(q, p, L)]);
+                else         for (int q = p + 1 + h4; q <= L - c; q += 4) m = fmin(m, cur[q] + s.W[widx(p, q, L)]);
             }
+            m = min4(m);
+            if (h4 == 0 && pi < np) nxt[MIRROR ? L - pi : pi] = m;
         }
-        __syncthreads();
-        double *tmp = cur; cur = nxt; nxt = tmp;
     }
 }
 
@@ -371,11 +340,12 @@ __global__ void __launch_bounds__(1024) k_exact_lds(Args a) {
     __shared__ unsigned s_next;
     if (*a.status != OOB_OK) return; // the same for every thread: nothing is computed from a bad profile
     const int L = a.L, M = a.M, count = a.n_max - a.n_min + 1, nw = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     Lds s;
     double *p = s_dyn;
     s.W = p;    p += tri(L);
     s.GU = p;   p += (size_t)(L + 1) * M;
-    s.NP = p;   p += 2 * (size_t)(L + 1);
+    s.NP = p;   p += 4 * (size_t)(L + 1);
     s.PU = p;   p += (size_t)a.n_max * M;
     s.SV = p;   p += (size_t)a.n_max * M;
     s.lo = (int *)p;    p += ((size_t)(L + 1) * M + 1) / 2;
@@ -383,12 +353,19 @@ __global__ void __launch_bounds__(1024) k_exact_lds(Args a) {
     s.bnd = p;  p += L;
     s.best = (unsigned long long *)p; p += count;
     s.G = p;
+    // rows -kGPad .. -1 of a wave's one-node table stay "impossible": the walks run in groups of four
+    // and may pass the table's first row
+    double *G = s.G + (size_t)wave * (L + 1 + kGPad) * (M + 1) + kGPad * (M + 1);
+    for (int g = lane; g < kGPad * (M + 1); g += 64) G[g - kGPad * (M + 1)] = kNone;
     const long long *bnd = (const long long *)a.prof.boundary_ns;
     for (int i = threadIdx.x; i < L; i += blockDim.x) s.bnd[i] = (double)bnd[i];
     for (int i = threadIdx.x; i < count; i += blockDim.x) s.best[i] = 0x7FF0000000000000ull;
     // weights of a stage before / after the slowest one and of the slowest one, as (t, tau) coefficients
     const double ptau = a.Nb > 0 ? 0.0 : 4.0, stau = a.Nb > 0 ? -1.0 : 3.0, mid = a.Nb > 0 ? (double)a.Nb : 4.0;
     const unsigned ncand = (unsigned)((long long)L * (L + 1) / 2 * M);
+    // node-level phase: the first half of the waves takes the prefix side, the second half the suffix side
+    const int nwp = (nw + 1) >> 1, mir = wave >= nwp && nw > 1;
+    const int th = mir ? (int)threadIdx.x - nwp * 64 : (int)threadIdx.x, nth = nw > 1 ? (mir ? nw - nwp : nwp) * 64 : 64;
     for (;;) {
         __syncthreads(); // the previous candidate is done with LDS (and s_next has been read)
         if (threadIdx.x == 0) s_next = atomicAdd(a.counter, 1u);
@@ -403,17 +380,70 @@ __global__ void __launch_bounds__(1024) k_exact_lds(Args a) {
         const int v = u + 1 + (int)pr;
         const double tau = a.tds[((size_t)u * M + d - 1) * (L + 1) + v];
         if (!(tau < kNone)) continue; // the same for the whole workgroup
-        one_side<false>(a, s, u, tau, 1.0, ptau, s.PU);
-        one_side<true>(a, s, v, tau, 2.0, stau, s.SV);
-        // the slowest stage at every place it fits, for every template whose stage limit cannot bind
-        const int places = M - d + 1; // g = 0 .. M - d GPUs of its node before it
-        for (int n = a.n_min; n <= a.n_max; ++n) {
-            if (a.Nb > 0 && a.Nb < min(L, n * M)) continue;
-            double m = kNone;
-            for (int i = threadIdx.x; i < n * places; i += blockDim.x) {
-                const int ca = i / places, g = i % places;
-                m = fmin(m, s.PU[ca * M + g] + s.SV[(n - 1 - ca) * M + (M - d - g)]);
+        // ---- reach of a stage into every layer 1..u and out of every layer v..L-1, per GPU count ----
+        for (int i = threadIdx.x; i < (L + 1) * M; i += blockDim.x) {
+            const int pl = i / M, dd = i % M + 1;
+            int r = pl;
+            if (pl >= 1 && pl <= u) r = side_reach<false>(a, s, pl, dd, tau);
+            else if (pl >= v && pl < L) r = side_reach<true>(a, s, pl, dd, tau);
+            s.lo[i] = r;
+            s.GU[i] = kNone;
+        }
+        __syncthreads();
+        for (int pl = threadIdx.x; pl <= L; pl += blockDim.x) {
+            int m = s.lo[pl * M];
+            if (pl <= u) for (int dd = 2; dd <= M; ++dd) m = min(m, s.lo[pl * M + dd - 1]);
+            else         for (int dd = 2; dd <= M; ++dd) m = max(m, s.lo[pl * M + dd - 1]);
+            s.lomin[pl] = m;
+        }
+        __syncthreads();
+        // ---- phase 1: one-node tables, one start layer per wave at a time; the longest first, the two
+        // sides in turn (prefix starts 0 .. u-1 have u, u-1, .. rows, suffix starts L .. v+1 have L-v, .. rows)
+        {
+            const int nP = u, nS = L - v, both = 2 * min(nP, nS);
+            for (int item = wave; item < nP + nS; item += nw) {
+                int side, idx;
+                if (item < both) { side = item & 1; idx = item >> 1; }
+                else { side = nS > nP; idx = item - (both >> 1); }
+                if (!side) one_node_table<false>(a, s, u, idx, tau, 1.0, ptau * tau, G);
+                else       one_node_table<true>(a, s, v, L - idx, tau, 2.0, stau * tau, G);
             }
+        }
+        __syncthreads();
+        // ---- phase 2: node after node, both sides at once -----------------------------------------
+        {
+            // a node covers at least one layer: more whole nodes than a side has layers cover nothing
+            const int cendP = min(a.n_max, u + 1), cendS = min(a.n_max, L - v + 1);
+            double *curP = s.NP, *nxtP = s.NP + (L + 1), *curS = s.NP + 2 * (L + 1), *nxtS = s.NP + 3 * (L + 1);
+            for (int pl = threadIdx.x; pl <= L; pl += blockDim.x) {
+                curP[pl] = pl == 0 ? 0.0 : kNone;
+                curS[pl] = pl == L ? 0.0 : kNone;
+            }
+            for (int i = threadIdx.x + cendP * M; i < a.n_max * M; i += blockDim.x) s.PU[i] = kNone;
+            for (int i = threadIdx.x + cendS * M; i < a.n_max * M; i += blockDim.x) s.SV[i] = kNone;
+            __syncthreads();
+            const int cmax = max(cendP, cendS);
+            for (int cc = 0; cc < cmax; ++cc) {
+                if (nw > 1) {
+                    if (!mir) { if (cc < cendP) node_step<false>(a, s, u, cc, cendP, curP, nxtP, s.PU, th, nth); }
+                    else      { if (cc < cendS) node_step<true>(a, s, v, cc, cendS, curS, nxtS, s.SV, th, nth); }
+                } else {
+                    if (cc < cendP) node_step<false>(a, s, u, cc, cendP, curP, nxtP, s.PU, th, nth);
+                    if (cc < cendS) node_step<true>(a, s, v, cc, cendS, curS, nxtS, s.SV, th, nth);
+                }
+                __syncthreads();
+                double *tmp = curP; curP = nxtP; nxtP = tmp;
+                tmp = curS; curS = nxtS; nxtS = tmp;
+            }
+        }
+        // ---- the slowest stage at every place it fits, for every template whose stage limit cannot bind:
+        // ca whole nodes and g GPUs before it, cb whole nodes and M - d - g GPUs after it, n = ca + cb + 1
+        const int places = M - d + 1; // g = 0 .. M - d GPUs of its node before it
+        for (int i = threadIdx.x; i < a.n_max * a.n_max; i += blockDim.x) {
+            const int ca = i / a.n_max, cb = i % a.n_max, n = ca + cb + 1;
+            if (n < a.n_min || n > a.n_max || (a.Nb > 0 && a.Nb < min(L, n * M))) continue;
+            double m = kNone;
+            for (int g = 0; g < places; ++g) m = fmin(m, s.PU[ca * M + g] + s.SV[cb * M + (M - d - g)]);
             m += mid * tau;
             if (m < kNone) atomicMin(&s.best[n - a.n_min], (unsigned long long)__double_as_longlong(m));
         }
@@ -421,7 +451,6 @@ __global__ void __launch_bounds__(1024) k_exact_lds(Args a) {
     __syncthreads();
     for (int i = threadIdx.x; i < count; i += blockDim.x)
         if (s.best[i] != 0x7FF0000000000000ull) atomicMin(&a.best[i], s.best[i]);
-    (void)nw;
 }
 
 // Results as int64: -1 where no pipeline exists, -2 (unstaged entry point) where the stage limit
