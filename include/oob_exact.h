@@ -40,7 +40,7 @@ extern "C" {
 #define OOB_EXACT_MAX_L 255      /* layers                                     */
 #define OOB_EXACT_MAX_GPUS 4096  /* n_max * gpus_per_node                      */
 
-/* Bytes of device workspace (256-byte aligned) of oob_exact_minimum: two tables of stage times
+/* Bytes of device workspace (256-byte aligned) of oob_exact_minimum: three tables of stage times
  * (the dynamic programs themselves run in LDS); for shapes whose tables exceed LDS also the tables
  * of the workgroups in flight.  0 if out of range. */
 size_t oob_exact_workspace_size(int L, int n_max, int gpus_per_node);
