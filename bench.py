@@ -516,6 +516,7 @@ def main():
     lvl_ms = sum(level_ms) / len(level_ms)
     achieved = cands * FP64_OPS_PER_CANDIDATE / (lvl_ms * 1e-3)
     measured_peak = planner.valu_peak()  # add / compare / select microbenchmark on this GPU
+    measured_peak_f64 = planner.valu_peak(f64_mix=True)  # the fp64 mix of a candidate, alone on the machine
     prof4 = PROFILE_CONFIG4 if args.config == 4 and not args.paper_nb else None
     line = {
         "metric": "DP states/sec (wall-ms per full template set in ms_per_step)",
@@ -541,6 +542,8 @@ def main():
                      "avg_launch_ms": lvl_ms / launches, "levels_ms_per_step": lvl_ms,
                      "candidates_per_s": cands / (lvl_ms * 1e-3),
                      "measured_peak_int32": measured_peak / 1e12,
+                     "measured_peak_fp64_candidate_mix": measured_peak_f64 / 1e12,
+                     "frac_of_measured_fp64_mix": achieved / measured_peak_f64,
                      "int64_formulation": {"ops_per_candidate": INT64_OPS_PER_CANDIDATE,
                                            "lane_ops_per_s": cands * INT64_OPS_PER_CANDIDATE / (lvl_ms * 1e-3) / 1e12,
                                            "ratio_to_int32_peak": cands * INT64_OPS_PER_CANDIDATE / (lvl_ms * 1e-3)

@@ -176,6 +176,11 @@ int oob_plan_last_level_ms(oob_plan *h, float *ms /* HOST */);
  * that the level kernels are priced against. */
 int oob_plan_valu_peak(oob_plan *h, void *stream, double *lane_ops_per_s /* HOST */);
 
+/* The same with the fp64 instruction mix of one candidate of Eq. 1-3 as the split kernels execute it
+ * (two adds, a compare, a 64-bit select, a min against a running minimum; eight candidates per
+ * step): the rate at which the machine issues that mix when nothing else is in the way. */
+int oob_plan_valu_peak_f64(oob_plan *h, void *stream, double *lane_ops_per_s /* HOST */);
+
 /* Introspection for tests: copies the records of (S', delta) left in the workspace by the last
  * oob_plan_templates call into dense DEVICE arrays of n*n entries, n = L - S' + 1, record
  * (u, v) at index u*n + (v - S') (v - u >= S'; other entries read as "no such state").

@@ -20,7 +20,7 @@ _ERR = {OOB_EINVAL: "OOB_EINVAL", OOB_ECAPACITY: "OOB_ECAPACITY", OOB_EOVERFLOW:
 
 SYMBOLS = ["oob_plan_max_stages", "oob_plan_workspace_size", "oob_plan_create",
            "oob_plan_templates", "oob_plan_templates_batch", "oob_plan_destroy", "oob_plan_export_block",
-           "oob_plan_level_timing", "oob_plan_last_level_ms", "oob_plan_export_flags", "oob_plan_valu_peak",
+           "oob_plan_level_timing", "oob_plan_last_level_ms", "oob_plan_export_flags", "oob_plan_valu_peak", "oob_plan_valu_peak_f64",
            "oob_plan_set_option"]
 OOB_OPT_PLAIN_SPLIT, OOB_OPT_XCD_ORDER, OOB_OPT_ONE_STREAM = 1, 2, 3
 INST_SYMBOLS = ["oob_inst_workspace_size", "oob_inst_count", "oob_inst_enumerate", "oob_inst_keep_wide_table",
@@ -88,6 +88,8 @@ def load():
         L.oob_plan_export_block.restype = C.c_int
         L.oob_plan_valu_peak.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
         L.oob_plan_valu_peak.restype = C.c_int
+        L.oob_plan_valu_peak_f64.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
+        L.oob_plan_valu_peak_f64.restype = C.c_int
         L.oob_plan_set_option.argtypes = [C.c_void_p, C.c_int, C.c_int]
         L.oob_plan_set_option.restype = C.c_int
         L.oob_inst_enumerate_static.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
@@ -320,13 +322,15 @@ class Planner:
         check(load().oob_plan_last_level_ms(self.h, C.byref(ms)), "oob_plan_last_level_ms")
         return float(ms.value)
 
-    def valu_peak(self) -> float:
-        """Measured 32-bit lane-operations per second (oob_plan_valu_peak)."""
+    def valu_peak(self, f64_mix: bool = False) -> float:
+        """Measured lane-operations per second: 32-bit add / compare / select (oob_plan_valu_peak) or
+        the fp64 mix of a candidate (oob_plan_valu_peak_f64)."""
         import torch
 
         v = C.c_double()
         s = torch.cuda.current_stream(self.device)
-        check(load().oob_plan_valu_peak(self.h, C.c_void_p(s.cuda_stream), C.byref(v)), "oob_plan_valu_peak")
+        fn = load().oob_plan_valu_peak_f64 if f64_mix else load().oob_plan_valu_peak
+        check(fn(self.h, C.c_void_p(s.cuda_stream), C.byref(v)), "oob_plan_valu_peak")
         return float(v.value)
 
     def new_outputs(self, inp) -> DeviceTemplates:

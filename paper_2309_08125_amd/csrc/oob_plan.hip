@@ -338,7 +338,7 @@ __global__ void __launch_bounds__(512) k_split(Tables t, int Sp, int fam, int NT
 // and yields, per (s, state), the smallest total and the first k reaching it at once.
 // ---------------------------------------------------------------------------------------
 constexpr int kKeyTargets = 64;
-constexpr int kFillBatch = 3; // records a thread has in flight while staging
+constexpr int kFillBatch = 3; // records a thread has in flight while staging (the variant with FB = 0 has none)
 
 // Workgroup x of a launch of n -> position in the task list (OOB_TUNE_XCD=1 only).  The hardware
 // deals consecutive workgroups out to the 8 XCDs in turn; this hands every XCD one contiguous
@@ -407,8 +407,13 @@ __host__ __device__ __forceinline__ int role_cost(int y0, int y1, int q0, int q1
 // One split point per pass, one LDS buffer: while the waves work on k, every thread has the
 // records of k+1 in flight from HBM/L2 and drops them into the buffer between the two barriers
 // of the pass (NBUF = 2: two buffers and one barrier; needs more LDS, measured slower).
-template <int NTAB, int NA, int NBUF>
-__global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, int NT, int NAall, int halves,
+// FB = kFillBatch: 163 vector registers, three waves per SIMD.  FB = 0: nothing in flight, the records of
+// k+1 are fetched between the barriers; that fits 128 registers, and the classes whose LDS admits a
+// fourth workgroup per compute unit use it and run four waves per SIMD.  Measured: 3-8 % per launch
+// at the middle levels, 10 % slower launches where the machine is not full, 2 % for the call; choosing
+// per launch was slower than either (workgroups of both register footprints then share compute units).
+template <int NTAB, int NA, int NBUF, int FB>
+__global__ void __launch_bounds__(256, FB ? 1 : 4) k_split_key(Tables t, int Sp, int fam, int NT, int NAall, int halves,
                                                    int s0, int sstep) {
     // Static, separate arrays: the compiler then knows that the key merges (atomics on s_acc) never
     // touch the staged records, and keeps the reads of the next step ahead of them.
@@ -457,12 +462,12 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
 
     // rows 1..na are the targets; rows 0 and na+1 swallow the minima of targets outside the group
     for (int e = threadIdx.x; e < (na + 2) * 64; e += blockDim.x) s_acc[e] = kNoneBits;
-    Rec24 pre[kFillBatch];
+    Rec24 pre[FB ? FB : 1];
 #pragma unroll
-    for (int q = 0; q < kFillBatch; ++q) pre[q] = stage_load(g, kmin, threadIdx.x + q * blockDim.x);
+    for (int q = 0; q < FB; ++q) pre[q] = stage_load(g, kmin, threadIdx.x + q * blockDim.x);
 #pragma unroll
-    for (int q = 0; q < kFillBatch; ++q) stage_store(g, s_pair[0], s_tm[0], threadIdx.x + q * blockDim.x, pre[q]);
-    for (int e = threadIdx.x + kFillBatch * blockDim.x; e < TS; e += blockDim.x)
+    for (int q = 0; q < FB; ++q) stage_store(g, s_pair[0], s_tm[0], threadIdx.x + q * blockDim.x, pre[q]);
+    for (int e = threadIdx.x + FB * blockDim.x; e < TS; e += blockDim.x)
         stage_store(g, s_pair[0], s_tm[0], e, stage_load(g, kmin, e));
     __syncthreads();
 
@@ -477,7 +482,7 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
         const double *tmv = s_tm[cur];
         if (k < kmax) { // records of the next split point: in flight during this pass
 #pragma unroll
-            for (int q = 0; q < kFillBatch; ++q) pre[q] = stage_load(g, k + 1, threadIdx.x + q * blockDim.x);
+            for (int q = 0; q < FB; ++q) pre[q] = stage_load(g, k + 1, threadIdx.x + q * blockDim.x);
         }
         // Lanes of this pass.  Only the rows 0..jr of the block hold states that can be split at k
         // (u + s <= k), and only the columns chi-jc..chi (k <= v - r): near the ends of the block's
@@ -581,9 +586,9 @@ __global__ void __launch_bounds__(256) k_split_key(Tables t, int Sp, int fam, in
         if (NBUF == 1) __syncthreads(); // one buffer: everybody is done reading it before it is refilled
         if (k < kmax) {
 #pragma unroll
-            for (int q = 0; q < kFillBatch; ++q)
+            for (int q = 0; q < FB; ++q)
                 stage_store(g, s_pair[nxt], s_tm[nxt], threadIdx.x + q * blockDim.x, pre[q]);
-            for (int e = threadIdx.x + kFillBatch * blockDim.x; e < TS; e += blockDim.x)
+            for (int e = threadIdx.x + FB * blockDim.x; e < TS; e += blockDim.x)
                 stage_store(g, s_pair[nxt], s_tm[nxt], e, stage_load(g, k + 1, e));
         }
         __syncthreads(); // buffer cur fully consumed, buffer cur^1 complete
@@ -1203,12 +1208,15 @@ static int waves_for(const Shape &sh, int S, int fam, const SplitPlan &sp, Split
 template <int NTAB, int NA>
 static void launch_split_key_c(const Tables &t, int S, int fam, const SplitPlan &sp, int NT, int NAall,
                                SplitRange sr, hipStream_t st) {
+    const dim3 grid(seg_count(t.sh.L, S), sr.scount, sp.groups);
+    const int waves = waves_for(t.sh, S, fam, sp, sr);
+    constexpr int fb = NTAB <= 64 ? 0 : kFillBatch; // four workgroups of the classes up to 64 tables fit a compute unit's LDS
     if (kKeyNbuf == 2)
-        hipLaunchKernelGGL((k_split_key<NTAB, NA, 2>), dim3(seg_count(t.sh.L, S), sr.scount, sp.groups),
-                           dim3(waves_for(t.sh, S, fam, sp, sr) * 64), 0, st, t, S, fam, NT, NAall, sp.pc, sr.s0, sr.sstep);
+        hipLaunchKernelGGL((k_split_key<NTAB, NA, 2, kFillBatch>), grid, dim3(waves * 64), 0, st, t, S, fam, NT, NAall,
+                           sp.pc, sr.s0, sr.sstep);
     else
-        hipLaunchKernelGGL((k_split_key<NTAB, NA, 1>), dim3(seg_count(t.sh.L, S), sr.scount, sp.groups),
-                           dim3(waves_for(t.sh, S, fam, sp, sr) * 64), 0, st, t, S, fam, NT, NAall, sp.pc, sr.s0, sr.sstep);
+        hipLaunchKernelGGL((k_split_key<NTAB, NA, 1, fb>), grid, dim3(waves * 64), 0, st, t, S, fam, NT, NAall,
+                           sp.pc, sr.s0, sr.sstep);
 }
 // LDS capacity classes of k_split_key: (tables staged, targets); the smallest that fits is used.
 static const int kKeyClasses[][2] = {{24, 16}, {48, 40}, {64, 48}, {96, 48}, {96, 64}, {136, 64}};
@@ -1445,6 +1453,31 @@ __global__ void __launch_bounds__(256) k_valu_peak(int *sink, int iters, int a, 
     if (r == 0x7fffffff) sink[0] = r; // keeps the chains alive; practically never taken
 }
 
+// Measurement: the instruction mix of a candidate of the split kernels in fp64, eight candidates per
+// step as there (two adds, a compare, a 64-bit select, a min against a running minimum each), plus
+// the three adds that change the step's streaming values.  51 lane-instructions per step.
+__global__ void __launch_bounds__(256) k_valu_peak_f64(double *sink, int iters, double a, double b) {
+    double bb2[8], bbt[8], btm[8], acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        bb2[i] = a * (threadIdx.x + i); bbt[i] = b * (threadIdx.x + 2 * i); btm[i] = a * b * (3 * i + (threadIdx.x & 7));
+        acc[i] = 1e300;
+    }
+    double px = a, py = b, atm = a + b;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const double T = atm >= btm[i] ? px + bb2[i] : py + bbt[i];
+            acc[i] = fmin(acc[i], T);
+        }
+        px += a; py += b; atm += a;
+    }
+    double r = 0.0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r += acc[i];
+    if (r == 12345.678) sink[0] = r; // keeps the chains alive; practically never taken
+}
+
 // Copies flags[0..3] of the last call to a device array (tests: which split kernel ran).
 __global__ void k_export_flags(const int *flags, int *dst) {
     if (threadIdx.x < 4) dst[threadIdx.x] = flags[threadIdx.x];
@@ -1472,25 +1505,34 @@ extern "C" int oob_plan_export_block(oob_plan *h, int S, int delta, double *T, d
     return OOB_OK;
 }
 
-// Measured vector-ALU peak of this GPU in 32-bit lane-operations per second (add, compare,
-// select), for comparison with the nominal 256 CUs x 64 lanes x clock.
-extern "C" int oob_plan_valu_peak(oob_plan *h, void *stream, double *lane_ops_per_s) {
+// Measured vector-ALU peak of this GPU in lane-operations per second, for comparison with the nominal
+// 256 CUs x 64 lanes x clock: 32-bit add / compare / select (f64_mix = 0) or the fp64 instruction mix
+// of a candidate of the split kernels (f64_mix = 1).
+static int valu_peak(oob_plan *h, void *stream, double *lane_ops_per_s, int f64_mix) {
     if (!h || !lane_ops_per_s) return OOB_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     hipEvent_t e0, e1;
     OOB_HIP_CHECK(hipEventCreate(&e0));
     OOB_HIP_CHECK(hipEventCreate(&e1));
-    const int iters = 20000, grid = 256 * 32; // 32 workgroups of 4 waves per compute unit
-    int *sink = (int *)(h->ws + h->cv.flags) + 32; // spare words of the flags array
-    hipLaunchKernelGGL(k_valu_peak, dim3(grid), dim3(256), 0, st, sink, 100, 1, 1 << 30); // warm-up
-    OOB_HIP_CHECK(hipEventRecord(e0, st));
-    hipLaunchKernelGGL(k_valu_peak, dim3(grid), dim3(256), 0, st, sink, iters, 1, 1 << 30);
+    const int iters = f64_mix ? 6000 : 20000, grid = 256 * 32; // 32 workgroups of 4 waves per compute unit
+    int *sink = (int *)(h->ws + h->cv.flags) + 32; // spare words of the flags array (8-byte aligned)
+    for (int pass = 0; pass < 2; ++pass) { // warm-up, then the timed launch
+        if (pass) OOB_HIP_CHECK(hipEventRecord(e0, st));
+        if (f64_mix) hipLaunchKernelGGL(k_valu_peak_f64, dim3(grid), dim3(256), 0, st, (double *)sink, pass ? iters : 100, 1.0, 3.0);
+        else         hipLaunchKernelGGL(k_valu_peak, dim3(grid), dim3(256), 0, st, sink, pass ? iters : 100, 1, 1 << 30);
+    }
     OOB_HIP_CHECK(hipEventRecord(e1, st));
     OOB_HIP_CHECK(hipEventSynchronize(e1));
     float ms = 0.f;
     OOB_HIP_CHECK(hipEventElapsedTime(&ms, e0, e1));
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
-    *lane_ops_per_s = (double)grid * 256 * 16 * 3 * iters / (ms * 1e-3);
+    *lane_ops_per_s = (double)grid * 256 * (f64_mix ? 51.0 : 16.0 * 3) * iters / (ms * 1e-3);
     return OOB_OK;
+}
+extern "C" int oob_plan_valu_peak(oob_plan *h, void *stream, double *lane_ops_per_s) {
+    return valu_peak(h, stream, lane_ops_per_s, 0);
+}
+extern "C" int oob_plan_valu_peak_f64(oob_plan *h, void *stream, double *lane_ops_per_s) {
+    return valu_peak(h, stream, lane_ops_per_s, 1);
 }
