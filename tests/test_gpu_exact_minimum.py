@@ -78,8 +78,8 @@ def test_4S_mode_and_stage_limit_against_the_oracle(P, shape):
             st, got = P.ExactMinimum(inp, staged=True).run()
             assert st == P.OOB_OK and got == E.exact_minimum_staged(inp), (shape, seed, var)
             st, got = P.ExactMinimum(inp).run()
-            want = E.exact_minimum(inp, allow_bound=True)
-            want = [w if E.is_tight(inp, n_min + i) else P.OOB_EXACT_LIMIT_CAN_BIND for i, w in enumerate(want)]
+            want = E.exact_minimum(inp, allow_bound=True)  # marks the other templates as the boundary does
+            assert E.LIMIT_CAN_BIND == P.OOB_EXACT_LIMIT_CAN_BIND
             assert st == P.OOB_OK and got == want, (shape, seed, var)
 
 

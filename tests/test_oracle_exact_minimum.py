@@ -112,17 +112,20 @@ def test_stage_limit_and_4S_mode_equal_exhaustive_enumeration(shape):
             inp = inputs.random_small(seed, L, M, n_min, n_max, nb, f=1, tight_mem=(var == "tight"),
                                       forbid_some_d=(var == "forbid"))
             staged, loose = E.exact_minimum_staged(inp), E.exact_minimum(inp, allow_bound=True)
+            raw = E.unlimited_raw(inp)
             for n in range(n_min, n_max + 1):
                 b = bf.brute_min(inp, n)
                 b = None if b is None else b[0]
                 assert staged[n - n_min] == b, (shape, seed, var, n)
                 if E.is_tight(inp, n):
                     assert loose[n - n_min] == b, (shape, seed, var, n)
-                elif b is not None:
-                    assert loose[n - n_min] is not None and loose[n - n_min] <= b
-                    differ += loose[n - n_min] < b
                 else:
-                    differ += loose[n - n_min] is not None  # pipelines exist only beyond the limit
+                    assert loose[n - n_min] == E.LIMIT_CAN_BIND
+                    if b is not None:
+                        assert raw[n - n_min] <= b  # a minimum over more pipelines; may even be negative
+                        differ += raw[n - n_min] < b
+                    else:
+                        differ += raw[n - n_min] != -1  # pipelines exist only beyond the limit
     BINDING[shape] = differ
 
 
@@ -157,9 +160,9 @@ def test_stage_limit_hand_case():
     assert E.exact_minimum_staged(inp) == [16, 10, None, None]
     with pytest.raises(ValueError):
         E.exact_minimum(inp)
-    # without the limit three and four stages exist (and cost less: the bound is below)
-    loose = E.exact_minimum(inp, allow_bound=True)
-    assert loose[:2] == [16, 10] and loose[2] is not None and loose[3] is not None
+    # without the limit three and four stages exist: those templates are marked, not answered
+    assert E.exact_minimum(inp, allow_bound=True) == [16, 10, E.LIMIT_CAN_BIND, E.LIMIT_CAN_BIND]
+    assert E.unlimited_raw(inp)[2] != -1 and E.unlimited_raw(inp)[3] != -1
 
 
 def test_rejects_what_it_does_not_model():
