@@ -46,7 +46,8 @@ static int cmp_i64(const void *a, const void *b) {
 
 /* best[n - n_min] = the exact minimum for n nodes, or -1 if no pipeline exists.
  * Without the stage-count limit (see the header): exact for a template n when Nb = 0 or
- * Nb >= min(L, n M), a lower bound otherwise.
+ * Nb >= min(L, n M), a lower bound otherwise (which can be negative, once stages outnumber
+ * microbatches, and then cannot be told from "no pipeline": use the number only where it is exact).
  * Returns the number of distinct tau tried, or -1 for arguments it does not take. */
 int64_t oob_oracle_exact_minimum(const int64_t *fwd, const int64_t *bwd, const int64_t *mem, const int64_t *bnd,
                                  int L, int M, int n_min, int n_max, int Nb, int64_t cap, int64_t *best) {
