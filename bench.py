@@ -99,8 +99,8 @@ def call_latency(P, planner, inp, reps=7):
         times.append((time.perf_counter() - t0) * 1e3)
         assert int(res["status"][0]) == 0
     return {"median": median(times[1:]), "min": min(times[1:]), "max": max(times[1:]), "calls": reps,
-            "what": "host clock: H2D of the profile, all kernels of one oob_plan_templates call, D2H of every "
-                    "result array; one call at a time, first call dropped"}
+            "what": "host clock: H2D of the profile (one copy), all kernels of one oob_plan_templates call, D2H of "
+                    "every result array (one copy); one call at a time, first call dropped"}
 
 
 def bench_instantiation(P, inp, res, reps=20):

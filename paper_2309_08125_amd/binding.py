@@ -244,24 +244,28 @@ def oob_exact_minimum_staged(profile, L, n_min, n_max, gpus_per_node, microbatch
 
 # ---- convenience layer over torch device memory ------------------------------------------
 class DeviceProfile:
-    """A PlanInput's arrays resident in HBM."""
+    """A PlanInput's arrays resident in HBM: one device buffer, one host-to-device copy."""
+
+    KEYS = ("fwd_ns", "bwd_ns", "mem_bytes", "boundary_ns")
 
     def __init__(self, inp, device="cuda:0"):
+        import numpy as np
         import torch
 
         self.inp = inp
-        self.t = {
-            "fwd_ns": torch.from_numpy(inp.fwd_ns.reshape(-1).copy()).to(device),
-            "bwd_ns": torch.from_numpy(inp.bwd_ns.reshape(-1).copy()).to(device),
-            "mem_bytes": torch.from_numpy(inp.mem_bytes.copy()).to(device),
-            "boundary_ns": torch.from_numpy(inp.boundary_ns.copy()).to(device),
-        }
-        self.c = oob_profile(*(self.t[k].data_ptr() for k in
-                               ("fwd_ns", "bwd_ns", "mem_bytes", "boundary_ns")))
+        parts = [np.ascontiguousarray(a, dtype=np.int64).reshape(-1)
+                 for a in (inp.fwd_ns, inp.bwd_ns, inp.mem_bytes, inp.boundary_ns)]
+        self.base = torch.from_numpy(np.concatenate(parts)).to(device)
+        self.t, o = {}, 0
+        for k, a in zip(self.KEYS, parts):
+            self.t[k] = self.base[o: o + a.size]
+            o += a.size
+        self.c = oob_profile(*(self.t[k].data_ptr() for k in self.KEYS))
 
 
 class DeviceTemplates:
-    """Result buffers in HBM for `count` templates of at most Smax stages."""
+    """Result buffers in HBM for `count` templates of at most Smax stages: views of one device buffer,
+    so that the results come back in one device-to-host copy."""
 
     I32 = ("feasible", "S", "kstar", "stage_off", "stage_begin", "stage_gpus", "cover_hdr",
            "cover_maxpipes", "status")
@@ -273,15 +277,28 @@ class DeviceTemplates:
         sizes = {"feasible": count, "S": count, "kstar": count, "stage_off": count + 1,
                  "stage_begin": count * (Smax + 1), "stage_gpus": count * Smax, "cover_hdr": 8,
                  "cover_maxpipes": max(count, f + 1), "status": 1}
-        self.t = {k: torch.zeros(max(1, sizes[k]), dtype=torch.int32, device=device)
-                  for k in self.I32}
-        self.t.update({k: torch.zeros(count, dtype=torch.int64, device=device) for k in self.I64})
+        # the 64-bit arrays first, then the 32-bit ones, every array on an 8-byte boundary
+        self.layout, o = {}, 0
+        for k in self.I64:
+            self.layout[k] = (o, count, torch.int64)
+            o += 8 * count
+        for k in self.I32:
+            n = max(1, sizes[k])
+            self.layout[k] = (o, n, torch.int32)
+            o += (4 * n + 7) // 8 * 8
+        self.base = torch.zeros(o, dtype=torch.uint8, device=device)
+        self.t = {k: self.base[off: off + n * (8 if dt == torch.int64 else 4)].view(dt)
+                  for k, (off, n, dt) in self.layout.items()}
         self.c = oob_templates()
         for k in self.I32 + self.I64:
             setattr(self.c, k, self.t[k].data_ptr())
 
     def to_host(self) -> Dict[str, "object"]:
-        r = {k: v.cpu().numpy() for k, v in self.t.items()}
+        import torch
+
+        host = self.base.cpu()  # waits for the stream's work, then one copy
+        r = {k: host[off: off + n * (8 if dt == torch.int64 else 4)].view(dt).numpy()
+             for k, (off, n, dt) in self.layout.items()}
         r["states"], r["candidates"] = int(self.c.states), int(self.c.candidates)
         return r
 
