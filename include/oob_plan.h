@@ -141,8 +141,8 @@ int oob_plan_templates_batch(oob_plan *h, int count, const oob_profile *profiles
                              const int *microbatches, const int64_t *mem_cap, const int *f,
                              oob_templates *outs, void *stream);
 
-/* Releases the handle.  The caller must have waited for every call that used it (the handle's
- * second stream and events go back to a pool of the library for the next handle). */
+/* Releases the handle.  The caller must have waited for every call that used it (the streams and
+ * events the handle borrowed go back to a pool of the library for the next handle). */
 int oob_plan_destroy(oob_plan *h);
 
 /* Launch options of a handle (tests and measurements; every setting gives bit-identical results).
@@ -153,8 +153,9 @@ int oob_plan_destroy(oob_plan *h);
  *   OOB_OPT_XCD_ORDER    1: the workgroup tasks of a level are ordered block row by block row and
  *                        every XCD walks one contiguous stretch of that list (fewer bytes from
  *                        HBM, slightly more time on the headline workload); default 0
- *   OOB_OPT_ONE_STREAM   1: all levels on the caller's stream (no second stream, no events);
- *                        default 0: consecutive levels overlap on a second stream of the library
+ *   OOB_OPT_ONE_STREAM   1: all levels on the caller's stream (no other stream, no events);
+ *                        default 0: the inner splits of consecutive levels run on two streams of the
+ *                        library beside the caller's, which carries the outer splits and the selects
  * Returns OOB_EINVAL for an unknown option. */
 #define OOB_OPT_PLAIN_SPLIT 1
 #define OOB_OPT_XCD_ORDER 2
