@@ -645,6 +645,11 @@ __global__ void k_fill_keys(unsigned long long *keys, long long n) {
 // ---------------------------------------------------------------------------------------
 // Levels S' >= 2, second kernel: grid (block of the plane, delta), one lane per state.
 // ---------------------------------------------------------------------------------------
+// Loads a lane of k_select keeps in flight: keys of the splits, and pairs of child records while it looks
+// for the first m.  With 16 and 4 the kernel needs 98 registers, with 16 and 2 it needs 64 and the call
+// is 1 % faster (its waves sit on the chain between the levels and find room beside the split kernels'
+// sooner); 8 and 2 the same; one pair or 4 keys at a time: slower again, the kernel's own latency shows.
+constexpr int kSelKeys = 16, kSelPairs = 2;
 __global__ void __launch_bounds__(64) k_select(Tables t, int Sp, int NT, int NAall) {
     const int L = t.sh.L, M = t.sh.M, lane = threadIdx.x;
     int ub, vb;
@@ -657,12 +662,12 @@ __global__ void __launch_bounds__(64) k_select(Tables t, int Sp, int NT, int NAa
         const double KS = (double)(1 << key_bits(L)), inv = 1.0 / KS;
         const long long o0 = ((long long)aidx * NT + blockIdx.x) * 64 + lane, os = (long long)NAall * NT * 64;
         double bkey = kNone;
-        for (int s0 = 1; s0 < Sp; s0 += 16) { // sixteen independent loads in flight
-            double key[16];
+        for (int s0 = 1; s0 < Sp; s0 += kSelKeys) { // independent loads in flight
+            double key[kSelKeys];
 #pragma unroll
-            for (int q = 0; q < 16; ++q) key[q] = s0 + q < Sp ? t.partT[o0 + (s0 + q - 1) * os] : kNone;
+            for (int q = 0; q < kSelKeys; ++q) key[q] = s0 + q < Sp ? t.partT[o0 + (s0 + q - 1) * os] : kNone;
 #pragma unroll
-            for (int q = 0; q < 16; ++q) {
+            for (int q = 0; q < kSelKeys; ++q) {
                 const double T = floor(key[q] * inv); // +inf stays +inf
                 if (T < best) { best = T; bs = s0 + q; bkey = key[q]; }
             }
@@ -704,21 +709,21 @@ __global__ void __launch_bounds__(64) k_select(Tables t, int Sp, int NT, int NAa
         int mlo, mhi;
         m_range(fam.fam, fam.units, bs, r, M, t.sh.n_max, &mlo, &mhi);
         const double cl = t.sh.Nb > 0 ? -(double)r : 3.0 * r, cr = t.sh.Nb > 0 ? 0.0 : 4.0 * bs;
-        // first m whose candidate equals the minimum; four candidates' records in flight at a time
+        // first m whose candidate equals the minimum; kSelPairs candidates' records in flight at a time
         const long long tabA = (t.lvl_tab[bs] - dlo_of(bs, M) + fam.fam_base) * (long long)t.tab_recs +
                                (long long)tri_index(u >> 3, bk >> 3, t.NB) * 64 + ((u & 7) << 3) + (bk & 7);
         const long long tabB = (t.lvl_tab[r] - dlo_of(r, M) + fam.fam_base + fam.units) * (long long)t.tab_recs +
                                (long long)tri_index(bk >> 3, v >> 3, t.NB) * 64 + ((bk & 7) << 3) + (v & 7);
-        for (int m0 = mlo; m0 <= mhi && bm == 0; m0 += 4) {
-            Rec ra[4], rb[4];
+        for (int m0 = mlo; m0 <= mhi && bm == 0; m0 += kSelPairs) {
+            Rec ra[kSelPairs], rb[kSelPairs];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < kSelPairs; ++q) {
                 const int m = imin(m0 + q, mhi);
                 ra[q] = t.rec[tabA + (long long)m * t.tab_recs];
                 rb[q] = t.rec[tabB - (long long)m * t.tab_recs];
             }
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < kSelPairs; ++q) {
                 const double T = ra[q].tmax >= rb[q].tmax ? (ra[q].T + cl * ra[q].tmax) + 2.0 * rb[q].T1
                                                           : ra[q].T1 + (rb[q].T + cr * rb[q].tmax);
                 if (bm == 0 && m0 + q <= mhi && T == best) { bm = m0 + q; a = ra[q]; b = rb[q]; }
