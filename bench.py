@@ -40,7 +40,7 @@ INT64_OPS_PER_CANDIDATE = 30
 # counter reads for one 256 MiB device-to-device copy), and vector-ALU wave-instructions per call
 # (SQ_INSTS_VALU of k_split_key + k_select).
 PROFILE_CONFIG4 = {"source": "profiles/k_split_key_config4.md",
-                   "hbm_read_bytes_per_call": 21.67e9, "hbm_written_bytes_per_call": 5.72e9,
+                   "hbm_read_bytes_per_call": 21.53e9, "hbm_written_bytes_per_call": 5.72e9,
                    "valu_wave_insts_per_call": 3.95e9 + 0.09e9,
                    "kernel_launches_per_call": 308}  # 204 k_split_key + 97 k_select + 7 others (kernel trace)
 
