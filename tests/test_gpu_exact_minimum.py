@@ -170,3 +170,28 @@ def test_status_for_times_too_large_to_be_exact(P):
     huge = dataclasses.replace(inp, fwd_ns=inp.fwd_ns + (1 << 57))
     st, _ = P.ExactMinimum(huge, staged=True).run()
     assert st == P.OOB_EOVERFLOW
+
+
+def test_many_random_shapes(P):
+    """400 seeded random shapes (1..16 GPUs per node, all three N_b regimes, tight memory, forbidden GPU
+    counts, small times against boundary terms) against the oracle; templates whose stage limit can bind
+    carry the marker on both sides."""
+    import random
+
+    rng = random.Random(2309)
+    for n in range(400):
+        M = rng.choice([1, 2, 3, 4, 5, 7, 8, 8, 9, 12, 16])
+        L = rng.randint(1, 44 if M <= 8 else 30)
+        n_max = rng.randint(1, max(1, min(10, L)))
+        n_min = rng.randint(1, n_max)
+        nb = rng.choice([0, 0, rng.randint(1, 2 * L + 2), L * M + 5, rng.randint(1, 12)])
+        var = rng.choice(["plain", "tight", "forbid"])
+        kw = {}
+        if rng.random() < 0.3:
+            kw = dict(t_lo=1, t_hi=rng.choice([3, 4, 8]))
+        if rng.random() < 0.2:
+            kw["uniform_layers"] = True
+        inp = inputs.random_small(rng.randint(0, 10 ** 6), L, M, n_min, n_max, nb, f=1, tight_mem=(var == "tight"),
+                                  forbid_some_d=(var == "forbid"), **kw)
+        st, got = P.ExactMinimum(inp).run()
+        assert st == P.OOB_OK and got == E.exact_minimum(inp, allow_bound=True), (n, L, M, n_min, n_max, nb, var, kw)
