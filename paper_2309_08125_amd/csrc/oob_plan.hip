@@ -514,7 +514,9 @@ __global__ void __launch_bounds__(256, FB ? 1 : 4) k_split_key(Tables t, int Sp,
             const int sb = cut ? full + jj / parts : item, part = cut ? jj % parts : 0, np = cut ? parts : 1;
             // stationary blocks sb R .. sb R + R - 1 (those that exist); this lane's is mb
             const int mb_first = sb * R, mb_last = imin(mb_first + R - 1, nmb - 1);
-            const bool dead = PACK && mb_first + slot > mb_last; // a lane without a block works on the last one, unseen
+            // a lane without a block of its own repeats the last block's work for its state: the same
+            // candidates into the same keys, which a minimum does not notice (masking them cost 32
+            // selects per item)
             const int mb = PACK ? imin(mb_first + slot, mb_last) : sb;
             const int q0 = qM0 + 8 * mb;                // first stationary unit count of this lane's block
             // streaming range: every unit count some block of the item pairs with inside the target
@@ -531,7 +533,7 @@ __global__ void __launch_bounds__(256, FB ? 1 : 4) k_split_key(Tables t, int Sp,
             for (int i = 0; i < 8; ++i) {
                 const int o = fillY + (8 * mb + i) * 8 + ql;
                 const double2 p = pair[o];
-                bb2[i] = dead ? kNone : p.x; bbt[i] = dead ? kNone : p.y; btm[i] = tmv[o];
+                bb2[i] = p.x; bbt[i] = p.y; btm[i] = tmv[o];
                 acc[i] = kNone;
             }
             const double kd = (double)k;
