@@ -358,25 +358,34 @@ __device__ __forceinline__ int xcd_chunked(int x, int n) {
 // [streaming tables][lane index], then [stationary tables, padded][lane index]; the lane index
 // is u for records of the left child and v for records of the right child.
 struct Stage {
-    const Rec *rec;
-    long long tabY, tabS; // table index of unit count 0 of the streaming / stationary side
+    const Rec *recY, *recS; // first record of the table of unit count 0 of the streaming / stationary side
     int tab_recs, NB, ub, vb, nS, fillY, fill;
-    int y_is_left;        // 1: left child streams, right child stationary; 0: the other way round
+    int y_is_left;          // 1: left child streams, right child stationary; 0: the other way round
     double cl, cr;
 };
 struct Rec24 { double2 a; double tm; }; // (T, T1), tmax: the 24 bytes of a record the splits need
 
-__device__ __forceinline__ Rec24 stage_load(const Stage &g, int k, int e) {
+// Where the records of split point k sit inside a table: the left child (s, u, k, m) is row u of
+// block (ub, k/8), column k; the right child (r, k, v, m') is row k of block (k/8, vb), column v.
+// Scalar work, once per split point; per staged record only a 32-bit offset is left to form
+// (tables of one side x records of a table x 32 bytes stays below 2^32).
+struct StagePoint { const Rec *py, *ps; int shY, shS; };
+__device__ __forceinline__ StagePoint stage_point(const Stage &g, int k) {
+    const int offL = tri_index(g.ub, k >> 3, g.NB) * 64 + (k & 7), offR = tri_index(k >> 3, g.vb, g.NB) * 64 + ((k & 7) << 3);
+    StagePoint sp;
+    sp.py = g.recY + (g.y_is_left ? offL : offR);
+    sp.ps = g.recS + (g.y_is_left ? offR : offL);
+    sp.shY = g.y_is_left ? 3 : 0; // the lane index is a row of the block for left records, a column for right ones
+    sp.shS = g.y_is_left ? 0 : 3;
+    return sp;
+}
+__device__ __forceinline__ Rec24 stage_load(const Stage &g, const StagePoint &sp, int e) {
     Rec24 rc = {make_double2(kNone, kNone), 0.0};
     const bool stream = e < g.fillY;
     const int e2 = stream ? e : e - g.fillY, tab = e2 >> 3, idx = e2 & 7;
     if (e < g.fill && (stream || tab < g.nS)) {
-        const bool left = stream == (g.y_is_left != 0);
-        const long long table = (stream ? g.tabY : g.tabS) + tab;
-        // left child (s, u, k, m): row u of block (ub, k/8); right child (r, k, v, m'): row k of block (k/8, vb)
-        const Rec *p = g.rec + table * g.tab_recs +
-                       (left ? (long long)tri_index(g.ub, k >> 3, g.NB) * 64 + (idx << 3) + (k & 7)
-                             : (long long)tri_index(k >> 3, g.vb, g.NB) * 64 + ((k & 7) << 3) + idx);
+        const unsigned off = (__umul24((unsigned)tab, (unsigned)g.tab_recs) + ((unsigned)idx << (stream ? sp.shY : sp.shS))) << 5;
+        const Rec *p = (const Rec *)((const char *)(stream ? sp.py : sp.ps) + off);
         rc.a = *(const double2 *)p;
         rc.tm = p->tmax;
     }
@@ -451,10 +460,9 @@ __global__ void __launch_bounds__(256, FB ? 1 : 4) k_split_key(Tables t, int Sp,
     const double KS = (double)(1 << key_bits(L));
 
     Stage g;
-    g.rec = t.rec;
     const long long tabA = t.lvl_tab[s] - dlo_of(s, M) + fam_base, tabB = t.lvl_tab[r] - dlo_of(r, M) + fam_base;
-    g.tabY = y_left ? tabA + mA0 : tabB + mB0;
-    g.tabS = y_left ? tabB + mB0 : tabA + mA0;
+    g.recY = t.rec + (y_left ? tabA + mA0 : tabB + mB0) * t.tab_recs;
+    g.recS = t.rec + (y_left ? tabB + mB0 : tabA + mA0) * t.tab_recs;
     g.tab_recs = t.tab_recs; g.NB = t.NB; g.ub = ub; g.vb = vb; g.nS = nS;
     g.fillY = fillY; g.fill = TS; g.y_is_left = y_left;
     g.cl = t.sh.Nb > 0 ? -(double)r : 3.0 * r;
@@ -463,12 +471,15 @@ __global__ void __launch_bounds__(256, FB ? 1 : 4) k_split_key(Tables t, int Sp,
     // rows 1..na are the targets; rows 0 and na+1 swallow the minima of targets outside the group
     for (int e = threadIdx.x; e < (na + 2) * 64; e += blockDim.x) s_acc[e] = kNoneBits;
     Rec24 pre[FB ? FB : 1];
+    {
+        const StagePoint sp0 = stage_point(g, kmin);
 #pragma unroll
-    for (int q = 0; q < FB; ++q) pre[q] = stage_load(g, kmin, threadIdx.x + q * blockDim.x);
+        for (int q = 0; q < FB; ++q) pre[q] = stage_load(g, sp0, threadIdx.x + q * blockDim.x);
 #pragma unroll
-    for (int q = 0; q < FB; ++q) stage_store(g, s_pair[0], s_tm[0], threadIdx.x + q * blockDim.x, pre[q]);
-    for (int e = threadIdx.x + FB * blockDim.x; e < TS; e += blockDim.x)
-        stage_store(g, s_pair[0], s_tm[0], e, stage_load(g, kmin, e));
+        for (int q = 0; q < FB; ++q) stage_store(g, s_pair[0], s_tm[0], threadIdx.x + q * blockDim.x, pre[q]);
+        for (int e = threadIdx.x + FB * blockDim.x; e < TS; e += blockDim.x)
+            stage_store(g, s_pair[0], s_tm[0], e, stage_load(g, sp0, e));
+    }
     __syncthreads();
 
     // Work items of a split point: the 8-blocks of the stationary side, `R` of them side by side in a
@@ -480,9 +491,10 @@ __global__ void __launch_bounds__(256, FB ? 1 : 4) k_split_key(Tables t, int Sp,
         const int cur = NBUF == 2 ? (k - kmin) & 1 : 0, nxt = NBUF == 2 ? cur ^ 1 : 0;
         const double2 *pair = s_pair[cur];
         const double *tmv = s_tm[cur];
+        const StagePoint spn = stage_point(g, k + 1);
         if (k < kmax) { // records of the next split point: in flight during this pass
 #pragma unroll
-            for (int q = 0; q < FB; ++q) pre[q] = stage_load(g, k + 1, threadIdx.x + q * blockDim.x);
+            for (int q = 0; q < FB; ++q) pre[q] = stage_load(g, spn, threadIdx.x + q * blockDim.x);
         }
         // Lanes of this pass.  Only the rows 0..jr of the block hold states that can be split at k
         // (u + s <= k), and only the columns chi-jc..chi (k <= v - r): near the ends of the block's
@@ -557,11 +569,11 @@ __global__ void __launch_bounds__(256, FB ? 1 : 4) k_split_key(Tables t, int Sp,
         const double tn = *ta;                                                                        \
         _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                               \
             const double T = atm >= btm[i] ? p.x + bb2[i] : p.y + bbt[i];                             \
-            acc[((j) + i) & 7] = fmin(acc[((j) + i) & 7], T);                                         \
+            /* the eighth candidate is the first one of its target: its slot was flushed one step ago */ \
+            acc[((j) + i) & 7] = i == 7 ? T : fmin(acc[((j) + i) & 7], T);                            \
         }                                                                                             \
         const int row = imin(imax(m + aoff, -1), na) + 1;                                             \
         atomicMin(&s_acc[row * 64 + col], (unsigned long long)__double_as_longlong(fma(acc[(j)], KS, kd))); \
-        acc[(j)] = kNone;                                                                             \
         p = pn; atm = tn;                                                                             \
     }
             if (j0) {
@@ -591,7 +603,7 @@ __global__ void __launch_bounds__(256, FB ? 1 : 4) k_split_key(Tables t, int Sp,
             for (int q = 0; q < FB; ++q)
                 stage_store(g, s_pair[nxt], s_tm[nxt], threadIdx.x + q * blockDim.x, pre[q]);
             for (int e = threadIdx.x + FB * blockDim.x; e < TS; e += blockDim.x)
-                stage_store(g, s_pair[nxt], s_tm[nxt], e, stage_load(g, k + 1, e));
+                stage_store(g, s_pair[nxt], s_tm[nxt], e, stage_load(g, spn, e));
         }
         __syncthreads(); // buffer cur fully consumed, buffer cur^1 complete
     }
@@ -652,7 +664,7 @@ __global__ void k_fill_keys(unsigned long long *keys, long long n) {
 // is 1 % faster (its waves sit on the chain between the levels and find room beside the split kernels'
 // sooner); 8 and 2 the same; one pair or 4 keys at a time: slower again, the kernel's own latency shows.
 constexpr int kSelKeys = 16, kSelPairs = 2;
-__global__ void __launch_bounds__(64) k_select(Tables t, int Sp, int NT, int NAall) {
+__device__ void select_lane_per_state(const Tables &t, int Sp, int NT, int NAall) {
     const int L = t.sh.L, M = t.sh.M, lane = threadIdx.x;
     int ub, vb;
     tile_decode(L, Sp, blockIdx.x, &ub, &vb);
@@ -747,6 +759,176 @@ __global__ void __launch_bounds__(64) k_select(Tables t, int Sp, int NT, int NAa
         }
     }
     const long long o = rec_index(t, Sp, delta, ub * 8, vb * 8) + lane;
+    t.rec[o] = out;
+    t.kstar[o] = ks;
+    t.choice[o] = ch;
+}
+__global__ void __launch_bounds__(64) k_select(Tables t, int Sp, int NT, int NAall) {
+    select_lane_per_state(t, Sp, NT, NAall);
+}
+
+// ---------------------------------------------------------------------------------------
+// Levels S' >= 2, second kernel, keyed path: grid (block of the plane, delta, row of the block),
+// eight lanes per state (a wave holds the eight states of one row of the block).
+//
+// The lanes of a state share out what the state has to look at, so that each dependent round trip
+// to memory covers eight times as much as it would with one lane per state; the kernel sits on the
+// chain between the levels and its duration is made of such round trips.
+//   1. FUSE only: the two outer splits s = 1 and s = S'-1, whose one-stage child has a single unit
+//      count across nodes (a line of candidates instead of a rectangle), are evaluated here,
+//      candidate by candidate from the child records; no split kernel is launched for them.
+//   2. The keys of the (other) splits: smallest total, then smallest s (a key holds its smallest k).
+//   3. The eight partial minima of a state are merged in the order (T, s, k, m).
+//   4. A winner that came from a key does not know its m yet: the lanes test eight m at a time.
+//   5. Lane 0 of the state forms the record from the two child records.
+// Without keys (flags[0] = 0) the wave of row 0 evaluates the block one lane per state as k_select does.
+// ---------------------------------------------------------------------------------------
+constexpr int kSel8Keys = 8;   // keys a lane has in flight (64 splits per round of a state)
+constexpr int kSel8Outer = 4;  // candidates of the outer splits a lane has in flight
+constexpr int kSel8M = 2;      // m a lane tests per round (16 per state)
+
+__device__ __forceinline__ Rec24 load24(const Rec *p) {
+    Rec24 r;
+    r.a = *(const double2 *)p;
+    r.tm = p->tmax;
+    return r;
+}
+// Eq. 1-3 for one candidate from the (T, T1, tmax) of its children.
+__device__ __forceinline__ double cand_total(const Rec24 &a, const Rec24 &b, double cl, double cr) {
+    return a.tm >= b.tm ? (a.a.x + cl * a.tm) + 2.0 * b.a.y : a.a.y + (b.a.x + cr * b.tm);
+}
+
+template <bool FUSE>
+__global__ void __launch_bounds__(64) k_select8(Tables t, int Sp, int NT, int NAall) {
+    if (t.flags[0] == 0) {
+        if (blockIdx.z == 0) select_lane_per_state(t, Sp, NT, NAall);
+        return;
+    }
+    const int L = t.sh.L, M = t.sh.M, lane = threadIdx.x, sub = lane & 7, st = lane >> 3;
+    int ub, vb;
+    tile_decode(L, Sp, blockIdx.x, &ub, &vb);
+    const int aidx = blockIdx.y, delta = dlo_of(Sp, M) + aidx;
+    const int tl = blockIdx.z * 8 + st, u = ub * 8 + blockIdx.z, v = vb * 8 + st;
+    const bool valid = v <= L && v - u >= Sp;
+    const Family fam = family_of(delta, M);
+    const bool fixed_nb = t.sh.Nb > 0;
+    const long long trecs = t.tab_recs;
+    double best = kNone;
+    unsigned btag = 0xffffffffu; // s << 21 | k << 10 | m (m = 0: not known yet)
+
+    if (FUSE && valid) {
+        const int nk = v - u - Sp + 1; // split points u + s .. v - r of either outer split
+        for (int side = 0; side < (Sp > 2 ? 2 : 1); ++side) {
+            const int s = side ? Sp - 1 : 1, r = Sp - s;
+            int mlo, mhi;
+            m_range(fam.fam, fam.units, s, r, M, t.sh.n_max, &mlo, &mhi);
+            const double cl = fixed_nb ? -(double)r : 3.0 * r, cr = fixed_nb ? 0.0 : 4.0 * s;
+            const Rec *baseA = t.rec + (t.lvl_tab[s] - dlo_of(s, M) + fam.fam_base) * trecs + ((u & 7) << 3);
+            const Rec *baseB = t.rec + (t.lvl_tab[r] - dlo_of(r, M) + fam.fam_base + fam.units) * trecs + (v & 7);
+            for (int m = mlo; m <= mhi; ++m)
+                for (int j0 = sub; j0 < nk; j0 += 8 * kSel8Outer) {
+                    Rec24 ra[kSel8Outer], rb[kSel8Outer];
+                    int kk[kSel8Outer];
+#pragma unroll
+                    for (int q = 0; q < kSel8Outer; ++q) { // past the end: the last candidate again
+                        const int k = u + s + imin(j0 + 8 * q, nk - 1);
+                        kk[q] = k;
+                        ra[q] = load24(baseA + m * trecs + (long long)tri_index(u >> 3, k >> 3, t.NB) * 64 + (k & 7));
+                        rb[q] = load24(baseB - m * trecs + (long long)tri_index(k >> 3, v >> 3, t.NB) * 64 + ((k & 7) << 3));
+                    }
+#pragma unroll
+                    for (int q = 0; q < kSel8Outer; ++q) {
+                        const double T = cand_total(ra[q], rb[q], cl, cr);
+                        const unsigned tag = ((unsigned)s << 21) | ((unsigned)kk[q] << 10) | (unsigned)m;
+                        if (T < best || (T == best && tag < btag)) { best = T; btag = tag; }
+                    }
+                }
+        }
+    }
+    if (valid) { // keys total * 2^kbits + k; consumed keys go back to "no such state"
+        const double KS = (double)(1 << key_bits(L)), inv = 1.0 / KS;
+        const int s_lo = FUSE ? 2 : 1, s_hi = FUSE ? Sp - 2 : Sp - 1;
+        const long long o0 = ((long long)aidx * NT + blockIdx.x) * 64 + tl, os = (long long)NAall * NT * 64;
+        for (int s0 = s_lo + sub; s0 <= s_hi; s0 += 8 * kSel8Keys) {
+            double key[kSel8Keys];
+#pragma unroll
+            for (int q = 0; q < kSel8Keys; ++q) {
+                const int s = s0 + 8 * q;
+                key[q] = s <= s_hi ? t.partT[o0 + (s - 1) * os] : kNone;
+            }
+#pragma unroll
+            for (int q = 0; q < kSel8Keys; ++q) {
+                const int s = s0 + 8 * q;
+                if (s <= s_hi) t.partT[o0 + (s - 1) * os] = kNone;
+            }
+#pragma unroll
+            for (int q = 0; q < kSel8Keys; ++q) {
+                const int s = s0 + 8 * q;
+                const double T = floor(key[q] * inv);
+                if (T < kNone) {
+                    const unsigned tag = ((unsigned)s << 21) | ((unsigned)(int)(key[q] - T * KS) << 10);
+                    if (T < best || (T == best && tag < btag)) { best = T; btag = tag; }
+                }
+            }
+        }
+    }
+    // the eight lanes of a state: smallest (T, s, k, m)
+#pragma unroll
+    for (int d = 1; d < 8; d <<= 1) {
+        const double ob = __shfl_xor(best, d, 64);
+        const unsigned ot = (unsigned)__shfl_xor((int)btag, d, 64);
+        if (ob < best || (ob == best && ot < btag)) { best = ob; btag = ot; }
+    }
+    const int bs = (int)(btag >> 21), bk = (int)((btag >> 10) & 2047u);
+    int bm = (int)(btag & 1023u);
+    if (best < kNone && bm == 0) { // first m whose candidate equals the minimum, eight m side by side
+        const int r = Sp - bs;
+        int mlo, mhi;
+        m_range(fam.fam, fam.units, bs, r, M, t.sh.n_max, &mlo, &mhi);
+        const double cl = fixed_nb ? -(double)r : 3.0 * r, cr = fixed_nb ? 0.0 : 4.0 * bs;
+        const Rec *baseA = t.rec + (t.lvl_tab[bs] - dlo_of(bs, M) + fam.fam_base) * trecs +
+                           (long long)tri_index(u >> 3, bk >> 3, t.NB) * 64 + ((u & 7) << 3) + (bk & 7);
+        const Rec *baseB = t.rec + (t.lvl_tab[r] - dlo_of(r, M) + fam.fam_base + fam.units) * trecs +
+                           (long long)tri_index(bk >> 3, v >> 3, t.NB) * 64 + ((bk & 7) << 3) + (v & 7);
+        for (int m0 = mlo + sub; m0 - sub <= mhi && bm == 0; m0 += 8 * kSel8M) {
+            Rec24 ra[kSel8M], rb[kSel8M];
+#pragma unroll
+            for (int q = 0; q < kSel8M; ++q) {
+                const int m = imin(m0 + 8 * q, mhi);
+                ra[q] = load24(baseA + m * trecs);
+                rb[q] = load24(baseB - m * trecs);
+            }
+            int found = 0x7fffffff;
+#pragma unroll
+            for (int q = kSel8M - 1; q >= 0; --q) {
+                const int m = m0 + 8 * q;
+                if (m <= mhi && cand_total(ra[q], rb[q], cl, cr) == best) found = m;
+            }
+#pragma unroll
+            for (int d = 1; d < 8; d <<= 1) found = imin(found, __shfl_xor(found, d, 64));
+            if (found != 0x7fffffff) bm = found;
+        }
+    }
+    if (sub != 0) return;
+    Rec out = {kNone, kNone, 0.0, 0.0};
+    int ks = 0, ch = 0;
+    if (best < kNone) {
+        if (bm == 0) {
+            *t.status = kInternalError;
+        } else {
+            const int r = Sp - bs;
+            const long long oa = rec_index(t, bs, fam.fam_base + bm, u, bk);
+            const long long ob = rec_index(t, r, fam.fam_base + fam.units - bm, bk, v);
+            const Rec a = t.rec[oa], b = t.rec[ob];
+            const int ka = t.kstar[oa], kb = t.kstar[ob];
+            out.T = best;
+            out.T1 = a.T1 + b.T1;                                                     // Eq. 1
+            if (a.tmax >= b.tmax) { out.tmax = a.tmax; ks = ka; out.T3 = a.T3 + b.T1; } // Eq. 3
+            else                  { out.tmax = b.tmax; ks = bs + kb; out.T3 = b.T3; }
+            ch = bs | (bk << 10) | (bm << 21);
+        }
+    }
+    const long long o = rec_index(t, Sp, delta, ub * 8, vb * 8) + tl;
     t.rec[o] = out;
     t.kstar[o] = ks;
     t.choice[o] = ch;
@@ -999,6 +1181,9 @@ static const int kKeyPack = env_or("OOB_TUNE_KEY_PACK", 1);
 static const int kKeyNbuf = env_or("OOB_TUNE_KEY_NBUF", 1);
 static const int kBatchOverlap = env_or("OOB_TUNE_BATCH_OVERLAP", 0);
 static const int kBatchLanes = env_or("OOB_TUNE_BATCH_LANES", 8);
+static const int kFuseLo = env_or("OOB_TUNE_FUSE_LO", 0);
+static const int kFuseHi = env_or("OOB_TUNE_FUSE_HI", 82);
+static const int kSel8From = env_or("OOB_TUNE_SEL8_FROM", 82);
 bool plan_split_key(const Shape &sh, int Sp, int fam, int xcd_order, SplitPlan *p) {
     int t_lo, t_hi;
     target_units(fam, Sp, sh.M, sh.n_max, &t_lo, &t_hi);
@@ -1341,16 +1526,21 @@ static int enqueue_job(oob_plan *h, int ln, bool want_overlap, const oob_profile
                 if (have[fam]) launch_split_key(tl, S, fam, kp[fam], NT, NAall, SplitRange{2, 1, S - 3}, sx);
             OOB_HIP_CHECK(hipEventRecord(lane.ev_level[2 * S + 1], sx));
         }
+        // the outer splits: launches of their own, or evaluated by the select kernel itself
+        const bool fuse = !force_plain && (S <= kFuseLo || S >= kFuseHi);
         for (int fam = 0; fam < 2; ++fam) {
             if (!have[fam]) continue;
-            const SplitRange sr = inner ? SplitRange{1, S - 2, 2} : SplitRange{1, 1, S - 1};
+            SplitRange sr = inner ? SplitRange{1, S - 2, 2} : SplitRange{1, 1, S - 1};
+            if (fuse) sr = inner ? SplitRange{1, 1, 0} : SplitRange{2, 1, S - 3};
             if (!force_plain) launch_split_key(tl, S, fam, kp[fam], NT, NAall, sr, st);
             else if (sp[fam].pc == 4) launch_split<4>(tl, S, fam, sp[fam], NT, NAall, st);
             else if (sp[fam].pc == 2) launch_split<2>(tl, S, fam, sp[fam], NT, NAall, st);
             else launch_split<1>(tl, S, fam, sp[fam], NT, NAall, st);
         }
         if (inner) OOB_HIP_CHECK(hipStreamWaitEvent(st, lane.ev_level[2 * S + 1], 0));
-        hipLaunchKernelGGL(k_select, dim3(NT, NAall), dim3(64), 0, st, tl, S, NT, NAall);
+        if (force_plain || (!fuse && S < kSel8From)) hipLaunchKernelGGL(k_select, dim3(NT, NAall), dim3(64), 0, st, tl, S, NT, NAall);
+        else if (fuse) hipLaunchKernelGGL(k_select8<true>, dim3(NT, NAall, 8), dim3(64), 0, st, tl, S, NT, NAall);
+        else hipLaunchKernelGGL(k_select8<false>, dim3(NT, NAall, 8), dim3(64), 0, st, tl, S, NT, NAall);
         if (overlap) OOB_HIP_CHECK(hipEventRecord(lane.ev_level[2 * S], st));
     }
     if (timed) { OOB_HIP_CHECK(hipEventRecord(h->ev_end, st)); h->timed = true; }
