@@ -82,49 +82,90 @@ __device__ __forceinline__ long long rec_index(const Tables &t, int S, int delta
 
 // ---------------------------------------------------------------------------------------
 // Set-up: prefix sums (Eq. 4's sums become differences), input validation, level offsets.
-// One block; thread d-1 scans the profile row of d GPUs.
+// One workgroup of 16 waves: a wave scans the profile row of d GPUs, 64 entries at a time (sums
+// saturate, so that no input can overflow them; a saturated sum is reported, not used); one wave
+// scans the bytes and the boundary terms, one lays out the levels.
 // ---------------------------------------------------------------------------------------
-__global__ void k_setup(Tables t, oob_profile prof, int force_plain) {
+constexpr int kSetupThreads = 1024;
+
+// Inclusive scan over the lanes of min(a + b, cap) for values in [0, cap], cap <= 2^62.
+__device__ __forceinline__ unsigned long long scan_sat(unsigned long long x, unsigned long long cap, int lane) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned long long y = __shfl_up(x, d, 64);
+        if (lane >= d) { x += y; if (x > cap) x = cap; }
+    }
+    return x;
+}
+__device__ __forceinline__ int scan_int(int x, int lane) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int y = __shfl_up(x, d, 64);
+        if (lane >= d) x += y;
+    }
+    return x;
+}
+
+__device__ void setup_body(const Tables &t, const oob_profile &prof, int force_plain) {
     const int L = t.sh.L, M = t.sh.M, W = L + 1;
     __shared__ long long s_worst[OOB_MAX_GPUS + 1];
     __shared__ int s_bad;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     if (threadIdx.x == 0) s_bad = 0;
     __syncthreads();
-    const int d = threadIdx.x + 1;
-    if (d <= M) {
-        long long acc = 0;
-        int forb = 0, bad = 0;
-        t.PT[d * W] = 0;
-        t.PF[d * W] = 0;
-        for (int l = 0; l < L; ++l) {
-            const long long F = prof.fwd_ns[(size_t)l * M + d - 1], B = prof.bwd_ns[(size_t)l * M + d - 1];
-            if (F < 0 || B < 0) bad = imax(bad, 1);
-            const int fb = (F >= OOB_FORBIDDEN || B >= OOB_FORBIDDEN);
-            if (!fb && F >= 0 && B >= 0) {
-                if (F >= kExactBound || B >= kExactBound || acc + F + B >= kExactBound) { bad = imax(bad, 2); acc = 0; }
-                else acc += F + B;
-            }
-            forb += fb;
-            t.PT[d * W + l + 1] = acc;
-            t.PF[d * W + l + 1] = forb;
+    const unsigned long long capT = (unsigned long long)kExactBound, capM = (unsigned long long)OOB_FORBIDDEN;
+    int bad = 0;
+    for (int d = 1 + wave; d <= M && wave < nw - 2; d += nw - 2) { // row of d GPUs
+        unsigned long long carry = 0;
+        int fcarry = 0;
+        if (lane == 0) { t.PT[d * W] = 0; t.PF[d * W] = 0; }
+        for (int l0 = 0; l0 < L; l0 += 64) {
+            const int l = l0 + lane;
+            const bool in = l < L;
+            const long long F = in ? prof.fwd_ns[(size_t)l * M + d - 1] : 0, B = in ? prof.bwd_ns[(size_t)l * M + d - 1] : 0;
+            const bool neg = F < 0 || B < 0;
+            const bool fb = F >= OOB_FORBIDDEN || B >= OOB_FORBIDDEN;
+            const bool big = !neg && !fb && (F >= kExactBound || B >= kExactBound);
+            if (neg) bad = imax(bad, 1);
+            if (big) bad = imax(bad, 2);
+            unsigned long long x = (neg || fb || big) ? 0ull : (unsigned long long)(F + B);
+            if (x > capT) x = capT;
+            x = scan_sat(x, capT, lane) + carry;
+            if (x > capT) x = capT;
+            const int c = scan_int(fb ? 1 : 0, lane) + fcarry;
+            if (in) { t.PT[d * W + l + 1] = (long long)x; t.PF[d * W + l + 1] = c; }
+            carry = __shfl(x, 63, 64);
+            fcarry = __shfl(c, 63, 64);
         }
-        s_worst[d] = acc;
-        if (bad) atomicMax(&s_bad, bad);
+        if (carry >= capT) bad = imax(bad, 2);
+        if (lane == 0) s_worst[d] = (long long)carry;
     }
-    if (threadIdx.x == blockDim.x - 1) { // bytes, boundary terms, level offsets
-        long long acc = 0, xs = 0;
-        int bad = 0;
-        t.PM[0] = 0;
-        for (int l = 0; l < L; ++l) {
-            const long long mb = prof.mem_bytes[l], x = prof.boundary_ns[l];
-            if (mb < 0 || x < 0 || mb >= OOB_FORBIDDEN || acc + mb >= OOB_FORBIDDEN) bad = imax(bad, 1);
-            else acc += mb;
-            if (x >= kExactBound || xs + x >= kExactBound) bad = imax(bad, 2);
-            else if (x > 0) xs += x;
-            t.PM[l + 1] = acc;
+    if (wave == nw - 2) { // bytes and boundary terms
+        unsigned long long cm = 0, cx = 0;
+        if (lane == 0) t.PM[0] = 0;
+        for (int l0 = 0; l0 < L; l0 += 64) {
+            const int l = l0 + lane;
+            const bool in = l < L;
+            const long long mb = in ? prof.mem_bytes[l] : 0, xb = in ? prof.boundary_ns[l] : 0;
+            const bool badm = mb < 0 || mb >= OOB_FORBIDDEN;
+            if (badm || xb < 0) bad = imax(bad, 1);
+            if (xb >= kExactBound) bad = imax(bad, 2);
+            unsigned long long m = badm ? 0ull : (unsigned long long)mb;
+            m = scan_sat(m, capM, lane) + cm;
+            if (m > capM) m = capM;
+            unsigned long long x = (xb < 0 || xb >= kExactBound) ? 0ull : (unsigned long long)xb;
+            x = scan_sat(x, capT, lane) + cx;
+            if (x > capT) x = capT;
+            if (in) t.PM[l + 1] = (long long)m;
+            cm = __shfl(m, 63, 64);
+            cx = __shfl(x, 63, 64);
         }
-        s_worst[0] = xs;
-        if (bad) atomicMax(&s_bad, bad);
+        if (cm >= capM) bad = imax(bad, 1);
+        if (cx >= capT) bad = imax(bad, 2);
+        if (lane == 0) s_worst[0] = (long long)cx;
+    }
+    if (bad) atomicMax(&s_bad, bad);
+    if (threadIdx.x == blockDim.x - 1) { // level offsets
         long long tab = 0;
         for (int S = 1; S <= t.sh.Smax + 1; ++S) {
             t.lvl_tab[S] = tab;
@@ -622,8 +663,7 @@ __global__ void __launch_bounds__(256, FB ? 1 : 4) k_split_key(Tables t, int Sp,
 // first.  by_row = 1 (OOB_TUNE_XCD=1, used together with xcd_chunked): block row ub, then segment,
 // then the blocks of that row from the far end, so that neighbours in the list split at the same
 // points k and stage the same left-child records.
-__global__ void k_seg_tab(Tables t, int by_row) {
-    const int S = blockIdx.x + 2;
+__device__ void seg_tab_body(const Tables &t, int S, int by_row) {
     if (S > t.sh.Smax || threadIdx.x != 0) return;
     const int L = t.sh.L, NB = nblocks_of(L), ubmax = (L - S) / 8, dmin = tile_dmin(S);
     int2 *out = t.seg_tab + (long long)(S - 2) * t.seg_stride;
@@ -650,9 +690,15 @@ __global__ void k_seg_tab(Tables t, int by_row) {
     }
 }
 
-// Sets n keys to "no such state".
-__global__ void k_fill_keys(unsigned long long *keys, long long n) {
-    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+// Everything a call needs before level 1, as one launch of kSetupThreads-wide workgroups:
+// workgroup 0 the set-up, workgroups 1 .. Smax-1 the task lists of the levels 2 .. Smax, the rest
+// set the n keys of the per-split minima to "no such state".  The three parts touch disjoint memory.
+__global__ void __launch_bounds__(kSetupThreads) k_prepare(Tables t, oob_profile prof, int force_plain, int by_row,
+                                                           unsigned long long *keys, long long n) {
+    const int b = blockIdx.x, nseg = imax(t.sh.Smax - 1, 0);
+    if (b == 0) { setup_body(t, prof, force_plain); return; }
+    if (b <= nseg) { seg_tab_body(t, b + 1, by_row); return; }
+    const long long i = (long long)(b - 1 - nseg) * blockDim.x + threadIdx.x;
     if (i < n) keys[i] = 0x7FF0000000000000ull;
 }
 
@@ -935,20 +981,28 @@ __global__ void __launch_bounds__(64) k_select8(Tables t, int Sp, int NT, int NA
 }
 
 // ---------------------------------------------------------------------------------------
-// Template extraction ("Choosing the number of stages"): thread i handles n = n_min + i.
+// Template extraction ("Choosing the number of stages"): one wave per template size
+// n = n_min + blockIdx.x, the lanes share out the stage counts; smallest T, then smallest S.
 // ---------------------------------------------------------------------------------------
-__global__ void k_pick(Tables t, oob_templates out) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= t.sh.count) return;
+__global__ void __launch_bounds__(64) k_pick(Tables t, oob_templates out) {
+    const int i = blockIdx.x, lane = threadIdx.x;
     const int L = t.sh.L, M = t.sh.M, n = t.sh.n_min + i, delta = M - 2 + n;
     double best = kNone;
-    int bestS = 0;
+    int bestS = 0x7fffffff;
     if (n <= t.sh.n_max)
-        for (int S = n; S <= t.sh.Smax; ++S) {
+        for (int S = n + lane; S <= t.sh.Smax; S += 64) { // ascending per lane: the first minimum stays
             if (delta < dlo_of(S, M) || delta > dhi_of(S, M, t.sh.n_max)) continue;
             const double T = t.rec[rec_index(t, S, delta, 0, L)].T;
             if (T < best) { best = T; bestS = S; }
         }
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const double ob = __shfl_xor(best, d, 64);
+        const int os = __shfl_xor(bestS, d, 64);
+        if (ob < best || (ob == best && os < bestS)) { best = ob; bestS = os; }
+    }
+    if (lane != 0) return;
+    if (!(best < kNone)) bestS = 0;
     out.feasible[i] = bestS > 0;
     out.S[i] = bestS;
     long long T = 0, T1 = 0, T2 = 0, T3 = 0, tm = 0;
@@ -964,39 +1018,44 @@ __global__ void k_pick(Tables t, oob_templates out) {
     out.T[i] = T; out.T1[i] = T1; out.T2[i] = T2; out.T3[i] = T3; out.tmax[i] = tm; out.kstar[i] = ks;
 }
 
-// Expands the stored (s, k, m) tree of each template left to right into stages.
-__global__ void k_backtrack(Tables t, oob_templates out) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i > t.sh.count) return;
+// Stages of each template from the stored (s, k, m) tree: one workgroup per template, one thread
+// per stage.  Thread p walks from the root to the p-th leaf (left subtree if p is below the left
+// child's stage count, else right with p reduced by it), so the walks of a template run side by
+// side and the kernel takes as long as the deepest leaf, not as the whole tree.
+// Workgroup `count` only writes the end of the offsets.
+__global__ void __launch_bounds__(128) k_backtrack(Tables t, oob_templates out) {
+    __shared__ long long s_lvl[OOB_MAX_L + 3];
+    __shared__ int s_part[128];
+    const int i = blockIdx.x, tid = threadIdx.x, cnt = t.sh.count;
+    int part = 0;
+    for (int q = tid; q < i && q < cnt; q += blockDim.x) part += out.S[q];
+    s_part[tid] = part;
+    for (int S = tid; S <= t.sh.Smax + 1; S += blockDim.x) s_lvl[S] = t.lvl_tab[S];
+    __syncthreads();
     int off = 0;
-    for (int q = 0; q < i && q < t.sh.count; ++q) off += out.S[q];
-    out.stage_off[i] = off;
-    if (i == t.sh.count) return;
+    for (int q = 0; q < (int)blockDim.x; ++q) off += s_part[q];
+    if (tid == 0) out.stage_off[i] = off;
+    if (i >= cnt) return;
     const int S = out.S[i];
     if (S == 0) return;
     const int L = t.sh.L, M = t.sh.M;
-    int *stk = t.stack + (size_t)i * (t.sh.Smax + 1) * 4;
     int *begin = out.stage_begin + off + i, *gpus = out.stage_gpus + off;
-    int sp = 0, pos = 0;
-    stk[0] = S; stk[1] = M - 2 + t.sh.n_min + i; stk[2] = 0; stk[3] = L; sp = 1;
-    while (sp > 0 && pos < S) {
-        --sp;
-        const int Sq = stk[sp * 4], delta = stk[sp * 4 + 1], u = stk[sp * 4 + 2], v = stk[sp * 4 + 3];
-        if (Sq == 1) {
-            begin[pos] = u;
-            gpus[pos] = delta < M - 1 ? delta + 1 : M;
-            ++pos;
-            continue;
+    for (int p = tid; p < S; p += blockDim.x) {
+        int Sq = S, delta = M - 2 + t.sh.n_min + i, u = 0, v = L, pos = p;
+        while (Sq > 1) {
+            const long long o = (s_lvl[Sq] + (delta - dlo_of(Sq, M))) * t.tab_recs +
+                                (long long)tri_index(u >> 3, v >> 3, t.NB) * 64 + ((u & 7) << 3) + (v & 7);
+            const int ch = t.choice[o];
+            const int s = ch & 1023, k = (ch >> 10) & 2047, m = (ch >> 21) & 1023;
+            const Family fam = family_of(delta, M);
+            if (s < 1 || s >= Sq) { *t.status = kInternalError; break; }
+            if (pos < s) { Sq = s; delta = fam.fam_base + m; v = k; }
+            else         { pos -= s; Sq -= s; delta = fam.fam_base + fam.units - m; u = k; }
         }
-        const int ch = t.choice[rec_index(t, Sq, delta, u, v)];
-        const int s = ch & 1023, k = (ch >> 10) & 2047, m = (ch >> 21) & 1023;
-        const Family fam = family_of(delta, M);
-        if (sp + 2 > t.sh.Smax + 1 || s < 1 || s >= Sq) { *t.status = kInternalError; break; }
-        // right half first so that the left half is expanded first
-        stk[sp * 4] = Sq - s; stk[sp * 4 + 1] = fam.fam_base + fam.units - m; stk[sp * 4 + 2] = k; stk[sp * 4 + 3] = v; ++sp;
-        stk[sp * 4] = s; stk[sp * 4 + 1] = fam.fam_base + m; stk[sp * 4 + 2] = u; stk[sp * 4 + 3] = k; ++sp;
+        begin[p] = u;
+        gpus[p] = delta < M - 1 ? delta + 1 : M;
     }
-    begin[S] = L;
+    if (tid == 0) begin[S] = L;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1477,13 +1536,11 @@ static int enqueue_job(oob_plan *h, int ln, bool want_overlap, const oob_profile
     const Tables t = make_tables(h, ln, sh, (int *)out->status);
     work_counts(sh, (long long *)&out->states, (long long *)&out->candidates);
 
-    hipLaunchKernelGGL(k_setup, dim3(1), dim3(OOB_MAX_GPUS + 1), 0, st, t, *profile, force_plain);
+    const long long slot_stride = h->cv.slots * 64; // distance between the two buffers of per-split minima
+    hipLaunchKernelGGL(k_prepare, dim3((unsigned)(1 + imax(sh.Smax - 1, 0) + (2 * slot_stride + kSetupThreads - 1) / kSetupThreads)),
+                       dim3(kSetupThreads), 0, st, t, *profile, force_plain, h->opt_xcd, t.partKey, 2 * slot_stride);
     hipLaunchKernelGGL(k_level1, dim3(tile_count(L, 1), M), dim3(64), 0, st, t,
                        (const long long *)profile->boundary_ns);
-    if (sh.Smax >= 2) hipLaunchKernelGGL(k_seg_tab, dim3(sh.Smax - 1), dim3(64), 0, st, t, h->opt_xcd);
-    const long long slot_stride = h->cv.slots * 64; // distance between the two buffers of per-split minima
-    hipLaunchKernelGGL(k_fill_keys, dim3((unsigned)((2 * slot_stride + 255) / 256)), dim3(256), 0, st, t.partKey,
-                       2 * slot_stride);
     // Levels.  Level S' depends on the lower levels like this: its inner splits 2 <= s <= S'-2 read the
     // levels up to S'-2 only, its two outer splits (s = 1 and S'-1) read level S'-1, and its select
     // needs all its splits.  So the chain that cannot be shortened is outer splits -> select ->
@@ -1544,8 +1601,8 @@ static int enqueue_job(oob_plan *h, int ln, bool want_overlap, const oob_profile
         if (overlap) OOB_HIP_CHECK(hipEventRecord(lane.ev_level[2 * S], st));
     }
     if (timed) { OOB_HIP_CHECK(hipEventRecord(h->ev_end, st)); h->timed = true; }
-    hipLaunchKernelGGL(k_pick, dim3((sh.count + 63) / 64), dim3(64), 0, st, t, *out);
-    hipLaunchKernelGGL(k_backtrack, dim3((sh.count + 1 + 63) / 64), dim3(64), 0, st, t, *out);
+    hipLaunchKernelGGL(k_pick, dim3(sh.count), dim3(64), 0, st, t, *out);
+    hipLaunchKernelGGL(k_backtrack, dim3(sh.count + 1), dim3(128), 0, st, t, *out);
     const int len = sh.count > f + 1 ? sh.count : f + 1;
     hipLaunchKernelGGL(k_coverage, dim3(1), dim3(64), 0, st, t, *out, len);
     OOB_HIP_CHECK(hipGetLastError());
