@@ -462,14 +462,14 @@ __host__ __device__ __forceinline__ int role_cost(int y0, int y1, int q0, int q1
 // fourth workgroup per compute unit use it and run four waves per SIMD.  Measured: 3-8 % per launch
 // at the middle levels, 10 % slower launches where the machine is not full, 2 % for the call; choosing
 // per launch was slower than either (workgroups of both register footprints then share compute units).
-template <int NTAB, int NA, int NBUF, int FB>
+template <int NTAB, int NBUF, int FB>
 __global__ void __launch_bounds__(256, FB ? 1 : 4) k_split_key(Tables t, int Sp, int fam, int NT, int NAall, int halves,
                                                    int s0, int sstep) {
     // Static, separate arrays: the compiler then knows that the key merges (atomics on s_acc) never
     // touch the staged records, and keeps the reads of the next step ahead of them.
     __shared__ double2 s_pair[NBUF][NTAB * 8]; // [buffer][staging order]: pre-combined pairs
     __shared__ double s_tm[NBUF][NTAB * 8];    // tmax (negated when the right child streams)
-    __shared__ unsigned long long s_acc[(NA + 2) * 64]; // keys, rows 1..na
+    HIP_DYNAMIC_SHARED(unsigned long long, s_acc)       // [(na + 2) * 64] keys, rows 1..na (sized by the launch)
     if (t.flags[0] == 0) return;        // keys do not fit: k_select evaluates the candidates itself
     const int L = t.sh.L, M = t.sh.M, n_max = t.sh.n_max;
     const int s = s0 + blockIdx.y * sstep, r = Sp - s; // a launch covers the splits s0, s0 + sstep, ...
@@ -1237,7 +1237,6 @@ int env_or(const char *name, int dflt) {
 static const int kKeyWaves = env_or("OOB_TUNE_KEY_WAVES", 4);
 static const int kKeyHalves = env_or("OOB_TUNE_KEY_HALVES", 2);
 static const int kKeyPack = env_or("OOB_TUNE_KEY_PACK", 1);
-static const int kKeyNbuf = env_or("OOB_TUNE_KEY_NBUF", 1);
 static const int kBatchOverlap = env_or("OOB_TUNE_BATCH_OVERLAP", 0);
 static const int kBatchLanes = env_or("OOB_TUNE_BATCH_LANES", 8);
 static const int kFuseLo = env_or("OOB_TUNE_FUSE_LO", 0);
@@ -1456,36 +1455,41 @@ static int waves_for(const Shape &sh, int S, int fam, const SplitPlan &sp, Split
     return imin(kKeyWaves, most);
 }
 
-template <int NTAB, int NA>
+// LDS of a keyed launch: the staged records of one split point (static, by capacity class NTAB of the
+// tables staged) and the key table of the launch's own target count (dynamic).  A launch whose
+// workgroups fit a compute unit's LDS four times runs the variant without records in flight
+// (128 registers, four waves per SIMD), else the one with them (three waves per SIMD either way).
+static const int kKeyClasses[] = {24, 32, 48, 64, 96, 136};
+static int key_class(int ntab, int na) {
+    (void)na;
+    for (int c = 0; c < 6; ++c)
+        if (ntab <= kKeyClasses[c]) return c;
+    return -1;
+}
+static size_t key_table_bytes(int na) { return (size_t)(na + 2) * 64 * sizeof(unsigned long long); }
+template <int NTAB>
 static void launch_split_key_c(const Tables &t, int S, int fam, const SplitPlan &sp, int NT, int NAall,
                                SplitRange sr, hipStream_t st) {
     const dim3 grid(seg_count(t.sh.L, S), sr.scount, sp.groups);
     const int waves = waves_for(t.sh, S, fam, sp, sr);
-    constexpr int fb = NTAB <= 64 ? 0 : kFillBatch; // four workgroups of the classes up to 64 tables fit a compute unit's LDS
-    if (kKeyNbuf == 2)
-        hipLaunchKernelGGL((k_split_key<NTAB, NA, 2, kFillBatch>), grid, dim3(waves * 64), 0, st, t, S, fam, NT, NAall,
+    const size_t dyn = key_table_bytes(sp.na), total = (size_t)NTAB * 8 * 24 + dyn;
+    if (4 * total <= kLdsLimit)
+        hipLaunchKernelGGL((k_split_key<NTAB, 1, 0>), grid, dim3(waves * 64), dyn, st, t, S, fam, NT, NAall,
                            sp.pc, sr.s0, sr.sstep);
     else
-        hipLaunchKernelGGL((k_split_key<NTAB, NA, 1, fb>), grid, dim3(waves * 64), 0, st, t, S, fam, NT, NAall,
+        hipLaunchKernelGGL((k_split_key<NTAB, 1, kFillBatch>), grid, dim3(waves * 64), dyn, st, t, S, fam, NT, NAall,
                            sp.pc, sr.s0, sr.sstep);
-}
-// LDS capacity classes of k_split_key: (tables staged, targets); the smallest that fits is used.
-static const int kKeyClasses[][2] = {{24, 16}, {48, 40}, {64, 48}, {96, 48}, {96, 64}, {136, 64}};
-static int key_class(int ntab, int na) {
-    for (int c = 0; c < 6; ++c)
-        if (ntab <= kKeyClasses[c][0] && na <= kKeyClasses[c][1]) return c;
-    return -1;
 }
 static void launch_split_key(const Tables &t, int S, int fam, const SplitPlan &sp, int NT, int NAall,
                              SplitRange sr, hipStream_t st) {
     if (sr.scount < 1) return;
     switch (sp.cls) {
-    case 0: launch_split_key_c<24, 16>(t, S, fam, sp, NT, NAall, sr, st); break;
-    case 1: launch_split_key_c<48, 40>(t, S, fam, sp, NT, NAall, sr, st); break;
-    case 2: launch_split_key_c<64, 48>(t, S, fam, sp, NT, NAall, sr, st); break;
-    case 3: launch_split_key_c<96, 48>(t, S, fam, sp, NT, NAall, sr, st); break;
-    case 4: launch_split_key_c<96, 64>(t, S, fam, sp, NT, NAall, sr, st); break;
-    default: launch_split_key_c<136, 64>(t, S, fam, sp, NT, NAall, sr, st); break;
+    case 0: launch_split_key_c<24>(t, S, fam, sp, NT, NAall, sr, st); break;
+    case 1: launch_split_key_c<32>(t, S, fam, sp, NT, NAall, sr, st); break;
+    case 2: launch_split_key_c<48>(t, S, fam, sp, NT, NAall, sr, st); break;
+    case 3: launch_split_key_c<64>(t, S, fam, sp, NT, NAall, sr, st); break;
+    case 4: launch_split_key_c<96>(t, S, fam, sp, NT, NAall, sr, st); break;
+    default: launch_split_key_c<136>(t, S, fam, sp, NT, NAall, sr, st); break;
     }
 }
 
