@@ -463,7 +463,7 @@ __host__ __device__ __forceinline__ int role_cost(int y0, int y1, int q0, int q1
 // at the middle levels, 10 % slower launches where the machine is not full, 2 % for the call; choosing
 // per launch was slower than either (workgroups of both register footprints then share compute units).
 template <int NTAB, int NBUF, int FB>
-__global__ void __launch_bounds__(256, FB ? 1 : 4) k_split_key(Tables t, int Sp, int fam, int NT, int NAall, int halves,
+__global__ void __launch_bounds__(256, FB ? 1 : 4) k_split_key(Tables t, int Sp, int fam0, int gz, int NT, int NAall, int halves,
                                                    int s0, int sstep) {
     // Static, separate arrays: the compiler then knows that the key merges (atomics on s_acc) never
     // touch the staged records, and keeps the reads of the next step ahead of them.
@@ -478,10 +478,13 @@ __global__ void __launch_bounds__(256, FB ? 1 : 4) k_split_key(Tables t, int Sp,
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
     const int2 sg = t.seg_tab[(long long)(Sp - 2) * t.seg_stride + ((halves & 8) ? xcd_chunked(blockIdx.x, gridDim.x) : (int)blockIdx.x)]; // x: tile index, y: ub | vb << 8 | seg << 16
     const int tile = sg.x, ub = sg.y & 255, vb = (sg.y >> 8) & 255, seg = sg.y >> 16;
+    // the first gz target groups of the launch belong to family fam0, the rest (a launch that covers
+    // both families of a low level) to the whole-node family
+    const int fam = (int)blockIdx.z < gz ? fam0 : 1, zg = (int)blockIdx.z < gz ? (int)blockIdx.z : (int)blockIdx.z - gz;
     const int fam_base = fam ? M - 2 : -1;
     int t_lo, t_hi;
     target_units(fam, Sp, M, n_max, &t_lo, &t_hi);
-    const int a_g0 = t_lo + blockIdx.z * kKeyTargets, a_g1 = imin(t_hi, a_g0 + kKeyTargets - 1);
+    const int a_g0 = t_lo + zg * kKeyTargets, a_g1 = imin(t_hi, a_g0 + kKeyTargets - 1);
     const int na = a_g1 - a_g0 + 1;
     int A_lo, A_hi, B_lo, B_hi;
     child_units(fam, s, M, n_max, &A_lo, &A_hi);
@@ -1467,30 +1470,50 @@ static int key_class(int ntab, int na) {
     return -1;
 }
 static size_t key_table_bytes(int na) { return (size_t)(na + 2) * 64 * sizeof(unsigned long long); }
+// A keyed launch: the target groups of family `fam` (gz of them) and, in a launch for both families
+// of a low level, those of the whole-node family behind them (`groups` in all).
+struct KeyLaunch { int fam, gz, groups, cls, na, pc, waves; };
 template <int NTAB>
-static void launch_split_key_c(const Tables &t, int S, int fam, const SplitPlan &sp, int NT, int NAall,
-                               SplitRange sr, hipStream_t st) {
-    const dim3 grid(seg_count(t.sh.L, S), sr.scount, sp.groups);
-    const int waves = waves_for(t.sh, S, fam, sp, sr);
-    const size_t dyn = key_table_bytes(sp.na), total = (size_t)NTAB * 8 * 24 + dyn;
+static void launch_split_key_c(const Tables &t, int S, const KeyLaunch &kl, int NT, int NAall, SplitRange sr,
+                               hipStream_t st) {
+    const dim3 grid(seg_count(t.sh.L, S), sr.scount, kl.groups);
+    const size_t dyn = key_table_bytes(kl.na), total = (size_t)NTAB * 8 * 24 + dyn;
     if (4 * total <= kLdsLimit)
-        hipLaunchKernelGGL((k_split_key<NTAB, 1, 0>), grid, dim3(waves * 64), dyn, st, t, S, fam, NT, NAall,
-                           sp.pc, sr.s0, sr.sstep);
+        hipLaunchKernelGGL((k_split_key<NTAB, 1, 0>), grid, dim3(kl.waves * 64), dyn, st, t, S, kl.fam, kl.gz, NT, NAall,
+                           kl.pc, sr.s0, sr.sstep);
     else
-        hipLaunchKernelGGL((k_split_key<NTAB, 1, kFillBatch>), grid, dim3(waves * 64), dyn, st, t, S, fam, NT, NAall,
-                           sp.pc, sr.s0, sr.sstep);
+        hipLaunchKernelGGL((k_split_key<NTAB, 1, kFillBatch>), grid, dim3(kl.waves * 64), dyn, st, t, S, kl.fam, kl.gz, NT,
+                           NAall, kl.pc, sr.s0, sr.sstep);
 }
-static void launch_split_key(const Tables &t, int S, int fam, const SplitPlan &sp, int NT, int NAall,
-                             SplitRange sr, hipStream_t st) {
+static void launch_split_key(const Tables &t, int S, const KeyLaunch &kl, int NT, int NAall, SplitRange sr,
+                             hipStream_t st) {
     if (sr.scount < 1) return;
-    switch (sp.cls) {
-    case 0: launch_split_key_c<24>(t, S, fam, sp, NT, NAall, sr, st); break;
-    case 1: launch_split_key_c<32>(t, S, fam, sp, NT, NAall, sr, st); break;
-    case 2: launch_split_key_c<48>(t, S, fam, sp, NT, NAall, sr, st); break;
-    case 3: launch_split_key_c<64>(t, S, fam, sp, NT, NAall, sr, st); break;
-    case 4: launch_split_key_c<96>(t, S, fam, sp, NT, NAall, sr, st); break;
-    default: launch_split_key_c<136>(t, S, fam, sp, NT, NAall, sr, st); break;
+    switch (kl.cls) {
+    case 0: launch_split_key_c<24>(t, S, kl, NT, NAall, sr, st); break;
+    case 1: launch_split_key_c<32>(t, S, kl, NT, NAall, sr, st); break;
+    case 2: launch_split_key_c<48>(t, S, kl, NT, NAall, sr, st); break;
+    case 3: launch_split_key_c<64>(t, S, kl, NT, NAall, sr, st); break;
+    case 4: launch_split_key_c<96>(t, S, kl, NT, NAall, sr, st); break;
+    default: launch_split_key_c<136>(t, S, kl, NT, NAall, sr, st); break;
     }
+}
+// The keyed launches of the splits `sr` of a level: one per family, or one for both.
+static void launch_split_keys(const Tables &t, int S, const bool *have, const SplitPlan *kp, int NT, int NAall,
+                              SplitRange sr, hipStream_t st) {
+    if (sr.scount < 1) return;
+    KeyLaunch kl[2];
+    for (int fam = 0; fam < 2; ++fam)
+        if (have[fam])
+            kl[fam] = KeyLaunch{fam, kp[fam].groups, kp[fam].groups, kp[fam].cls, kp[fam].na, kp[fam].pc,
+                                waves_for(t.sh, S, fam, kp[fam], sr)};
+    if (have[0] && have[1]) {
+        const KeyLaunch both{0, kl[0].groups, kl[0].groups + kl[1].groups, imax(kl[0].cls, kl[1].cls),
+                             imax(kl[0].na, kl[1].na), kl[0].pc, imax(kl[0].waves, kl[1].waves)};
+        launch_split_key(t, S, both, NT, NAall, sr, st);
+        return;
+    }
+    for (int fam = 0; fam < 2; ++fam)
+        if (have[fam]) launch_split_key(t, S, kl[fam], NT, NAall, sr, st);
 }
 
 template <int PC>
@@ -1583,18 +1606,19 @@ static int enqueue_job(oob_plan *h, int ln, bool want_overlap, const oob_profile
         if (inner) {
             hipStream_t sx = (S & 1) ? lane.aux2 : lane.aux;
             OOB_HIP_CHECK(hipStreamWaitEvent(sx, lane.ev_level[2 * (S - 2)], 0)); // select of level S'-2
-            for (int fam = 0; fam < 2; ++fam)
-                if (have[fam]) launch_split_key(tl, S, fam, kp[fam], NT, NAall, SplitRange{2, 1, S - 3}, sx);
+            launch_split_keys(tl, S, have, kp, NT, NAall, SplitRange{2, 1, S - 3}, sx);
             OOB_HIP_CHECK(hipEventRecord(lane.ev_level[2 * S + 1], sx));
         }
         // the outer splits: launches of their own, or evaluated by the select kernel itself
         const bool fuse = !force_plain && (S <= kFuseLo || S >= kFuseHi);
-        for (int fam = 0; fam < 2; ++fam) {
-            if (!have[fam]) continue;
+        if (!force_plain) {
             SplitRange sr = inner ? SplitRange{1, S - 2, 2} : SplitRange{1, 1, S - 1};
             if (fuse) sr = inner ? SplitRange{1, 1, 0} : SplitRange{2, 1, S - 3};
-            if (!force_plain) launch_split_key(tl, S, fam, kp[fam], NT, NAall, sr, st);
-            else if (sp[fam].pc == 4) launch_split<4>(tl, S, fam, sp[fam], NT, NAall, st);
+            launch_split_keys(tl, S, have, kp, NT, NAall, sr, st);
+        }
+        for (int fam = 0; fam < 2 && force_plain; ++fam) {
+            if (!have[fam]) continue;
+            if (sp[fam].pc == 4) launch_split<4>(tl, S, fam, sp[fam], NT, NAall, st);
             else if (sp[fam].pc == 2) launch_split<2>(tl, S, fam, sp[fam], NT, NAall, st);
             else launch_split<1>(tl, S, fam, sp[fam], NT, NAall, st);
         }
