@@ -379,7 +379,8 @@ __global__ void __launch_bounds__(512) k_split(Tables t, int Sp, int fam, int NT
 // and yields, per (s, state), the smallest total and the first k reaching it at once.
 // ---------------------------------------------------------------------------------------
 constexpr int kKeyTargets = 64;
-constexpr int kFillBatch = 3; // records a thread has in flight while staging (the variant with FB = 0 has none)
+constexpr int kFillBatch = 3;      // records a thread has in flight while staging: three waves per SIMD
+constexpr int kFillBatchSmall = 2; // the same for launches whose LDS admits four workgroups per compute unit
 
 // Workgroup x of a launch of n -> position in the task list (OOB_TUNE_XCD=1 only).  The hardware
 // deals consecutive workgroups out to the 8 XCDs in turn; this hands every XCD one contiguous
@@ -457,13 +458,13 @@ __host__ __device__ __forceinline__ int role_cost(int y0, int y1, int q0, int q1
 // One split point per pass, one LDS buffer: while the waves work on k, every thread has the
 // records of k+1 in flight from HBM/L2 and drops them into the buffer between the two barriers
 // of the pass (NBUF = 2: two buffers and one barrier; needs more LDS, measured slower).
-// FB = kFillBatch: 163 vector registers, three waves per SIMD.  FB = 0: nothing in flight, the records of
-// k+1 are fetched between the barriers; that fits 128 registers, and the classes whose LDS admits a
-// fourth workgroup per compute unit use it and run four waves per SIMD.  Measured: 3-8 % per launch
-// at the middle levels, 10 % slower launches where the machine is not full, 2 % for the call; choosing
-// per launch was slower than either (workgroups of both register footprints then share compute units).
+// FB = kFillBatch: 167 vector registers, three waves per SIMD.  FB = kFillBatchSmall: launch bounds hold
+// the kernel to 128 registers (four waves per SIMD, for launches whose LDS admits a fourth workgroup
+// per compute unit) at the price of 24 bytes of spills per lane in the per-pass code, none in the step
+// loop; records beyond FB per thread are fetched between the barriers.  Measured on the headline
+// workload: nothing in flight 9.78 ms, one record 9.84 ms, two 9.64 ms for the levels.
 template <int NTAB, int NBUF, int FB>
-__global__ void __launch_bounds__(256, FB ? 1 : 4) k_split_key(Tables t, int Sp, int fam0, int gz, int NT, int NAall, int halves,
+__global__ void __launch_bounds__(256, FB == kFillBatch ? 1 : 4) k_split_key(Tables t, int Sp, int fam0, int gz, int NT, int NAall, int halves,
                                                    int s0, int sstep) {
     // Static, separate arrays: the compiler then knows that the key merges (atomics on s_acc) never
     // touch the staged records, and keeps the reads of the next step ahead of them.
@@ -1460,8 +1461,8 @@ static int waves_for(const Shape &sh, int S, int fam, const SplitPlan &sp, Split
 
 // LDS of a keyed launch: the staged records of one split point (static, by capacity class NTAB of the
 // tables staged) and the key table of the launch's own target count (dynamic).  A launch whose
-// workgroups fit a compute unit's LDS four times runs the variant without records in flight
-// (128 registers, four waves per SIMD), else the one with them (three waves per SIMD either way).
+// workgroups fit a compute unit's LDS four times runs the variant held to 128 registers (four
+// waves per SIMD), else the one with three records in flight (three waves per SIMD either way).
 static const int kKeyClasses[] = {24, 32, 48, 64, 96, 136};
 static int key_class(int ntab, int na) {
     (void)na;
@@ -1479,7 +1480,7 @@ static void launch_split_key_c(const Tables &t, int S, const KeyLaunch &kl, int 
     const dim3 grid(seg_count(t.sh.L, S), sr.scount, kl.groups);
     const size_t dyn = key_table_bytes(kl.na), total = (size_t)NTAB * 8 * 24 + dyn;
     if (4 * total <= kLdsLimit)
-        hipLaunchKernelGGL((k_split_key<NTAB, 1, 0>), grid, dim3(kl.waves * 64), dyn, st, t, S, kl.fam, kl.gz, NT, NAall,
+        hipLaunchKernelGGL((k_split_key<NTAB, 1, kFillBatchSmall>), grid, dim3(kl.waves * 64), dyn, st, t, S, kl.fam, kl.gz, NT, NAall,
                            kl.pc, sr.s0, sr.sstep);
     else
         hipLaunchKernelGGL((k_split_key<NTAB, 1, kFillBatch>), grid, dim3(kl.waves * 64), dyn, st, t, S, kl.fam, kl.gz, NT,
