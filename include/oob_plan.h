@@ -156,10 +156,19 @@ int oob_plan_destroy(oob_plan *h);
  *   OOB_OPT_ONE_STREAM   1: all levels on the caller's stream (no other stream, no events);
  *                        default 0: the inner splits of consecutive levels run on two streams of the
  *                        library beside the caller's, which carries the outer splits and the selects
+ *   OOB_OPT_SELECT8_FROM value = first level S' whose select kernel works with eight lanes per
+ *                        state (below it: one lane per state); default 82 (the top levels, where
+ *                        the select kernel's own latency is what a level waits for)
+ *   OOB_OPT_FUSE_FROM    value = first level S' whose two outer splits (s = 1 and s = S'-1) are
+ *                        evaluated inside that select kernel instead of by split launches of
+ *                        their own; default 82.  A value of 2 covers every level, one above the
+ *                        stage limit none
  * Returns OOB_EINVAL for an unknown option. */
 #define OOB_OPT_PLAIN_SPLIT 1
 #define OOB_OPT_XCD_ORDER 2
 #define OOB_OPT_ONE_STREAM 3
+#define OOB_OPT_SELECT8_FROM 4
+#define OOB_OPT_FUSE_FROM 5
 int oob_plan_set_option(oob_plan *h, int option, int value);
 
 /* Measurement hook.  After oob_plan_level_timing(h, 1) every oob_plan_templates call records

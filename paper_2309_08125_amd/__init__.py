@@ -4,6 +4,7 @@ from .binding import (  # noqa: F401
     DeviceProfile, DeviceTemplates, Planner, load, oob_plan_create, oob_plan_destroy,
     oob_plan_max_stages, oob_plan_templates, oob_plan_templates_batch, oob_plan_workspace_size,
     template_stages, OOB_OPT_PLAIN_SPLIT, OOB_OPT_XCD_ORDER, OOB_OPT_ONE_STREAM,
+    OOB_OPT_SELECT8_FROM, OOB_OPT_FUSE_FROM,
     EXACT_SYMBOLS, ExactMinimum, oob_exact_minimum, oob_exact_workspace_size,
     OOB_EXACT_LIMIT_CAN_BIND, oob_exact_minimum_staged, oob_exact_staged_workspace_size,
     DIST_SYMBOLS, Distributor, oob_dist_choose, oob_dist_solve,

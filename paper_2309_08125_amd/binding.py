@@ -23,6 +23,7 @@ SYMBOLS = ["oob_plan_max_stages", "oob_plan_workspace_size", "oob_plan_create",
            "oob_plan_level_timing", "oob_plan_last_level_ms", "oob_plan_export_flags", "oob_plan_valu_peak", "oob_plan_valu_peak_f64",
            "oob_plan_set_option"]
 OOB_OPT_PLAIN_SPLIT, OOB_OPT_XCD_ORDER, OOB_OPT_ONE_STREAM = 1, 2, 3
+OOB_OPT_SELECT8_FROM, OOB_OPT_FUSE_FROM = 4, 5
 INST_SYMBOLS = ["oob_inst_workspace_size", "oob_inst_count", "oob_inst_enumerate", "oob_inst_keep_wide_table",
                 "oob_inst_enumerate_static"]
 OOB_INST_STATIC_BYTES = 4 << 20

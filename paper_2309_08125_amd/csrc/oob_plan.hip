@@ -1243,9 +1243,11 @@ static const int kKeyHalves = env_or("OOB_TUNE_KEY_HALVES", 2);
 static const int kKeyPack = env_or("OOB_TUNE_KEY_PACK", 1);
 static const int kBatchOverlap = env_or("OOB_TUNE_BATCH_OVERLAP", 0);
 static const int kBatchLanes = env_or("OOB_TUNE_BATCH_LANES", 8);
-static const int kFuseLo = env_or("OOB_TUNE_FUSE_LO", 0);
-static const int kFuseHi = env_or("OOB_TUNE_FUSE_HI", 82);
-static const int kSel8From = env_or("OOB_TUNE_SEL8_FROM", 82);
+// From this level on the select kernel works with eight lanes per state and evaluates the two outer
+// splits itself (below it the machine is full of split workgroups, and eight times the waves of
+// the plain select only wait longer for a place); measured on the headline workload, where 78-88 gave
+// the same time.  Handle options move both thresholds.
+constexpr int kSelect8From = 82, kFuseFrom = 82;
 bool plan_split_key(const Shape &sh, int Sp, int fam, int xcd_order, SplitPlan *p) {
     int t_lo, t_hi;
     target_units(fam, Sp, sh.M, sh.n_max, &t_lo, &t_hi);
@@ -1337,7 +1339,7 @@ struct oob_plan {
     bool have_last;
     hipEvent_t ev_begin, ev_end; // optional: recorded around the level launches
     bool timed;
-    int opt_plain, opt_xcd, opt_one_stream; // oob_plan_set_option
+    int opt_plain, opt_xcd, opt_one_stream, opt_select8_from, opt_fuse_from; // oob_plan_set_option
 };
 
 #define OOB_HIP_CHECK(expr)                                                                   \
@@ -1380,6 +1382,7 @@ extern "C" int oob_plan_create(oob_plan **h, int max_L, int max_nodes, int max_g
     p->lanes = (int)std::min<size_t>(kMaxLanes, std::max<size_t>(1, workspace_bytes / p->lane_bytes));
     p->ev_fork = nullptr; p->last_lane = 0;
     p->opt_plain = p->opt_xcd = p->opt_one_stream = 0;
+    p->opt_select8_from = kSelect8From; p->opt_fuse_from = kFuseFrom;
     *h = p;
     return OOB_OK;
 }
@@ -1611,7 +1614,7 @@ static int enqueue_job(oob_plan *h, int ln, bool want_overlap, const oob_profile
             OOB_HIP_CHECK(hipEventRecord(lane.ev_level[2 * S + 1], sx));
         }
         // the outer splits: launches of their own, or evaluated by the select kernel itself
-        const bool fuse = !force_plain && (S <= kFuseLo || S >= kFuseHi);
+        const bool fuse = !force_plain && S >= h->opt_fuse_from;
         if (!force_plain) {
             SplitRange sr = inner ? SplitRange{1, S - 2, 2} : SplitRange{1, 1, S - 1};
             if (fuse) sr = inner ? SplitRange{1, 1, 0} : SplitRange{2, 1, S - 3};
@@ -1624,7 +1627,7 @@ static int enqueue_job(oob_plan *h, int ln, bool want_overlap, const oob_profile
             else launch_split<1>(tl, S, fam, sp[fam], NT, NAall, st);
         }
         if (inner) OOB_HIP_CHECK(hipStreamWaitEvent(st, lane.ev_level[2 * S + 1], 0));
-        if (force_plain || (!fuse && S < kSel8From)) hipLaunchKernelGGL(k_select, dim3(NT, NAall), dim3(64), 0, st, tl, S, NT, NAall);
+        if (force_plain || (!fuse && S < h->opt_select8_from)) hipLaunchKernelGGL(k_select, dim3(NT, NAall), dim3(64), 0, st, tl, S, NT, NAall);
         else if (fuse) hipLaunchKernelGGL(k_select8<true>, dim3(NT, NAall, 8), dim3(64), 0, st, tl, S, NT, NAall);
         else hipLaunchKernelGGL(k_select8<false>, dim3(NT, NAall, 8), dim3(64), 0, st, tl, S, NT, NAall);
         if (overlap) OOB_HIP_CHECK(hipEventRecord(lane.ev_level[2 * S], st));
@@ -1692,6 +1695,8 @@ extern "C" int oob_plan_set_option(oob_plan *h, int option, int value) {
     case OOB_OPT_PLAIN_SPLIT: h->opt_plain = value != 0; break;
     case OOB_OPT_XCD_ORDER: h->opt_xcd = value != 0; break;
     case OOB_OPT_ONE_STREAM: h->opt_one_stream = value != 0; break;
+    case OOB_OPT_SELECT8_FROM: h->opt_select8_from = value; break;
+    case OOB_OPT_FUSE_FROM: h->opt_fuse_from = value; break;
     default: return OOB_EINVAL;
     }
     return OOB_OK;

@@ -321,6 +321,29 @@ def test_xcd_chunked_task_order(P):
         planner.close()
 
 
+def test_select_with_eight_lanes_per_state(P):
+    """The select kernel of the top levels (eight lanes per state), forced onto every level of
+    shapes the oracle finishes in seconds: once reading the keys of all splits, once evaluating
+    the two outer splits of every level itself (both device-set families, both N_b modes, a
+    profile whose totals are too large for keys, so that its one-lane fallback runs too)."""
+    seen = set()
+    for fuse_from in (1 << 20, 2):
+        for inp in (inputs.config(1), inputs.config(2),
+                    inputs.random_small(3, 37, 3, 1, 5, 9, f=1, tight_mem=True),
+                    inputs.random_small(5, 60, 2, 1, 6, 11, f=2),
+                    inputs.random_small(4, 30, 3, 2, 30, 0, f=2),
+                    inputs.random_small(7, 12, 8, 1, 3, 5),
+                    inputs.random_small(21, 9, 2, 1, 3, 7, t_lo=(1 << 38), t_hi=(1 << 39))):
+            print("select8", fuse_from, inp.name, inp.L, flush=True)
+            planner = P.Planner(inp.L, inp.n_max, inp.gpus_per_node)
+            planner.set_option(P.OOB_OPT_SELECT8_FROM, 2)
+            planner.set_option(P.OOB_OPT_FUSE_FROM, fuse_from)
+            full_check(P, planner, inp)
+            seen.add(tuple(planner.flags()[:2]))
+            planner.close()
+    assert seen == {(0, 0), (1, 0)}, "keys and the evaluation without keys must both have run"
+
+
 def test_two_calls_same_answer(P):
     """Determinism: the same job twice on one handle gives identical tables."""
     inp = inputs.config(2)
