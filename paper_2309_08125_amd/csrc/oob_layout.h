@@ -8,11 +8,16 @@
 // and fam_base = M-2 across nodes (units = nodes).
 //
 // Storage.  Every valid (S', delta) owns one table: the (u, v) plane in ABSOLUTE layer
-// coordinates, 0 <= u <= v <= L, cut into 8 x 8 blocks (block row u/8, block column v/8, only
-// block columns >= block rows are kept), 64 records per block, row-major inside the block.
+// coordinates, 0 <= u <= v <= L, cut into 8 x 8 blocks: block row u/8, block column (v + c)/8
+// with the column shift c = col_shift(L), which puts v = L into the last column of its block
+// (only block columns >= block rows are kept), 64 records per block, row-major inside the block.
+// The shift matters because the states that end at the last layers are the ones every level needs
+// and a ragged last block column would leave most of its lanes idle; the ragged column is the
+// first one instead (v < 0, no states).  Rows need no shift: u = 0 already starts a block.
 // Absolute coordinates make the three operands of a split at k line up on the same block
 // grid: left child at (u, k), right child at (k, v), target at (u, v) -- the layout of a
-// blocked matrix product.  Entries that are not states (v - u < S', u >= L, v > L) inside a
+// blocked matrix product (a split point k is column k + c of the left child's table and row k of
+// the right child's).  Entries that are not states (v - u < S', u >= L, v < 0) inside a
 // block that holds at least one state carry the "no such state" value, so inner loops need
 // no masks; blocks without any state are never written and never read.
 #pragma once
@@ -92,56 +97,68 @@ __host__ __device__ inline int key_bits(int L) {
 
 // ---- blocked (u, v) plane ----------------------------------------------------------------
 __host__ __device__ inline int nblocks_of(int L) { return L / 8 + 1; } // v runs 0..L
+__host__ __device__ inline int col_shift(int L) { return (8 - ((L + 1) & 7)) & 7; }
 __host__ __device__ inline int tri_blocks(int NB) { return NB * (NB + 1) / 2; }
 __host__ __device__ inline int tri_index(int ub, int vb, int NB) {
     return ub * NB - ub * (ub - 1) / 2 + (vb - ub);
 }
+// Record of (u, v) inside a table (c = col_shift(L)).
+__host__ __device__ inline int rec_off(int u, int v, int c, int NB) {
+    return tri_index(u >> 3, (v + c) >> 3, NB) * 64 + ((u & 7) << 3) + ((v + c) & 7);
+}
 
-// Blocks of level S' that hold at least one state: (ub, vb = ub + d) with 8d + 7 >= S' and
+// Blocks of level S' that hold at least one state: (ub, vb = ub + d) with 8 d + 7 - c >= S' and
 // 8 ub + S' <= L.  They are enumerated by decreasing d (the blocks far from the diagonal have
 // the longest split ranges, so the heaviest workgroups start first).
-__host__ __device__ inline int tile_dmin(int S) { return S / 8; } // = ceil((S' - 7) / 8)
+__host__ __device__ inline int tile_dmin(int L, int S) { return (S + col_shift(L)) / 8; } // = ceil((S' + c - 7) / 8)
 __host__ __device__ inline int tile_count(int L, int S) {
     const int NB = nblocks_of(L), ubmax = (L - S) / 8;
     int c = 0;
-    for (int d = NB - 1; d >= tile_dmin(S); --d) c += imin(ubmax, NB - 1 - d) + 1;
+    for (int d = NB - 1; d >= tile_dmin(L, S); --d) c += imin(ubmax, NB - 1 - d) + 1;
     return c;
 }
 __host__ __device__ inline void tile_decode(int L, int S, int t, int *ub, int *vb) {
     const int NB = nblocks_of(L), ubmax = (L - S) / 8;
-    for (int d = NB - 1; d >= tile_dmin(S); --d) {
+    for (int d = NB - 1; d >= tile_dmin(L, S); --d) {
         const int c = imin(ubmax, NB - 1 - d) + 1;
         if (t < c) { *ub = t; *vb = t + d; return; }
         t -= c;
     }
     *ub = 0; *vb = 0;
 }
+// Last layer position of block column vb (the last block column ends at L exactly).
+__host__ __device__ inline int tile_vmax(int L, int vb) { return vb * 8 + 7 - col_shift(L); }
 
-// Split points k of a block of the plane at level S': kmin = 8 ub + s .. kmax = vmax - (S' - s),
-// vmax = min(8 vb + 7, L): their number does not depend on s.  The keyed split kernel cuts
+// Split points k of a block of the plane at level S': kmin = 8 ub + s .. kmax = vmax - (S' - s):
+// their number does not depend on s.  The keyed split kernel cuts
 // this range into segments of kSegK consecutive k, one workgroup each.
 constexpr int kSegK = 8;
 __host__ __device__ inline int tile_krange(int L, int S, int ub, int vb) {
-    return imin(vb * 8 + 7, L) - ub * 8 - S + 1;
+    return tile_vmax(L, vb) - ub * 8 - S + 1;
 }
 __host__ __device__ inline int seg_count(int L, int S) { // over all blocks of the level
     const int NB = nblocks_of(L), ubmax = (L - S) / 8;
     int c = 0;
-    for (int d = NB - 1; d >= tile_dmin(S); --d)
+    for (int d = NB - 1; d >= tile_dmin(L, S); --d)
         for (int ub = 0; ub <= imin(ubmax, NB - 1 - d); ++ub) c += cdiv(tile_krange(L, S, ub, ub + d), kSegK);
     return c;
 }
-// g-th segment of the level -> block (ub, vb), its index t in tile order, segment j of it.
-__host__ __device__ inline void seg_decode(int L, int S, int g, int *t, int *ub, int *vb, int *j) {
+// Upper bounds that grow with L, for sizing a workspace that serves every L up to a maximum: the
+// counts of the same plane without the column shift (a shifted plane never has more blocks of a
+// level, nor more segments at S' = 2, where a level's task list is longest).
+__host__ __device__ inline int tile_count_bound(int L, int S) {
     const int NB = nblocks_of(L), ubmax = (L - S) / 8;
-    int tt = 0;
-    for (int d = NB - 1; d >= tile_dmin(S); --d)
-        for (int u = 0; u <= imin(ubmax, NB - 1 - d); ++u, ++tt) {
-            const int c = cdiv(tile_krange(L, S, u, u + d), kSegK);
-            if (g < c) { *t = tt; *ub = u; *vb = u + d; *j = g; return; }
-            g -= c;
-        }
-    *t = 0; *ub = 0; *vb = 0; *j = 0;
+    int c = 0;
+    for (int d = NB - 1; d >= S / 8; --d) c += imin(ubmax, NB - 1 - d) + 1;
+    return c;
+}
+__host__ __device__ inline int seg_count_bound(int L) {
+    const int NB = nblocks_of(L), ubmax = (L - 2) / 8;
+    int c = 0;
+    for (int d = NB - 1; d >= 0; --d)
+        for (int ub = 0; ub <= imin(ubmax, NB - 1 - d); ++ub)
+            c += cdiv(imin((ub + d) * 8 + 7, L) - ub * 8 - 2 + 1, kSegK);
+    return c;
 }
 
 } // namespace oob

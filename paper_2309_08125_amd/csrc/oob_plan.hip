@@ -56,6 +56,7 @@ struct Rec { double T, T1, tmax, T3; };        // 32 bytes, one per (table, u, v
 struct Tables {
     Shape sh;
     int NB;               // blocks per side of the (u, v) plane
+    int coff;             // column shift of the plane: v sits in block column (v + coff) / 8
     int tab_recs;         // records per table = tri_blocks(NB) * 64
     long long *lvl_tab;   // [Smax+2] index of the first table of level S'
     long long *PT;        // [(M+1)*(L+1)] prefix sums of F+B for d GPUs (row d)
@@ -77,7 +78,12 @@ struct Tables {
 
 __device__ __forceinline__ long long rec_index(const Tables &t, int S, int delta, int u, int v) {
     const long long tab = t.lvl_tab[S] + (delta - dlo_of(S, t.sh.M));
-    return tab * t.tab_recs + (long long)tri_index(u >> 3, v >> 3, t.NB) * 64 + ((u & 7) << 3) + (v & 7);
+    return tab * t.tab_recs + rec_off(u, v, t.coff, t.NB);
+}
+// First record of block (ub, vb) of that table.
+__device__ __forceinline__ long long rec_block(const Tables &t, int S, int delta, int ub, int vb) {
+    const long long tab = t.lvl_tab[S] + (delta - dlo_of(S, t.sh.M));
+    return tab * t.tab_recs + (long long)tri_index(ub, vb, t.NB) * 64;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -218,9 +224,9 @@ __global__ void __launch_bounds__(64) k_level1(Tables t, const long long *X) {
     const int L = t.sh.L, M = t.sh.M;
     int ub, vb;
     tile_decode(L, 1, blockIdx.x, &ub, &vb);
-    const int delta = blockIdx.y, u = ub * 8 + (threadIdx.x >> 3), v = vb * 8 + (threadIdx.x & 7);
+    const int delta = blockIdx.y, u = ub * 8 + (threadIdx.x >> 3), v = vb * 8 + (threadIdx.x & 7) - t.coff;
     Rec r = {kNone, kNone, 0.0, 0.0};
-    if (u < L && v <= L && v - u >= 1) {
+    if (u < L && v <= L && v - u >= 1) { // (v < 0 in the first block column: no state)
         const int d = delta < M - 1 ? delta + 1 : M;
         long long st;
         if (stage_time(t, X, u, v, d, &st)) {
@@ -229,7 +235,7 @@ __global__ void __launch_bounds__(64) k_level1(Tables t, const long long *X) {
             r.T = r.T1 + (nb - 2.0) * r.tmax + r.T3; // Eq. 2 with S' = 1, k* = 0
         }
     }
-    const long long o = rec_index(t, 1, delta, ub * 8, vb * 8) + threadIdx.x;
+    const long long o = rec_block(t, 1, delta, ub, vb) + threadIdx.x;
     t.rec[o] = r;
     t.kstar[o] = 0;
     t.choice[o] = 0;
@@ -261,7 +267,7 @@ __global__ void __launch_bounds__(512) k_split(Tables t, int Sp, int fam, int NT
     // left / right unit counts some target of this workgroup pairs up
     const int mA0 = imax(A_lo, a_wg0 - B_hi), mA1 = imin(A_hi, a_wg1 - B_lo);
     const int mB0 = imax(B_lo, a_wg0 - A_hi), mB1 = imin(B_hi, a_wg1 - A_lo);
-    const int kmin = ub * 8 + s, kmax = imin(vb * 8 + 7, L) - r;
+    const int kmin = ub * 8 + s, kmax = tile_vmax(L, vb) - r;
     const bool work = mA0 <= mA1 && mB0 <= mB1 && kmin <= kmax;
     const int nA = work ? mA1 - mA0 + 1 : 0, nB = work ? mB1 - mB0 + 1 : 0, dummy = nA + nB;
     constexpr int TS = PC * 8;
@@ -291,8 +297,8 @@ __global__ void __launch_bounds__(512) k_split(Tables t, int Sp, int fam, int NT
                 if (e < fillA) {       // left child (s, u, k, m): row u of block (ub, k/8)
                     const int tab = e / TS, rem = e - tab * TS, u_l = rem / PC, k_l = rem - u_l * PC;
                     const int k = kc + k_l;
-                    const Rec a = t.rec[(tabA + mA0 + tab) * t.tab_recs + (long long)tri_index(ub, k >> 3, t.NB) * 64 +
-                                        (u_l << 3) + (k & 7)];
+                    const Rec a = t.rec[(tabA + mA0 + tab) * t.tab_recs + (long long)tri_index(ub, (k + t.coff) >> 3, t.NB) * 64 +
+                                        (u_l << 3) + ((k + t.coff) & 7)];
                     const int o = (tab * PC + k_l) * 8 + u_l;
                     s_pair[o] = make_double2(a.T + cl * a.tmax, a.T1);
                     s_tm[o] = a.tmax;
@@ -401,7 +407,7 @@ __device__ __forceinline__ int xcd_chunked(int x, int n) {
 // is u for records of the left child and v for records of the right child.
 struct Stage {
     const Rec *recY, *recS; // first record of the table of unit count 0 of the streaming / stationary side
-    int tab_recs, NB, ub, vb, nS, fillY, fill;
+    int tab_recs, NB, coff, ub, vb, nS, fillY, fill;
     int y_is_left;          // 1: left child streams, right child stationary; 0: the other way round
     double cl, cr;
 };
@@ -413,7 +419,8 @@ struct Rec24 { double2 a; double tm; }; // (T, T1), tmax: the 24 bytes of a reco
 // (tables of one side x records of a table x 32 bytes stays below 2^32).
 struct StagePoint { const Rec *py, *ps; int shY, shS; };
 __device__ __forceinline__ StagePoint stage_point(const Stage &g, int k) {
-    const int offL = tri_index(g.ub, k >> 3, g.NB) * 64 + (k & 7), offR = tri_index(k >> 3, g.vb, g.NB) * 64 + ((k & 7) << 3);
+    const int ck = k + g.coff; // column of split point k in the left child's table
+    const int offL = tri_index(g.ub, ck >> 3, g.NB) * 64 + (ck & 7), offR = tri_index(k >> 3, g.vb, g.NB) * 64 + ((k & 7) << 3);
     StagePoint sp;
     sp.py = g.recY + (g.y_is_left ? offL : offR);
     sp.ps = g.recS + (g.y_is_left ? offR : offL);
@@ -493,7 +500,8 @@ __global__ void __launch_bounds__(256, FB == kFillBatch ? 1 : 4) k_split_key(Tab
     const int mA0 = imax(A_lo, a_g0 - B_hi), mA1 = imin(A_hi, a_g1 - B_lo);
     const int mB0 = imax(B_lo, a_g0 - A_hi), mB1 = imin(B_hi, a_g1 - A_lo);
     // this workgroup's segment of the split points of the block
-    const int kmin = ub * 8 + s + seg * kSegK, kmax = imin(imin(vb * 8 + 7, L) - r, kmin + kSegK - 1);
+    const int vmax = tile_vmax(L, vb); // last layer position of the block's columns (never beyond L)
+    const int kmin = ub * 8 + s + seg * kSegK, kmax = imin(vmax - r, kmin + kSegK - 1);
     if (!(mA0 <= mA1 && mB0 <= mB1 && kmin <= kmax)) return; // nothing to merge
     // roles: the left child streams (and the right one is stationary) unless the other way pads less
     const bool y_left = role_cost(mA0, mA1, mB0, mB1, a_g0, a_g1) <= role_cost(mB0, mB1, mA0, mA1, a_g0, a_g1);
@@ -508,7 +516,7 @@ __global__ void __launch_bounds__(256, FB == kFillBatch ? 1 : 4) k_split_key(Tab
     const long long tabA = t.lvl_tab[s] - dlo_of(s, M) + fam_base, tabB = t.lvl_tab[r] - dlo_of(r, M) + fam_base;
     g.recY = t.rec + (y_left ? tabA + mA0 : tabB + mB0) * t.tab_recs;
     g.recS = t.rec + (y_left ? tabB + mB0 : tabA + mA0) * t.tab_recs;
-    g.tab_recs = t.tab_recs; g.NB = t.NB; g.ub = ub; g.vb = vb; g.nS = nS;
+    g.tab_recs = t.tab_recs; g.NB = t.NB; g.coff = t.coff; g.ub = ub; g.vb = vb; g.nS = nS;
     g.fillY = fillY; g.fill = TS; g.y_is_left = y_left;
     g.cl = t.sh.Nb > 0 ? -(double)r : 3.0 * r;
     g.cr = t.sh.Nb > 0 ? 0.0 : 4.0 * s;
@@ -531,7 +539,7 @@ __global__ void __launch_bounds__(256, FB == kFillBatch ? 1 : 4) k_split_key(Tab
     // wave (see below).  Whole items go round robin over the waves; the items left over after the last
     // full round are cut into `parts` pieces of their streaming range so that every wave gets one
     // (halves = 0 disables the cutting).
-    const int chi = imin(vb * 8 + 7, L) - vb * 8; // last column of the block that exists
+    const int chi = 7; // last column of the block that exists (a block column that is not full lacks its FIRST columns)
     for (int k = kmin; k <= kmax; ++k) {
         const int cur = NBUF == 2 ? (k - kmin) & 1 : 0, nxt = NBUF == 2 ? cur ^ 1 : 0;
         const double2 *pair = s_pair[cur];
@@ -545,7 +553,7 @@ __global__ void __launch_bounds__(256, FB == kFillBatch ? 1 : 4) k_split_key(Tab
         // (u + s <= k), and only the columns chi-jc..chi (k <= v - r): near the ends of the block's
         // split range most of the 64 states idle.  Then the wave takes R items at once: the rows (or
         // columns) that matter, padded to a power of two, times R stationary blocks.
-        const int jr = k - (ub * 8 + s), jc = imin(vb * 8 + 7, L) - r - k;
+        const int jr = k - (ub * 8 + s), jc = vmax - r - k;
         const int nr = imin(jr, 7) + 1, nc = imin(jc, chi) + 1;
         const int lr = nr <= 1 ? 0 : nr <= 2 ? 1 : nr <= 4 ? 2 : 3, lc = nc <= 1 ? 0 : nc <= 2 ? 1 : nc <= 4 ? 2 : 3;
         int R, slot, ue, ve; // items side by side, this lane's item among them, its row and column
@@ -669,7 +677,7 @@ __global__ void __launch_bounds__(256, FB == kFillBatch ? 1 : 4) k_split_key(Tab
 // points k and stage the same left-child records.
 __device__ void seg_tab_body(const Tables &t, int S, int by_row) {
     if (S > t.sh.Smax || threadIdx.x != 0) return;
-    const int L = t.sh.L, NB = nblocks_of(L), ubmax = (L - S) / 8, dmin = tile_dmin(S);
+    const int L = t.sh.L, NB = nblocks_of(L), ubmax = (L - S) / 8, dmin = tile_dmin(L, S);
     int2 *out = t.seg_tab + (long long)(S - 2) * t.seg_stride;
     int n = 0;
     if (!by_row) {
@@ -719,7 +727,7 @@ __device__ void select_lane_per_state(const Tables &t, int Sp, int NT, int NAall
     int ub, vb;
     tile_decode(L, Sp, blockIdx.x, &ub, &vb);
     const int aidx = blockIdx.y, delta = dlo_of(Sp, M) + aidx;
-    const int u = ub * 8 + (lane >> 3), v = vb * 8 + (lane & 7);
+    const int u = ub * 8 + (lane >> 3), v = vb * 8 + (lane & 7) - t.coff;
     double best = kNone;
     int bs = 0, bk = 0;
     if (t.flags[0]) { // keys total * 2^kbits + k; consumed keys go back to "no such state"
@@ -775,9 +783,9 @@ __device__ void select_lane_per_state(const Tables &t, int Sp, int NT, int NAall
         const double cl = t.sh.Nb > 0 ? -(double)r : 3.0 * r, cr = t.sh.Nb > 0 ? 0.0 : 4.0 * bs;
         // first m whose candidate equals the minimum; kSelPairs candidates' records in flight at a time
         const long long tabA = (t.lvl_tab[bs] - dlo_of(bs, M) + fam.fam_base) * (long long)t.tab_recs +
-                               (long long)tri_index(u >> 3, bk >> 3, t.NB) * 64 + ((u & 7) << 3) + (bk & 7);
+                               rec_off(u, bk, t.coff, t.NB);
         const long long tabB = (t.lvl_tab[r] - dlo_of(r, M) + fam.fam_base + fam.units) * (long long)t.tab_recs +
-                               (long long)tri_index(bk >> 3, v >> 3, t.NB) * 64 + ((bk & 7) << 3) + (v & 7);
+                               rec_off(bk, v, t.coff, t.NB);
         for (int m0 = mlo; m0 <= mhi && bm == 0; m0 += kSelPairs) {
             Rec ra[kSelPairs], rb[kSelPairs];
 #pragma unroll
@@ -808,7 +816,7 @@ __device__ void select_lane_per_state(const Tables &t, int Sp, int NT, int NAall
             ch = bs | (bk << 10) | (bm << 21);
         }
     }
-    const long long o = rec_index(t, Sp, delta, ub * 8, vb * 8) + lane;
+    const long long o = rec_block(t, Sp, delta, ub, vb) + lane;
     t.rec[o] = out;
     t.kstar[o] = ks;
     t.choice[o] = ch;
@@ -858,7 +866,7 @@ __global__ void __launch_bounds__(64) k_select8(Tables t, int Sp, int NT, int NA
     int ub, vb;
     tile_decode(L, Sp, blockIdx.x, &ub, &vb);
     const int aidx = blockIdx.y, delta = dlo_of(Sp, M) + aidx;
-    const int tl = blockIdx.z * 8 + st, u = ub * 8 + blockIdx.z, v = vb * 8 + st;
+    const int tl = blockIdx.z * 8 + st, u = ub * 8 + blockIdx.z, v = vb * 8 + st - t.coff;
     const bool valid = v <= L && v - u >= Sp;
     const Family fam = family_of(delta, M);
     const bool fixed_nb = t.sh.Nb > 0;
@@ -873,8 +881,8 @@ __global__ void __launch_bounds__(64) k_select8(Tables t, int Sp, int NT, int NA
             int mlo, mhi;
             m_range(fam.fam, fam.units, s, r, M, t.sh.n_max, &mlo, &mhi);
             const double cl = fixed_nb ? -(double)r : 3.0 * r, cr = fixed_nb ? 0.0 : 4.0 * s;
-            const Rec *baseA = t.rec + (t.lvl_tab[s] - dlo_of(s, M) + fam.fam_base) * trecs + ((u & 7) << 3);
-            const Rec *baseB = t.rec + (t.lvl_tab[r] - dlo_of(r, M) + fam.fam_base + fam.units) * trecs + (v & 7);
+            const Rec *baseA = t.rec + (t.lvl_tab[s] - dlo_of(s, M) + fam.fam_base) * trecs;
+            const Rec *baseB = t.rec + (t.lvl_tab[r] - dlo_of(r, M) + fam.fam_base + fam.units) * trecs;
             for (int m = mlo; m <= mhi; ++m)
                 for (int j0 = sub; j0 < nk; j0 += 8 * kSel8Outer) {
                     Rec24 ra[kSel8Outer], rb[kSel8Outer];
@@ -883,8 +891,8 @@ __global__ void __launch_bounds__(64) k_select8(Tables t, int Sp, int NT, int NA
                     for (int q = 0; q < kSel8Outer; ++q) { // past the end: the last candidate again
                         const int k = u + s + imin(j0 + 8 * q, nk - 1);
                         kk[q] = k;
-                        ra[q] = load24(baseA + m * trecs + (long long)tri_index(u >> 3, k >> 3, t.NB) * 64 + (k & 7));
-                        rb[q] = load24(baseB - m * trecs + (long long)tri_index(k >> 3, v >> 3, t.NB) * 64 + ((k & 7) << 3));
+                        ra[q] = load24(baseA + m * trecs + rec_off(u, k, t.coff, t.NB));
+                        rb[q] = load24(baseB - m * trecs + rec_off(k, v, t.coff, t.NB));
                     }
 #pragma unroll
                     for (int q = 0; q < kSel8Outer; ++q) {
@@ -937,9 +945,9 @@ __global__ void __launch_bounds__(64) k_select8(Tables t, int Sp, int NT, int NA
         m_range(fam.fam, fam.units, bs, r, M, t.sh.n_max, &mlo, &mhi);
         const double cl = fixed_nb ? -(double)r : 3.0 * r, cr = fixed_nb ? 0.0 : 4.0 * bs;
         const Rec *baseA = t.rec + (t.lvl_tab[bs] - dlo_of(bs, M) + fam.fam_base) * trecs +
-                           (long long)tri_index(u >> 3, bk >> 3, t.NB) * 64 + ((u & 7) << 3) + (bk & 7);
+                           rec_off(u, bk, t.coff, t.NB);
         const Rec *baseB = t.rec + (t.lvl_tab[r] - dlo_of(r, M) + fam.fam_base + fam.units) * trecs +
-                           (long long)tri_index(bk >> 3, v >> 3, t.NB) * 64 + ((bk & 7) << 3) + (v & 7);
+                           rec_off(bk, v, t.coff, t.NB);
         for (int m0 = mlo + sub; m0 - sub <= mhi && bm == 0; m0 += 8 * kSel8M) {
             Rec24 ra[kSel8M], rb[kSel8M];
 #pragma unroll
@@ -978,7 +986,7 @@ __global__ void __launch_bounds__(64) k_select8(Tables t, int Sp, int NT, int NA
             ch = bs | (bk << 10) | (bm << 21);
         }
     }
-    const long long o = rec_index(t, Sp, delta, ub * 8, vb * 8) + tl;
+    const long long o = rec_block(t, Sp, delta, ub, vb) + tl;
     t.rec[o] = out;
     t.kstar[o] = ks;
     t.choice[o] = ch;
@@ -1048,7 +1056,7 @@ __global__ void __launch_bounds__(128) k_backtrack(Tables t, oob_templates out) 
         int Sq = S, delta = M - 2 + t.sh.n_min + i, u = 0, v = L, pos = p;
         while (Sq > 1) {
             const long long o = (s_lvl[Sq] + (delta - dlo_of(Sq, M))) * t.tab_recs +
-                                (long long)tri_index(u >> 3, v >> 3, t.NB) * 64 + ((u & 7) << 3) + (v & 7);
+                                rec_off(u, v, t.coff, t.NB);
             const int ch = t.choice[o];
             const int s = ch & 1023, k = (ch >> 10) & 2047, m = (ch >> 21) & 1023;
             const Family fam = family_of(delta, M);
@@ -1142,7 +1150,7 @@ long long part_slots(int L, int M, int n_max, int Nb) {
     for (int S = 2; S <= Smax; ++S) {
         const long long nd = dhi_of(S, M, n_max) - dlo_of(S, M) + 1;
         if (nd <= 0) continue;
-        const long long sl = (long long)(S - 1) * nd * tile_count(L, S);
+        const long long sl = (long long)(S - 1) * nd * tile_count_bound(L, S);
         if (sl > best) best = sl;
     }
     return best;
@@ -1173,7 +1181,7 @@ Carve carve(int L, int nodes, int M) {
     c.stack = o;   o = align_up(o + sizeof(int) * ((size_t)nodes * (Smax + 1) * 4 + nodes + 2));
     c.flags = o;   o = align_up(o + sizeof(int) * 64);
     // the task list of a level is longest at S' = 2; every level gets that many entries
-    c.seg_tab = o; o = align_up(o + sizeof(int2) * ((size_t)imax(Smax - 1, 1) * seg_count(L, 2) + 1));
+    c.seg_tab = o; o = align_up(o + sizeof(int2) * ((size_t)imax(Smax - 1, 1) * seg_count_bound(L) + 1));
     c.total = o;
     return c;
 }
@@ -1411,6 +1419,7 @@ static Tables make_tables(const oob_plan *h, int lane, const Shape &sh, int *sta
     char *ws = h->ws + (size_t)lane * h->lane_bytes;
     t.sh = sh;
     t.NB = nblocks_of(sh.L);
+    t.coff = col_shift(sh.L);
     t.tab_recs = tri_blocks(t.NB) * 64;
     t.lvl_tab = (long long *)(ws + h->cv.lvl_tab);
     t.PT = (long long *)(ws + h->cv.PT);
