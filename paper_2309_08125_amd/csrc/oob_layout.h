@@ -130,22 +130,36 @@ __host__ __device__ inline void tile_decode(int L, int S, int t, int *ub, int *v
 __host__ __device__ inline int tile_vmax(int L, int vb) { return vb * 8 + 7 - col_shift(L); }
 
 // Split points k of a block of the plane at level S': kmin = 8 ub + s .. kmax = vmax - (S' - s):
-// their number does not depend on s.  The keyed split kernel cuts
-// this range into segments of kSegK consecutive k, one workgroup each.
-constexpr int kSegK = 8;
+// their number does not depend on s.  The keyed split kernel cuts this range into segments of
+// about seg_target() consecutive k, one workgroup each: as many segments as the range divided by
+// the target gives, rounded to the nearest (at least one), all of the same length up to one
+// split point -- so no workgroup is left with a stub of one or two split points, which would pay
+// the whole set-up and the merge of its keys for next to nothing.
+constexpr int kSegTarget = 8, kSegTargetTop = 4, kSegTopLayers = 20; // measured on the headline workload
+constexpr int kSegMin = 4; // no target below this (sizes the task lists)
+// The top levels (fewer than kSegTopLayers layers of slack, a handful of blocks) cannot fill the
+// machine with workgroups of eight split points: there the target is four.
+__host__ __device__ inline int seg_target(int L, int S) { return L - S < kSegTopLayers ? kSegTargetTop : kSegTarget; }
 __host__ __device__ inline int tile_krange(int L, int S, int ub, int vb) {
     return tile_vmax(L, vb) - ub * 8 - S + 1;
+}
+__host__ __device__ inline int seg_n(int krange, int target) { return imax(1, (krange + target / 2) / target); }
+// Segment j of n over a range of `krange` split points: offset of its first one and its length.
+__host__ __device__ inline void seg_span(int krange, int n, int j, int *ofs, int *len) {
+    const int base = krange / n, extra = krange % n;
+    *ofs = j * base + imin(j, extra);
+    *len = base + (j < extra ? 1 : 0);
 }
 __host__ __device__ inline int seg_count(int L, int S) { // over all blocks of the level
     const int NB = nblocks_of(L), ubmax = (L - S) / 8;
     int c = 0;
     for (int d = NB - 1; d >= tile_dmin(L, S); --d)
-        for (int ub = 0; ub <= imin(ubmax, NB - 1 - d); ++ub) c += cdiv(tile_krange(L, S, ub, ub + d), kSegK);
+        for (int ub = 0; ub <= imin(ubmax, NB - 1 - d); ++ub) c += seg_n(tile_krange(L, S, ub, ub + d), seg_target(L, S));
     return c;
 }
 // Upper bounds that grow with L, for sizing a workspace that serves every L up to a maximum: the
 // counts of the same plane without the column shift (a shifted plane never has more blocks of a
-// level, nor more segments at S' = 2, where a level's task list is longest).
+// level), with every split range cut at the smallest segment target.
 __host__ __device__ inline int tile_count_bound(int L, int S) {
     const int NB = nblocks_of(L), ubmax = (L - S) / 8;
     int c = 0;
@@ -157,7 +171,7 @@ __host__ __device__ inline int seg_count_bound(int L) {
     int c = 0;
     for (int d = NB - 1; d >= 0; --d)
         for (int ub = 0; ub <= imin(ubmax, NB - 1 - d); ++ub)
-            c += cdiv(imin((ub + d) * 8 + 7, L) - ub * 8 - 2 + 1, kSegK);
+            c += cdiv(imin((ub + d) * 8 + 7, L) - ub * 8 - 2 + 1, kSegMin) + 1;
     return c;
 }
 

@@ -501,7 +501,12 @@ __global__ void __launch_bounds__(256, FB == kFillBatch ? 1 : 4) k_split_key(Tab
     const int mB0 = imax(B_lo, a_g0 - A_hi), mB1 = imin(B_hi, a_g1 - A_lo);
     // this workgroup's segment of the split points of the block
     const int vmax = tile_vmax(L, vb); // last layer position of the block's columns (never beyond L)
-    const int kmin = ub * 8 + s + seg * kSegK, kmax = imin(vmax - r, kmin + kSegK - 1);
+    int kofs, klen;
+    {
+        const int kr = tile_krange(L, Sp, ub, vb);
+        seg_span(kr, seg_n(kr, seg_target(L, Sp)), seg, &kofs, &klen);
+    }
+    const int kmin = ub * 8 + s + kofs, kmax = imin(vmax - r, kmin + klen - 1);
     if (!(mA0 <= mA1 && mB0 <= mB1 && kmin <= kmax)) return; // nothing to merge
     // roles: the left child streams (and the right one is stationary) unless the other way pads less
     const bool y_left = role_cost(mA0, mA1, mB0, mB1, a_g0, a_g1) <= role_cost(mB0, mB1, mA0, mA1, a_g0, a_g1);
@@ -684,17 +689,17 @@ __device__ void seg_tab_body(const Tables &t, int S, int by_row) {
         int tt = 0;
         for (int d = NB - 1; d >= dmin; --d)
             for (int u = 0; u <= imin(ubmax, NB - 1 - d); ++u, ++tt) {
-                const int c = cdiv(tile_krange(L, S, u, u + d), kSegK);
+                const int c = seg_n(tile_krange(L, S, u, u + d), seg_target(L, S));
                 for (int j = 0; j < c; ++j) out[n++] = make_int2(tt, u | ((u + d) << 8) | (j << 16));
             }
         return;
     }
     for (int u = 0; u <= imin(ubmax, NB - 1 - dmin); ++u) {
-        const int cmax = cdiv(tile_krange(L, S, u, NB - 1), kSegK); // the row's longest split range
+        const int cmax = seg_n(tile_krange(L, S, u, NB - 1), seg_target(L, S)); // the row's longest split range
         for (int j = 0; j < cmax; ++j) {
             int tt = u; // index of block (u, u + d) in tile order: the blocks of all larger d come first
             for (int d = NB - 1; d >= dmin; --d) {
-                if (u + d <= NB - 1 && j < cdiv(tile_krange(L, S, u, u + d), kSegK))
+                if (u + d <= NB - 1 && j < seg_n(tile_krange(L, S, u, u + d), seg_target(L, S)))
                     out[n++] = make_int2(tt, u | ((u + d) << 8) | (j << 16));
                 tt += imin(ubmax, NB - 1 - d) + 1;
             }
@@ -1434,7 +1439,7 @@ static Tables make_tables(const oob_plan *h, int lane, const Shape &sh, int *sta
     t.stack = (int *)(ws + h->cv.stack);
     t.flags = (int *)(ws + h->cv.flags);
     t.seg_tab = (int2 *)(ws + h->cv.seg_tab);
-    t.seg_stride = seg_count(sh.L, 2);
+    t.seg_stride = seg_count_bound(sh.L);
     t.status = status;
     return t;
 }
