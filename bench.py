@@ -40,9 +40,9 @@ INT64_OPS_PER_CANDIDATE = 30
 # counter reads for one 256 MiB device-to-device copy), and vector-ALU wave-instructions per call
 # (SQ_INSTS_VALU of k_split_key + k_select).
 PROFILE_CONFIG4 = {"source": "profiles/k_split_key_config4.md",
-                   "hbm_read_bytes_per_call": 21.53e9, "hbm_written_bytes_per_call": 5.72e9,
-                   "valu_wave_insts_per_call": 3.95e9 + 0.09e9,
-                   "kernel_launches_per_call": 308}  # 204 k_split_key + 97 k_select + 7 others (kernel trace)
+                   "hbm_read_bytes_per_call": 19.17e9, "hbm_written_bytes_per_call": 5.90e9,
+                   "valu_wave_insts_per_call": 3.11e9 + 0.07e9,
+                   "kernel_launches_per_call": 277}  # 175 k_split_key + 97 k_select / k_select8 + 5 others (kernel trace)
 
 
 def median(xs):
@@ -537,7 +537,7 @@ def main():
                      "traffic": ((prof4["hbm_read_bytes_per_call"] + prof4["hbm_written_bytes_per_call"]) / launches
                                  if prof4 else None),
                      "traffic_unit": "HBM bytes per level (one launch group), rocprofv3 --pmc",
-                     "kernel": "level kernels S'>=2 (divide/combine, Eq. 1-3): k_split_key + k_select",
+                     "kernel": "level kernels S'>=2 (divide/combine, Eq. 1-3): k_split_key + k_select / k_select8",
                      "ops_per_candidate": FP64_OPS_PER_CANDIDATE, "launches": launches,
                      "avg_launch_ms": lvl_ms / launches, "levels_ms_per_step": lvl_ms,
                      "candidates_per_s": cands / (lvl_ms * 1e-3),

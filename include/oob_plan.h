@@ -124,7 +124,10 @@ int oob_plan_create(oob_plan **h, int max_L, int max_nodes, int max_gpus_per_nod
  *   mem_cap       bytes per GPU
  *   f             fault-tolerance threshold
  *   stream        hipStream_t (NULL = default stream)
- * Enqueues one launch per stage-count level plus set-up, extraction and coverage kernels. */
+ * Enqueues, per stage-count level, the split kernel (once or twice: the inner splits of consecutive
+ * levels run on two streams of the library beside `stream`, see OOB_OPT_ONE_STREAM) and the select
+ * kernel, plus one launch before level 1 (set-up), level 1, and three after the last level
+ * (stage counts, stages, coverage). */
 int oob_plan_templates(oob_plan *h, const oob_profile *profile, int L, int n_min, int n_max,
                        int gpus_per_node, int microbatches, int64_t mem_cap, int f,
                        oob_templates *out, void *stream);

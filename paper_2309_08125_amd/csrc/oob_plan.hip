@@ -18,16 +18,16 @@
 // loop needs only (T, T1, tmax) per child: 2 adds, 1 compare, 2 selects, 1 min per candidate.
 // T3 and k* are carried per state for the output only.
 //
-// One level S' = two kernels.
-//   k_split  grid (block of the (u,v) plane) x (split s) x (group of target device sets).
-//            A workgroup stages, per chunk of k, the left-child records of every m it needs
-//            and the right-child records of every m' in LDS, pre-combined with cl / cr; each
-//            wave owns 8 target device sets x an 8 x 8 block of (u, v) (one state per lane and
-//            set) and walks k ascending, all m per k, keeping only the running minimum and,
-//            per state, the first k that reached it.  Result: per (s, state) the minimum over
-//            (k, m) and that k.
-//   k_select per state: first s with the smallest partial minimum, then the first m at that
+// One level S' = split kernels, then a select kernel.
+//   k_split_key  per (block of the (u,v) plane, segment of its split points k, split s, group of
+//            target device sets): the minimum over (k, m) of Eq. 1-3 per state as a key
+//            total * 2^kbits + k, merged into the level's key array (described at the kernel).
+//            k_split is the variant without keys for shapes beyond its LDS classes.
+//   k_select / k_select8  per state: first s with the smallest key, then the first m at that
 //            (s, k) whose candidate equals it -- the smallest (T, s, k, m) -- and the record.
+// Before level 1 one launch (k_prepare) scans and validates the profile, lays out the tables, lists the
+// tasks of every level and clears the keys; after the last level k_pick chooses the stage count of
+// every template size, k_backtrack expands the stages, k_coverage does Section 4.1.1's node specification.
 #include <hip/hip_runtime.h>
 
 #include <mutex>
@@ -88,11 +88,11 @@ __device__ __forceinline__ long long rec_block(const Tables &t, int S, int delta
 
 // ---------------------------------------------------------------------------------------
 // Set-up: prefix sums (Eq. 4's sums become differences), input validation, level offsets.
-// One workgroup of 16 waves: a wave scans the profile row of d GPUs, 64 entries at a time (sums
+// One workgroup of four waves: two of them scan the profile rows of d GPUs, 64 entries at a time (sums
 // saturate, so that no input can overflow them; a saturated sum is reported, not used); one wave
 // scans the bytes and the boundary terms, one lays out the levels.
 // ---------------------------------------------------------------------------------------
-constexpr int kSetupThreads = 1024;
+constexpr int kSetupThreads = 256; // a larger workgroup waits long for a place on a GPU that other jobs of a batch keep busy
 
 // Inclusive scan over the lanes of min(a + b, cap) for values in [0, cap], cap <= 2^62.
 __device__ __forceinline__ unsigned long long scan_sat(unsigned long long x, unsigned long long cap, int lane) {
@@ -388,7 +388,7 @@ constexpr int kKeyTargets = 64;
 constexpr int kFillBatch = 3;      // records a thread has in flight while staging: three waves per SIMD
 constexpr int kFillBatchSmall = 2; // the same for launches whose LDS admits four workgroups per compute unit
 
-// Workgroup x of a launch of n -> position in the task list (OOB_TUNE_XCD=1 only).  The hardware
+// Workgroup x of a launch of n -> position in the task list (handle option OOB_OPT_XCD_ORDER only).  The hardware
 // deals consecutive workgroups out to the 8 XCDs in turn; this hands every XCD one contiguous
 // stretch of the list instead (workgroups x, x + 8, x + 16, ... walk it in order), so that tasks
 // that share records meet in one L2.  A bijection on 0..n-1 for any n.  Measured on the headline
@@ -473,8 +473,9 @@ __host__ __device__ __forceinline__ int role_cost(int y0, int y1, int q0, int q1
 template <int NTAB, int NBUF, int FB>
 __global__ void __launch_bounds__(256, FB == kFillBatch ? 1 : 4) k_split_key(Tables t, int Sp, int fam0, int gz, int NT, int NAall, int halves,
                                                    int s0, int sstep) {
-    // Static, separate arrays: the compiler then knows that the key merges (atomics on s_acc) never
-    // touch the staged records, and keeps the reads of the next step ahead of them.
+    // Separate arrays (the staged records static, the key table the launch's dynamic LDS, sized by
+    // its target count): the compiler then knows that the key merges (atomics on s_acc) never touch
+    // the staged records, and keeps the reads of the next step ahead of them.
     __shared__ double2 s_pair[NBUF][NTAB * 8]; // [buffer][staging order]: pre-combined pairs
     __shared__ double s_tm[NBUF][NTAB * 8];    // tmax (negated when the right child streams)
     HIP_DYNAMIC_SHARED(unsigned long long, s_acc)       // [(na + 2) * 64] keys, rows 1..na (sized by the launch)
@@ -677,7 +678,7 @@ __global__ void __launch_bounds__(256, FB == kFillBatch ? 1 : 4) k_split_key(Tab
 
 // Per level: the list of (block, segment) workgroup tasks, written once per call.
 // by_row = 0 (default): blocks by decreasing distance from the diagonal, the longest split ranges
-// first.  by_row = 1 (OOB_TUNE_XCD=1, used together with xcd_chunked): block row ub, then segment,
+// first.  by_row = 1 (handle option OOB_OPT_XCD_ORDER, used together with xcd_chunked): block row ub, then segment,
 // then the blocks of that row from the far end, so that neighbours in the list split at the same
 // points k and stage the same left-child records.
 __device__ void seg_tab_body(const Tables &t, int S, int by_row) {
@@ -1286,7 +1287,7 @@ bool plan_split_key(const Shape &sh, int Sp, int fam, int xcd_order, SplitPlan *
     p->pc = (kKeyHalves & 3) | (kKeyPack ? 4 : 0) | (xcd_order ? 8 : 0); // bits 0-1: cut left-over items; bit 2: several items per wave near the range ends; bit 3: XCD-chunked task order
     p->ntab = ntab;
     p->na = imin(cnt, kKeyTargets);
-    p->lds = 0; // static LDS: see the capacity classes at the launch site
+    p->lds = 0; // staged records in static LDS by capacity class, key table in dynamic LDS: see the launch site
     p->waves = kKeyWaves;
     return true;
 }
