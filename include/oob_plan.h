@@ -174,6 +174,13 @@ int oob_plan_destroy(oob_plan *h);
 #define OOB_OPT_FUSE_FROM 5
 int oob_plan_set_option(oob_plan *h, int option, int value);
 
+/* Test hook, host only (no GPU is touched): checks the table layout and the per-level task lists the
+ * library would use for L layers -- every state in exactly one block of its level and at a record of
+ * its own, the split-point segments of a block a partition of its range, all counts within the
+ * bounds that size a workspace.  Returns 0, a positive number naming the first check that failed,
+ * or OOB_EINVAL for L outside 1..OOB_MAX_L. */
+int oob_plan_layout_selftest(int L);
+
 /* Measurement hook.  After oob_plan_level_timing(h, 1) every oob_plan_templates call records
  * two HIP events of the handle on its stream, one before the first and one after the last
  * launch of the levels S' >= 2 (the divide/combine step, Eq. 1-3).  oob_plan_last_level_ms

@@ -2,7 +2,7 @@
 from .binding import (  # noqa: F401
     OOB_ECAPACITY, OOB_EHIP, OOB_EINVAL, OOB_EOVERFLOW, OOB_FORBIDDEN, OOB_OK, SYMBOLS,
     DeviceProfile, DeviceTemplates, Planner, load, oob_plan_create, oob_plan_destroy,
-    oob_plan_max_stages, oob_plan_templates, oob_plan_templates_batch, oob_plan_workspace_size,
+    oob_plan_layout_selftest, oob_plan_max_stages, oob_plan_templates, oob_plan_templates_batch, oob_plan_workspace_size,
     template_stages, OOB_OPT_PLAIN_SPLIT, OOB_OPT_XCD_ORDER, OOB_OPT_ONE_STREAM,
     OOB_OPT_SELECT8_FROM, OOB_OPT_FUSE_FROM,
     EXACT_SYMBOLS, ExactMinimum, oob_exact_minimum, oob_exact_workspace_size,

@@ -21,7 +21,7 @@ _ERR = {OOB_EINVAL: "OOB_EINVAL", OOB_ECAPACITY: "OOB_ECAPACITY", OOB_EOVERFLOW:
 SYMBOLS = ["oob_plan_max_stages", "oob_plan_workspace_size", "oob_plan_create",
            "oob_plan_templates", "oob_plan_templates_batch", "oob_plan_destroy", "oob_plan_export_block",
            "oob_plan_level_timing", "oob_plan_last_level_ms", "oob_plan_export_flags", "oob_plan_valu_peak", "oob_plan_valu_peak_f64",
-           "oob_plan_set_option"]
+           "oob_plan_set_option", "oob_plan_layout_selftest"]
 OOB_OPT_PLAIN_SPLIT, OOB_OPT_XCD_ORDER, OOB_OPT_ONE_STREAM = 1, 2, 3
 OOB_OPT_SELECT8_FROM, OOB_OPT_FUSE_FROM = 4, 5
 INST_SYMBOLS = ["oob_inst_workspace_size", "oob_inst_count", "oob_inst_enumerate", "oob_inst_keep_wide_table",
@@ -61,6 +61,8 @@ def load():
         L = C.CDLL(LIB_PATH)
         L.oob_plan_max_stages.argtypes = [C.c_int] * 4
         L.oob_plan_max_stages.restype = C.c_int
+        L.oob_plan_layout_selftest.argtypes = [C.c_int]
+        L.oob_plan_layout_selftest.restype = C.c_int
         L.oob_plan_workspace_size.argtypes = [C.c_int] * 3
         L.oob_plan_workspace_size.restype = C.c_size_t
         L.oob_plan_create.argtypes = [C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_int, C.c_void_p,
@@ -135,6 +137,10 @@ def check(rc: int, what: str):
 # ---- the C entry points under their own names (thin wrappers) ----------------------------
 def oob_plan_max_stages(L, n_max, gpus_per_node, microbatches) -> int:
     return load().oob_plan_max_stages(L, n_max, gpus_per_node, microbatches)
+
+
+def oob_plan_layout_selftest(L) -> int:
+    return load().oob_plan_layout_selftest(L)
 
 
 def oob_plan_workspace_size(max_L, max_nodes, max_gpus_per_node) -> int:

@@ -1781,6 +1781,62 @@ __global__ void __launch_bounds__(256) k_valu_peak_f64(double *sink, int iters, 
     if (r == 12345.678) sink[0] = r; // keeps the chains alive; practically never taken
 }
 
+// Host-side check of the table layout and the task lists for L layers (no GPU involved): every state
+// (S', u, v) lies in exactly one enumerated block of its level and at a record of its own, every
+// enumerated block holds a state, the segments of a block partition its split range into parts of at
+// least one split point, and the counts stay within the bounds that size a workspace.
+extern "C" int oob_plan_layout_selftest(int L) {
+    if (L < 1 || L > OOB_MAX_L) return OOB_EINVAL;
+    const int NB = nblocks_of(L), c = col_shift(L), recs = tri_blocks(NB) * 64;
+    if ((L + c + 1) % 8 != 0 || (L + c) / 8 != NB - 1) return 1;
+    std::vector<int> owner((size_t)(L + 1) * (L + 1));
+    std::vector<char> used(recs);
+    for (int u = 0; u <= L; ++u) // records of distinct (u, v) are distinct and inside the table
+        for (int v = u; v <= L; ++v) {
+            const int o = rec_off(u, v, c, NB);
+            if (o < 0 || o >= recs || used[o]) return 2;
+            used[o] = 1;
+        }
+    for (int S = 1; S <= L; ++S) {
+        std::fill(owner.begin(), owner.end(), -1);
+        const int nt = tile_count(L, S);
+        if (nt > tile_count_bound(L, S)) return 3;
+        int segs = 0;
+        for (int t = 0; t < nt; ++t) {
+            int ub, vb;
+            tile_decode(L, S, t, &ub, &vb);
+            if (ub < 0 || vb < ub || vb >= NB) return 4;
+            const int kr = tile_krange(L, S, ub, vb);
+            if (kr < 1 || tile_vmax(L, vb) > L) return 5;
+            const int n = seg_n(kr, seg_target(L, S));
+            int next = 0;
+            for (int j = 0; j < n; ++j) {
+                int ofs, len;
+                seg_span(kr, n, j, &ofs, &len);
+                if (ofs != next || len < 1) return 6;
+                next = ofs + len;
+            }
+            if (next != kr) return 6;
+            segs += n;
+            int states = 0;
+            for (int u = ub * 8; u < ub * 8 + 8; ++u)
+                for (int v = vb * 8 - c; v <= vb * 8 + 7 - c; ++v) {
+                    if (u >= L || v < 0 || v > L || v - u < S) continue;
+                    if (owner[(size_t)u * (L + 1) + v] != -1) return 7;
+                    owner[(size_t)u * (L + 1) + v] = t;
+                    if (rec_off(u, v, c, NB) != tri_index(ub, vb, NB) * 64 + ((u - ub * 8) << 3) + (v + c - vb * 8)) return 8;
+                    ++states;
+                }
+            if (states == 0) return 9;
+        }
+        for (int u = 0; u < L; ++u)
+            for (int v = u + S; v <= L; ++v)
+                if (owner[(size_t)u * (L + 1) + v] < 0) return 10;
+        if (S >= 2 && (segs != seg_count(L, S) || segs > seg_count_bound(L))) return 11;
+    }
+    return 0;
+}
+
 // Copies flags[0..3] of the last call to a device array (tests: which split kernel ran).
 __global__ void k_export_flags(const int *flags, int *dst) {
     if (threadIdx.x < 4) dst[threadIdx.x] = flags[threadIdx.x];

@@ -159,3 +159,18 @@ def test_create_and_call_reject_bad_arguments_without_touching_the_gpu():
     assert call() == P.OOB_EINVAL  # null output pointer
     assert P.load().oob_plan_export_block(h, 1, 0, 1, 1, 1, 1, 1, 1, None) == P.OOB_EINVAL  # no call yet
     assert P.oob_plan_destroy(h) == P.OOB_OK
+
+
+def test_table_layout_and_task_lists_for_every_depth():
+    """Host side of the table layout (block columns shifted so that v = L ends a block) and of the
+    per-level task lists (split ranges cut into segments of equal length): for every depth up to 160
+    layers and a few beyond, every state of every level lies in exactly one enumerated block and at
+    a record of its own, every enumerated block holds a state, the segments of a block partition
+    its split range, and the counts stay within the bounds that size a handle's workspace."""
+    for L in list(range(1, 161)) + [255, 256, 257, 383]:
+        assert P.oob_plan_layout_selftest(L) == 0, L
+    assert P.oob_plan_layout_selftest(0) == P.OOB_EINVAL
+    assert P.oob_plan_layout_selftest(1 << 20) == P.OOB_EINVAL
+    # a workspace sized for a depth serves every smaller depth: sizes grow with every maximum
+    sizes = [P.oob_plan_workspace_size(L, 16, 4) for L in range(8, 140)]
+    assert all(a <= b for a, b in zip(sizes, sizes[1:]))
