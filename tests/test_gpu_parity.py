@@ -325,9 +325,10 @@ def test_select_with_eight_lanes_per_state(P):
     """The select kernel of the top levels (eight lanes per state), forced onto every level of
     shapes the oracle finishes in seconds: once reading the keys of all splits, once evaluating
     the two outer splits of every level itself (both device-set families, both N_b modes, a
-    profile whose totals are too large for keys, so that its one-lane fallback runs too)."""
+    profile whose totals are too large for keys, so that its one-lane fallback runs too), the
+    latter also with every launch on one stream."""
     seen = set()
-    for fuse_from in (1 << 20, 2):
+    for fuse_from, one_stream in ((1 << 20, 0), (2, 0), (2, 1)):
         for inp in (inputs.config(1), inputs.config(2),
                     inputs.random_small(3, 37, 3, 1, 5, 9, f=1, tight_mem=True),
                     inputs.random_small(5, 60, 2, 1, 6, 11, f=2),
@@ -338,6 +339,7 @@ def test_select_with_eight_lanes_per_state(P):
             planner = P.Planner(inp.L, inp.n_max, inp.gpus_per_node)
             planner.set_option(P.OOB_OPT_SELECT8_FROM, 2)
             planner.set_option(P.OOB_OPT_FUSE_FROM, fuse_from)
+            planner.set_option(P.OOB_OPT_ONE_STREAM, one_stream)
             full_check(P, planner, inp)
             seen.add(tuple(planner.flags()[:2]))
             planner.close()
