@@ -135,10 +135,10 @@ __host__ __device__ inline int tile_vmax(int L, int vb) { return vb * 8 + 7 - co
 // the target gives, rounded to the nearest (at least one), all of the same length up to one
 // split point -- so no workgroup is left with a stub of one or two split points, which would pay
 // the whole set-up and the merge of its keys for next to nothing.
-constexpr int kSegTarget = 8, kSegTargetTop = 4, kSegTopLayers = 20; // measured on the headline workload
-constexpr int kSegMin = 4; // no target below this (sizes the task lists)
+constexpr int kSegTarget = 8, kSegTargetTop = 3, kSegTopLayers = 28; // measured on the headline workload
+constexpr int kSegMin = 3; // no target below this (sizes the task lists)
 // The top levels (fewer than kSegTopLayers layers of slack, a handful of blocks) cannot fill the
-// machine with workgroups of eight split points: there the target is four.
+// machine with workgroups of eight split points: there the target is three.
 __host__ __device__ inline int seg_target(int L, int S) { return L - S < kSegTopLayers ? kSegTargetTop : kSegTarget; }
 __host__ __device__ inline int tile_krange(int L, int S, int ub, int vb) {
     return tile_vmax(L, vb) - ub * 8 - S + 1;
