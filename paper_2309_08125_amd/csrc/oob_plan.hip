@@ -451,6 +451,12 @@ __device__ __forceinline__ void stage_store(const Stage &g, double2 *pair, doubl
     tm[e] = g.y_is_left ? rc.tm : -rc.tm;
 }
 
+// floor(x / d) for 0 <= x < 10000 and 1 <= d <= 4 without the division sequence (x 21846 >> 16 is
+// exact for thirds in that range).
+__device__ __forceinline__ int div_small(int x, int d) {
+    return d == 1 ? x : d == 2 ? x >> 1 : d == 4 ? x >> 2 : (x * 21846) >> 16;
+}
+
 // Candidate slots an assignment of roles executes: per block of eight stationary unit counts the
 // streaming range that pairs with it (targets a0..a1), times eight.
 __host__ __device__ __forceinline__ int role_cost(int y0, int y1, int q0, int q1, int a0, int a1) {
@@ -562,27 +568,29 @@ __global__ void __launch_bounds__(256, FB == kFillBatch ? 1 : 4) k_split_key(Tab
         const int jr = k - (ub * 8 + s), jc = vmax - r - k;
         const int nr = imin(jr, 7) + 1, nc = imin(jc, chi) + 1;
         const int lr = nr <= 1 ? 0 : nr <= 2 ? 1 : nr <= 4 ? 2 : 3, lc = nc <= 1 ? 0 : nc <= 2 ? 1 : nc <= 4 ? 2 : 3;
-        int R, slot, ue, ve; // items side by side, this lane's item among them, its row and column
+        int R, lgR, slot, ue, ve; // items side by side (and its binary logarithm), this lane's item among them, its row and column
         if (lr <= lc) {      // rows 0..2^lr-1, all columns
-            R = 8 >> lr; slot = lane >> (3 + lr); ue = (lane >> 3) & ((1 << lr) - 1); ve = lane & 7;
+            R = 8 >> lr; lgR = 3 - lr; slot = lane >> (3 + lr); ue = (lane >> 3) & ((1 << lr) - 1); ve = lane & 7;
         } else {             // all rows, the last 2^lc columns that exist
-            R = 8 >> lc; slot = lane >> (3 + lc);
+            R = 8 >> lc; lgR = 3 - lc; slot = lane >> (3 + lc);
             const int w = lane & ((8 << lc) - 1);
             ue = w >> lc; ve = imax(0, chi - (1 << lc) + 1) + (w & ((1 << lc) - 1));
         }
         // The items of the pass, with (PACK) or without several of them side by side in a wave; the
         // plain variant keeps the item's block, row offset and key column in scalar registers.
-        auto run_items = [&](auto pack_c, const int R, const int slot, const int ue, const int ve) {
+        auto run_items = [&](auto pack_c, const int R, const int lgR, const int slot, const int ue, const int ve) {
         constexpr bool PACK = decltype(pack_c)::value;
         const int yl = y_left ? ue : ve, ql = y_left ? ve : ue; // lane index of a streaming / stationary record
         const int col = PACK ? ue * 8 + ve : lane;              // this lane's state: its column of the key table
-        const int nsup = cdiv(nmb, R);
-        const int rem = nsup % nw, full = nsup - rem;
-        const int parts = ((halves & 3) && rem) ? imax(1, nw / rem) : 1;
+        // (R is a power of two, a workgroup has at most four waves: no integer division below)
+        const int nsup = (nmb + R - 1) >> lgR;
+        const int rem = nsup - div_small(nsup, nw) * nw, full = nsup - rem;
+        const int parts = ((halves & 3) && rem) ? (rem == 1 ? nw : (nw == 4 && rem == 2) ? 2 : 1) : 1;
         const int nitems = full + rem * parts;
         for (int item = wave; item < nitems; item += nw) {
             const int cut = item >= full, jj = item - full;
-            const int sb = cut ? full + jj / parts : item, part = cut ? jj % parts : 0, np = cut ? parts : 1;
+            const int jq = div_small(jj, parts);
+            const int sb = cut ? full + jq : item, part = cut ? jj - jq * parts : 0, np = cut ? parts : 1;
             // stationary blocks sb R .. sb R + R - 1 (those that exist); this lane's is mb
             const int mb_first = sb * R, mb_last = imin(mb_first + R - 1, nmb - 1);
             // a lane without a block of its own repeats the last block's work for its state: the same
@@ -594,8 +602,8 @@ __global__ void __launch_bounds__(256, FB == kFillBatch ? 1 : 4) k_split_key(Tab
             // group; a lane's surplus steps fall on targets outside the group and are swallowed
             int mlo = imax(yM0, a_g0 - (qM0 + 8 * mb_last + 7)), mhi = imin(yM1, a_g1 - (qM0 + 8 * mb_first));
             if (np > 1 && mlo <= mhi) { // piece `part` of `np` of that range
-                const int len = mhi - mlo + 1, lo = mlo + len * part / np;
-                mhi = mlo + len * (part + 1) / np - 1;
+                const int len = mhi - mlo + 1, lo = mlo + div_small(len * part, np);
+                mhi = mlo + div_small(len * (part + 1), np) - 1;
                 mlo = lo;
             }
             if (mlo > mhi) continue;
@@ -654,8 +662,8 @@ __global__ void __launch_bounds__(256, FB == kFillBatch ? 1 : 4) k_split_key(Tab
             }
         }
         };
-        if (R > 1 && nmb > 1 && (halves & 4)) run_items(std::true_type{}, R, slot, ue, ve);
-        else run_items(std::false_type{}, 1, 0, lane >> 3, lane & 7);
+        if (R > 1 && nmb > 1 && (halves & 4)) run_items(std::true_type{}, R, lgR, slot, ue, ve);
+        else run_items(std::false_type{}, 1, 0, 0, lane >> 3, lane & 7);
         if (NBUF == 1) __syncthreads(); // one buffer: everybody is done reading it before it is refilled
         if (k < kmax) {
 #pragma unroll
