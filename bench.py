@@ -40,8 +40,8 @@ INT64_OPS_PER_CANDIDATE = 30
 # counter reads for one 256 MiB device-to-device copy), and vector-ALU wave-instructions per call
 # (SQ_INSTS_VALU of k_split_key + k_select).
 PROFILE_CONFIG4 = {"source": "profiles/k_split_key_config4.md",
-                   "hbm_read_bytes_per_call": 19.17e9, "hbm_written_bytes_per_call": 5.90e9,
-                   "valu_wave_insts_per_call": 3.11e9 + 0.07e9,
+                   "hbm_read_bytes_per_call": 19.29e9, "hbm_written_bytes_per_call": 6.27e9,
+                   "valu_wave_insts_per_call": 3.06e9 + 0.07e9,
                    "kernel_launches_per_call": 277}  # 175 k_split_key + 97 k_select / k_select8 + 5 others (kernel trace)
 
 
